@@ -1,0 +1,219 @@
+"""Token table of a serial-parallel decoded sequence, grown by replaying appends.
+
+TEST INFRASTRUCTURE (see oracle/__init__.py).  Plain Python and numpy.
+
+Follows ASPD Sec. 3.2 "Preliminaries" and Eq. 2-4.  A sequence is a succession of
+stages; a serial stage has one main branch, a parallel stage has K parallel
+branches.  Every token carries (stage, branch, index within its branch, position
+id).  One KV cache per sequence is reused throughout (abstract, Sec. 2.3): a token's
+logical slot is its index in the order the tokens were appended, and a merge moves
+nothing.
+
+Readings of the paper taken here (each is also listed in the design notes):
+  * Position ids are 0-based: Eq. 4 minus one throughout (rotary encodings only see
+    differences).
+  * Eq. 4, main branch: position = number of tokens of all earlier timesteps, i.e.
+    the count of tokens already in the sequence ("absolute positions in the
+    flattened sequence").
+  * Eq. 4, parallel branch: stage_start = position the first token of every branch
+    takes = number of tokens before the stage; Delta = 0-based index of the token
+    within its own branch ("shared position encodings at each timestamp").
+  * Eq. 2 is read with self-visibility: visible iff S = 1 and (pos(i) > pos(j) or
+    i = j); a strict test alone would leave the first token's row empty.
+  * One append call lays its new tokens at the tail ordered by (branch index, token
+    index).  A one-token-per-branch step therefore interleaves branches (the
+    inference arrangement of Fig. 5) and a multi-token call lays each branch's chunk
+    contiguously (the teacher-forcing arrangement of Fig. 5).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+MAIN = 0  # branch id of the main branch; parallel branches are 1..K within their stage
+
+
+@dataclass
+class StepMeta:
+    """What one append call hands to the attention call that follows it."""
+
+    cu_new: np.ndarray         # [NB+1] (parallel) or [B+1] (serial): first packed row of each branch / sequence
+    cu_seq_new: np.ndarray     # [B+1]  first packed row of each sequence
+    q_seq: np.ndarray          # [NQ]   sequence of each new token
+    q_branch: np.ndarray       # [NQ]   global branch index (parallel) or -1 (serial)
+    position_ids: np.ndarray   # [NQ]   Eq. 4, 0-based
+    logical_slot: np.ndarray   # [NQ]   index of the token in its sequence's cache
+    slot_mapping: np.ndarray   # [NQ]   int64 physical slot through the block table
+    kv_len: np.ndarray         # [NQ]   number of keys the token attends to, itself included
+
+    @property
+    def NQ(self) -> int:
+        return int(self.q_seq.shape[0])
+
+
+class TokenTable:
+    def __init__(self, block_tables: np.ndarray, block_size: int):
+        self.block_tables = np.asarray(block_tables)
+        self.block_size = int(block_size)
+        self.B = int(self.block_tables.shape[0])
+        # per sequence, per logical slot
+        self.stage = [[] for _ in range(self.B)]
+        self.branch = [[] for _ in range(self.B)]
+        self.index_in_branch = [[] for _ in range(self.B)]
+        self.pos = [[] for _ in range(self.B)]
+        # stage bookkeeping
+        self.cur_stage = [0] * self.B            # stage number of the stage now being decoded
+        self.cur_parallel = [False] * self.B
+        self.stage_first_slot = [0] * self.B     # slot of the first token of the current stage
+        self.stage_start_pos = [0] * self.B      # Eq. 4 stage_start of the current parallel stage
+        self.tokens_in_branch = [[] for _ in range(self.B)]   # per branch of the current parallel stage
+        self.main_count = [0] * self.B
+
+    # ------------------------------------------------------------------ appends
+    def _push(self, s: int, branch: int, t: int, pos: int) -> int:
+        slot = len(self.pos[s])
+        self.stage[s].append(self.cur_stage[s])
+        self.branch[s].append(branch)
+        self.index_in_branch[s].append(t)
+        self.pos[s].append(pos)
+        return slot
+
+    def append_serial(self, new_len) -> StepMeta:
+        """Main-branch tokens: new_len[s] of them for sequence s (Eq. 4 case 1)."""
+        new_len = np.asarray(new_len)
+        assert new_len.shape == (self.B,)
+        rows = []
+        for s in range(self.B):
+            assert not self.cur_parallel[s], "merge before appending main tokens"
+            for _ in range(int(new_len[s])):
+                pos = len(self.pos[s])               # tokens decoded before this one, all branches included
+                slot = self._push(s, MAIN, self.main_count[s], pos)
+                self.main_count[s] += 1
+                rows.append((s, -1, slot))
+        cu_new = np.zeros(self.B + 1, dtype=np.int32)
+        np.cumsum(new_len, out=cu_new[1:])
+        return self._step_meta(rows, cu_new)
+
+    def open_parallel(self, num_branches) -> None:
+        """Start a parallel stage with num_branches[s] branches (0 leaves the sequence serial)."""
+        num_branches = np.asarray(num_branches)
+        assert num_branches.shape == (self.B,)
+        for s in range(self.B):
+            if int(num_branches[s]) == 0:
+                self.tokens_in_branch[s] = []
+                continue
+            assert not self.cur_parallel[s]
+            self.cur_stage[s] += 1
+            self.cur_parallel[s] = True
+            self.stage_first_slot[s] = len(self.pos[s])
+            self.stage_start_pos[s] = len(self.pos[s])   # number of tokens before the stage
+            self.tokens_in_branch[s] = [0] * int(num_branches[s])
+
+    def append_parallel(self, new_len) -> StepMeta:
+        """new_len[b] tokens for every branch b (global index over the batch), Eq. 4 case 2."""
+        new_len = np.asarray(new_len)
+        rows = []
+        g = 0
+        for s in range(self.B):
+            for k in range(len(self.tokens_in_branch[s])):       # branch index ascending
+                for _ in range(int(new_len[g])):                 # token index ascending
+                    t = self.tokens_in_branch[s][k]
+                    pos = self.stage_start_pos[s] + t
+                    slot = self._push(s, k + 1, t, pos)
+                    self.tokens_in_branch[s][k] = t + 1
+                    rows.append((s, g, slot))
+                g += 1
+        assert g == new_len.shape[0]
+        cu_new = np.zeros(g + 1, dtype=np.int32)
+        np.cumsum(new_len, out=cu_new[1:])
+        return self._step_meta(rows, cu_new)
+
+    def merge(self) -> None:
+        """All branches done: back to one main branch.  Nothing in the cache moves."""
+        for s in range(self.B):
+            if self.cur_parallel[s]:
+                self.cur_parallel[s] = False
+                self.cur_stage[s] += 1
+                self.tokens_in_branch[s] = []
+                self.stage_first_slot[s] = len(self.pos[s])
+
+    # ------------------------------------------------------------------ views
+    def seq_len(self) -> np.ndarray:
+        return np.array([len(p) for p in self.pos], dtype=np.int32)
+
+    def stage_base(self) -> np.ndarray:
+        """Number of leading slots that every current query may see: the first slot of the
+        running parallel stage, or everything when the sequence is serial."""
+        return np.array([self.stage_first_slot[s] if self.cur_parallel[s] else len(self.pos[s])
+                         for s in range(self.B)], dtype=np.int32)
+
+    def branch_len(self) -> np.ndarray:
+        out = [n for s in range(self.B) for n in self.tokens_in_branch[s]]
+        return np.array(out, dtype=np.int32)
+
+    def slot_owner(self, stride: int) -> np.ndarray:
+        """[B][stride] uint8: branch id (1..K) of every slot of the running parallel stage, 0 elsewhere."""
+        out = np.zeros((self.B, stride), dtype=np.uint8)
+        for s in range(self.B):
+            if self.cur_parallel[s]:
+                for slot in range(self.stage_first_slot[s], len(self.pos[s])):
+                    out[s, slot] = self.branch[s][slot]
+        return out
+
+    def physical_slot(self, s: int, slot: int) -> int:
+        blk = int(self.block_tables[s, slot // self.block_size])
+        assert blk >= 0, "sequence outgrew its block table"
+        return blk * self.block_size + slot % self.block_size
+
+    def physical_slots(self, s: int) -> np.ndarray:
+        return np.array([self.physical_slot(s, j) for j in range(len(self.pos[s]))], dtype=np.int64)
+
+    # ------------------------------------------------------------------ mask (Eq. 2-3)
+    def visible_pair(self, s: int, i: int, j: int) -> bool:
+        """Eq. 2 with Eq. 3, for query slot i and key slot j of sequence s, one pair at a time."""
+        bi, bj = self.branch[s][i], self.branch[s][j]
+        si, sj = self.stage[s][i], self.stage[s][j]
+        if bi == MAIN:                       # Eq. 3 case 1: the main branch sees every branch
+            S = 1
+        elif si == sj and bi == bj:          # case 2: same parallel branch
+            S = 1
+        elif si != sj:                       # case 3: different stage
+            S = 1
+        else:
+            S = 0
+        return S == 1 and (self.pos[s][i] > self.pos[s][j] or i == j)
+
+    def dense_mask(self, s: int, query_slots) -> np.ndarray:
+        """bool [len(query_slots)][T_s]: the same rule as visible_pair, on whole arrays."""
+        q = np.asarray(query_slots, dtype=np.int64)
+        stage = np.asarray(self.stage[s], dtype=np.int64)
+        branch = np.asarray(self.branch[s], dtype=np.int64)
+        pos = np.asarray(self.pos[s], dtype=np.int64)
+        slots = np.arange(len(pos), dtype=np.int64)
+        q_main = (branch[q] == MAIN)[:, None]
+        same_stage = stage[q][:, None] == stage[None, :]
+        same_branch = branch[q][:, None] == branch[None, :]
+        S = q_main | (same_stage & same_branch) | ~same_stage
+        before = pos[q][:, None] > pos[None, :]
+        itself = q[:, None] == slots[None, :]
+        return S & (before | itself)
+
+    # ------------------------------------------------------------------ internals
+    def _step_meta(self, rows, cu_new) -> StepMeta:
+        nq = len(rows)
+        q_seq = np.array([r[0] for r in rows], dtype=np.int32).reshape(nq)
+        q_branch = np.array([r[1] for r in rows], dtype=np.int32).reshape(nq)
+        slot = np.array([r[2] for r in rows], dtype=np.int32).reshape(nq)
+        position_ids = np.array([self.pos[s][j] for s, _, j in rows], dtype=np.int32).reshape(nq)
+        slot_mapping = np.array([self.physical_slot(s, j) for s, _, j in rows], dtype=np.int64).reshape(nq)
+        kv_len = np.zeros(nq, dtype=np.int32)
+        cu_seq_new = np.zeros(self.B + 1, dtype=np.int32)
+        for s in range(self.B):
+            idx = np.nonzero(q_seq == s)[0]
+            cu_seq_new[s + 1] = cu_seq_new[s] + idx.size
+            if idx.size:
+                kv_len[idx] = self.dense_mask(s, slot[idx]).sum(axis=1)
+        return StepMeta(cu_new=cu_new, cu_seq_new=cu_seq_new, q_seq=q_seq, q_branch=q_branch,
+                        position_ids=position_ids, logical_slot=slot, slot_mapping=slot_mapping,
+                        kv_len=kv_len)

@@ -1,0 +1,265 @@
+"""Pins for the oracle's token table: position ids (Eq. 4), cache slots, mask (Eq. 2-3).
+
+None of these re-types the oracle's own formula: they use the hand-derived fixture, an
+independently written visible-set enumeration, closed forms and invariants."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import aspd_workloads as W
+from oracle import TokenTable, MAIN
+from oracle_drive import table_at, table_with_prefix
+
+
+# ----------------------------------------------------------------------------- fixture
+def _parse_examples(path):
+    examples, cur = {}, None
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        w = line.split()
+        if w[0] == "example":
+            cur = {"history": [], "slots": []}
+            examples[w[1]] = cur
+        elif w[0] == "history":
+            cur["history"].append((w[1], [int(x) for x in w[2:]]))
+        elif w[0] == "slot":
+            i = w.index(":")
+            slot, branch, stage, pos = (int(x) for x in w[1:i])
+            cur["slots"].append((slot, branch, stage, pos, {int(x) for x in w[i + 1:]}))
+    return examples
+
+
+def _replay(history, blocks=8):
+    tt = TokenTable(np.arange(blocks, dtype=np.int32)[None, :], 16)
+    metas = []
+    for op, args in history:
+        if op == "serial":
+            metas.append(tt.append_serial([args[0]]))
+        elif op == "open":
+            tt.open_parallel([args[0]])
+        elif op == "step":
+            metas.append(tt.append_parallel(args))
+        elif op == "merge":
+            tt.merge()
+    return tt, metas
+
+
+@pytest.mark.parametrize("name", ["two_branches_then_merge", "two_rounds", "chunk_then_step"])
+def test_worked_examples(golden_dir, name):
+    ex = _parse_examples(os.path.join(golden_dir, "worked_examples.txt"))[name]
+    tt, metas = _replay(ex["history"])
+    T = len(ex["slots"])
+    assert len(tt.pos[0]) == T
+    kv_len = np.concatenate([m.kv_len for m in metas])
+    slots = np.concatenate([m.logical_slot for m in metas])
+    pos = np.concatenate([m.position_ids for m in metas])
+    for slot, branch, stage, p, vis in ex["slots"]:
+        assert tt.branch[0][slot] == branch
+        assert tt.stage[0][slot] == stage
+        assert tt.pos[0][slot] == p
+        assert slots[slot] == slot and pos[slot] == p
+        # visibility as of the moment the token was appended == as of now, restricted to then-existing
+        got = {j for j in range(T) if tt.visible_pair(0, slot, j)}
+        assert got == vis, (slot, got, vis)
+        assert set(np.nonzero(tt.dense_mask(0, [slot])[0])[0]) == vis
+        assert kv_len[slot] == len(vis)
+
+
+# ----------------------------------------------------------------------------- brute force
+def _visible_set_by_history(stages, slot_of):
+    """Independent enumeration from the prose of Sec. 3.3: a parallel token attends the tokens of
+    the main branch and of earlier stages plus its own branch's earlier tokens and itself; a
+    main token attends the complete history.  `stages` is a list of ("serial", n) or
+    ("parallel", [n_1..n_K]) with branch tokens appended one per active branch per step."""
+    order = []          # (stage index, branch, t) in append order
+    for si, (kind, arg) in enumerate(stages):
+        if kind == "serial":
+            order += [(si, 0, t) for t in range(arg)]
+        else:
+            for t in range(max(arg)):
+                order += [(si, k + 1, t) for k, n in enumerate(arg) if n > t]
+    vis = []
+    for i, (si, bi, ti) in enumerate(order):
+        if bi == 0:
+            vis.append(set(range(i + 1)))
+        else:
+            v = {j for j, (sj, bj, tj) in enumerate(order) if sj < si}
+            v |= {j for j, (sj, bj, tj) in enumerate(order) if sj == si and bj == bi and tj <= ti}
+            vis.append(v)
+    return order, vis
+
+
+def _table_from_stages(stages):
+    tt = TokenTable(np.arange(8, dtype=np.int32)[None, :], 16)
+    for kind, arg in stages:
+        if kind == "serial":
+            tt.append_serial([arg])
+        else:
+            tt.open_parallel([len(arg)])
+            for new_len in W.interleaved_history(arg):
+                tt.append_parallel(new_len)
+            tt.merge()
+    return tt
+
+
+def test_mask_brute_force_tiny():
+    count = 0
+    for L in range(0, 4):
+        for K in range(1, 4):
+            for lens in itertools.product(range(1, 4), repeat=K):
+                for tail in (0, 2):
+                    stages = [("serial", L), ("parallel", list(lens)), ("serial", tail)]
+                    order, vis = _visible_set_by_history(stages, None)
+                    tt = _table_from_stages(stages)
+                    T = len(order)
+                    assert len(tt.pos[0]) == T
+                    dm = tt.dense_mask(0, np.arange(T))
+                    for i in range(T):
+                        got = {j for j in range(T) if tt.visible_pair(0, i, j)}
+                        assert got == vis[i], (stages, i)
+                        assert set(np.nonzero(dm[i])[0]) == vis[i]
+                    count += 1
+    assert count > 150
+
+
+def test_mask_brute_force_two_rounds():
+    for a, b in itertools.product([[1, 2], [3, 1, 2]], [[2], [1, 3]]):
+        stages = [("serial", 2), ("parallel", a), ("serial", 1), ("parallel", b), ("serial", 1)]
+        order, vis = _visible_set_by_history(stages, None)
+        tt = _table_from_stages(stages)
+        dm = tt.dense_mask(0, np.arange(len(order)))
+        for i in range(len(order)):
+            assert set(np.nonzero(dm[i])[0]) == vis[i]
+
+
+# ----------------------------------------------------------------------------- closed forms
+def test_parallel_counts_and_positions_closed_form():
+    wl = W.random_small(11, batch=4)
+    tt = table_with_prefix(wl)
+    tt.open_parallel(wl.num_branches)
+    cu = wl.cu_branches
+    n = np.zeros(wl.NB, dtype=np.int64)
+    seq_of_branch = np.repeat(np.arange(wl.B), wl.num_branches)
+    for new_len in W.interleaved_history(wl.branch_len):
+        m = tt.append_parallel(new_len)
+        n += new_len
+        active = np.nonzero(new_len)[0]
+        assert m.NQ == active.size
+        assert np.array_equal(m.q_branch, active)
+        assert np.array_equal(m.q_seq, seq_of_branch[active])
+        L = wl.prefix_len[m.q_seq]
+        # number of visible keys: shared prefix plus the own branch, itself included
+        assert np.array_equal(m.kv_len, L + n[active])
+        # Eq. 4 case 2: stage_start + index within the branch; equal for branches at equal index
+        assert np.array_equal(m.position_ids, L + n[active] - 1)
+    T = wl.prefix_len + np.add.reduceat(wl.branch_len, cu[:-1])
+    assert np.array_equal(tt.seq_len(), T)
+    assert np.array_equal(tt.stage_base(), wl.prefix_len)
+    assert np.array_equal(tt.branch_len(), wl.branch_len)
+    # after the merge the first main token sits at its flattened index and sees everything
+    tt.merge()
+    m = tt.append_serial(np.ones(wl.B, dtype=np.int32))
+    assert np.array_equal(m.position_ids, T)
+    assert np.array_equal(m.kv_len, T + 1)
+    assert np.array_equal(m.q_branch, -np.ones(wl.B, dtype=np.int32))
+    assert np.array_equal(tt.stage_base(), T + 1)
+
+
+def test_chunk_counts_closed_form():
+    wl = W.random_small(12, batch=3)
+    tt = table_at(wl, wl.branch_len)
+    c = np.arange(wl.NB, dtype=np.int32) % 4 + 1          # ragged chunk lengths 1..4
+    m = tt.append_parallel(c)
+    assert m.NQ == int(c.sum())
+    seq_of_branch = np.repeat(np.arange(wl.B), wl.num_branches)
+    row = 0
+    for b in range(wl.NB):
+        assert m.cu_new[b] == row
+        for j in range(c[b]):
+            L = wl.prefix_len[seq_of_branch[b]]
+            assert m.q_branch[row] == b
+            assert m.kv_len[row] == L + wl.branch_len[b] + j + 1
+            assert m.position_ids[row] == L + wl.branch_len[b] + j
+            row += 1
+    # the chunk of one branch occupies consecutive slots
+    for b in range(wl.NB):
+        sl = m.logical_slot[m.cu_new[b]:m.cu_new[b + 1]]
+        assert np.array_equal(sl, sl[0] + np.arange(c[b]))
+
+
+def test_single_branch_is_native_autoregression():
+    # K = 1: position id == slot, every earlier token visible (Sec. 3.2, "consistent with native
+    # autoregressive generation")
+    wl = W.random_small(13, batch=2, branches_range=(1, 1))
+    tt = table_at(wl, wl.branch_len)
+    for s in range(wl.B):
+        T = len(tt.pos[s])
+        assert tt.pos[s] == list(range(T))
+        dm = tt.dense_mask(s, np.arange(T))
+        assert np.array_equal(dm, np.tril(np.ones((T, T), dtype=bool)))
+
+
+def test_positions_increase_along_every_visible_chain():
+    wl = W.random_small(14, batch=3)
+    tt = table_at(wl, wl.branch_len)
+    tt.merge()
+    tt.append_serial(np.full(wl.B, 2, dtype=np.int32))
+    for s in range(wl.B):
+        T = len(tt.pos[s])
+        dm = tt.dense_mask(s, np.arange(T))
+        pos = np.array(tt.pos[s])
+        for i in range(T):
+            others = np.nonzero(dm[i])[0]
+            others = others[others != i]
+            assert np.all(pos[others] < pos[i])
+            assert dm[i, i]
+
+
+# ----------------------------------------------------------------------------- slots
+def test_slot_mapping_bijection_and_owner_histogram():
+    wl = W.random_small(15, batch=5)
+    tt = table_with_prefix(wl)
+    tt.open_parallel(wl.num_branches)
+    seen = {}
+    for new_len in W.interleaved_history(wl.branch_len):
+        m = tt.append_parallel(new_len)
+        for r in range(m.NQ):
+            s, ls, ph = int(m.q_seq[r]), int(m.logical_slot[r]), int(m.slot_mapping[r])
+            assert ph == int(wl.block_tables[s, ls // 16]) * 16 + ls % 16
+            assert ph not in seen
+            seen[ph] = (s, ls)
+    stride = wl.max_blocks_per_seq * 16
+    owner = tt.slot_owner(stride)
+    cu = wl.cu_branches
+    for s in range(wl.B):
+        L = wl.prefix_len[s]
+        tags = owner[s, L:tt.seq_len()[s]]
+        hist = np.bincount(tags, minlength=wl.num_branches[s] + 1)
+        assert hist[0] == 0
+        assert np.array_equal(hist[1:], wl.branch_len[cu[s]:cu[s + 1]])
+        assert not owner[s, :L].any() and not owner[s, tt.seq_len()[s]:].any()
+    # all physical slots of all sequences are distinct
+    allp = np.concatenate([tt.physical_slots(s) for s in range(wl.B)])
+    assert np.unique(allp).size == allp.size
+
+
+def test_identity_table_slot_mapping():
+    wl = W.config(1)
+    tt = table_at(wl, wl.branch_len)
+    assert np.array_equal(tt.physical_slots(0), np.arange(94))
+    assert tt.pos[0][-3:] != []  # table non-empty
+    # config 1: the three last-appended branch tokens sit at positions 64+4, 64+8, 64+15
+    last = {}
+    for slot in range(64, 94):
+        last[tt.branch[0][slot]] = tt.pos[0][slot]
+    assert last == {1: 68, 2: 72, 3: 79}
+
+
+def test_replay_is_deterministic():
+    wl = W.random_small(16, batch=3)
+    a, b = table_at(wl, wl.branch_len), table_at(wl, wl.branch_len)
+    assert a.pos == b.pos and a.branch == b.branch and a.stage == b.stage
