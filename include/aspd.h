@@ -1,0 +1,171 @@
+/* aspd.h - branch-isolated attention over one reusable paged KV cache, for AMD MI355X (gfx950).
+ *
+ * The operations are those of the Hybrid Decoding Engine of "ASPD: Adaptive Serial-Parallel
+ * Decoding" (arXiv 2508.08895), Sec. 3.2-3.3.  A sequence is decoded in stages.  In a serial stage
+ * one main branch grows token by token.  In a parallel stage K branches grow at once; a branch token
+ * attends the tokens of all earlier stages plus the earlier tokens of its own branch, never a sibling
+ * branch (Eq. 2-3), and branches share position ids at equal depth (Eq. 4).  After the stage the
+ * main branch attends everything; the KV cache is reused as it is, nothing is recomputed or moved.
+ *
+ * Conventions fixed here where the paper leaves them open:
+ *   - Position ids are 0-based (Eq. 4 minus one; rotary encodings see differences only).
+ *   - A token sees itself (Eq. 2 read as pos(i) > pos(j) or i = j).
+ *   - One cache per sequence, addressed by LOGICAL SLOT = index of the token in append order.
+ *     One append call lays its new tokens at the tail ordered by (branch ascending, token
+ *     ascending).  Physical slot = block_tables[s][slot / block_size] * block_size + slot % block_size.
+ *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).  Scores are scaled by
+ *     sm_scale (0 selects 1/sqrt(head_dim), Eq. 1); natural exponent.
+ *   - The K/V rows of the tokens of an append call must already be in the cache (at
+ *     slot_mapping) when the attention call for them runs.
+ *
+ * Memory: every pointer named *_d is DEVICE memory owned by the caller.  Structs themselves are
+ * host memory, read during the call only.  The library allocates nothing, frees nothing, never
+ * synchronises: each call enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the
+ * default stream) and returns.  Calls read no device data on the host, so they may be captured
+ * into a HIP graph.
+ *
+ * Errors: every entry point returns ASPD_OK (0) or a negative code.  Host-checkable arguments are
+ * validated before anything is launched; contents of device arrays are trusted, except that
+ * aspd_build_branch_meta never writes outside the arrays described to it (see aspd_state.fault_d).
+ */
+#ifndef ASPD_H
+#define ASPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define ASPD_API __attribute__((visibility("default")))
+#else
+#define ASPD_API
+#endif
+
+#define ASPD_OK               0
+#define ASPD_ERR_INVALID_ARG (-1) /* null pointer, negative size, misaligned buffer            */
+#define ASPD_ERR_UNSUPPORTED (-2) /* dtype / head_dim / block_size / head ratio / batch limits */
+#define ASPD_ERR_WORKSPACE   (-3) /* workspace_bytes below aspd_workspace_bytes(...)           */
+#define ASPD_ERR_HIP         (-4) /* a HIP call or launch failed                               */
+
+#define ASPD_F32  0 /* fp32 in, fp32 accumulate, fp32 out                                 */
+#define ASPD_BF16 1 /* bf16 in, fp32 accumulate, bf16 out (round to nearest even)         */
+
+#define ASPD_STAGE_PARALLEL 0 /* append new_len[b] tokens to branch b of the running parallel stage */
+#define ASPD_STAGE_SERIAL   1 /* append new_len[s] main-branch tokens to sequence s                 */
+#define ASPD_STAGE_MERGE    2 /* the parallel stage ends; no token is appended, no KV is touched     */
+
+#define ASPD_POS_SAME_SEQ 0 /* Eq. 4 as adopted by the paper (Sec. 4.5.3, "Same-Sequential")     */
+
+#define ASPD_MAX_BATCH             1024 /* sequences per call                                      */
+#define ASPD_MAX_BRANCHES_PER_SEQ  255  /* owner tags are one byte                                 */
+
+/* bits of *aspd_state.fault_d */
+#define ASPD_FAULT_BLOCK_TABLE 1 /* a sequence outgrew max_blocks_per_seq or hit a negative block id */
+#define ASPD_FAULT_OWNER_ROW   2 /* a sequence outgrew owner_stride                                   */
+#define ASPD_FAULT_ROW_COUNT   4 /* the sum of new_len exceeded aspd_step.NQ                          */
+#define ASPD_FAULT_BRANCHES    8 /* a sequence has more than ASPD_MAX_BRANCHES_PER_SEQ branches        */
+
+/* The one reusable KV cache (paper: abstract, Sec. 2.3).  K and V each are
+ * [num_blocks][num_kv_heads][block_size][head_dim] elements of `dtype`, so the rows one KV head
+ * keeps for one block are one contiguous page.  block_size must be 16; head_dim 64 or 128;
+ * num_q_heads a multiple of num_kv_heads.  "Contiguous KV" is the identity block table. */
+typedef struct aspd_kv {
+  void*          k_cache_d;
+  void*          v_cache_d;
+  const int32_t* block_tables_d; /* [B][max_blocks_per_seq], physical block of logical block i */
+  int32_t        num_blocks;
+  int32_t        block_size;
+  int32_t        num_q_heads;
+  int32_t        num_kv_heads;
+  int32_t        head_dim;
+  int32_t        max_blocks_per_seq;
+  int32_t        dtype;          /* ASPD_F32 | ASPD_BF16 */
+} aspd_kv;
+
+/* Decode state of a batch.  Caller-owned; only aspd_build_branch_meta writes it.
+ * Sequence s: slots [0, stage_base[s]) are visible to every current query (everything before the
+ * running parallel stage: Eq. 3, "different stage"); slots [stage_base[s], seq_len[s]) belong to the
+ * branches of the running parallel stage, slot j to branch slot_owner[s][j] in 1..K_s.  Branches are
+ * numbered globally over the batch: sequence s owns branches [cu_branches[s], cu_branches[s+1]).
+ * To open a parallel stage the caller provides cu_branches and zeroes branch_len (stage_base equals
+ * seq_len after any serial append or merge). */
+typedef struct aspd_state {
+  int32_t        B;              /* sequences                                                      */
+  int32_t        NB;             /* branches over the whole batch (0 when every sequence is serial) */
+  int32_t*       stage_base_d;   /* [B]                                                            */
+  int32_t*       seq_len_d;      /* [B]  logical slots in use                                      */
+  const int32_t* cu_branches_d;  /* [B+1] exclusive scan of branches per sequence                  */
+  int32_t*       branch_len_d;   /* [NB] tokens held by each branch                                */
+  uint8_t*       slot_owner_d;   /* [B][owner_stride], indexed by logical slot                     */
+  int32_t        owner_stride;
+  int32_t*       fault_d;        /* nullable; ASPD_FAULT_* bits are OR-ed in, tokens that would not
+                                    fit are dropped instead of written out of bounds               */
+} aspd_state;
+
+/* What one aspd_build_branch_meta call produces for the NQ tokens it appends (caller-allocated).
+ * Packed row order: sequence-major, then branch, then token: the order of the query rows in
+ * q_d / out_d of the attention call that follows. */
+typedef struct aspd_step {
+  int32_t  NQ;              /* host: total tokens appended (sum of new_len)                        */
+  int32_t* cu_new_d;        /* [NB+1] (PARALLEL) or [B+1] (SERIAL): first row of each branch / sequence */
+  int32_t* cu_seq_new_d;    /* [B+1] first row of each sequence                                    */
+  int32_t* q_seq_d;         /* [NQ] sequence of the token                                          */
+  int32_t* q_branch_d;      /* [NQ] global branch index, -1 for main-branch tokens                 */
+  int32_t* position_ids_d;  /* [NQ] Eq. 4, 0-based                                                 */
+  int32_t* logical_slot_d;  /* [NQ]                                                                */
+  int64_t* slot_mapping_d;  /* [NQ] physical slot: where the caller writes the token's K and V      */
+  int32_t* kv_len_d;        /* [NQ] number of keys the token attends to, itself included           */
+} aspd_step;
+
+/* Sec. 3.2 Eq. 4 and the bookkeeping behind Eq. 2-3; Sec. 3.3 for the stage switches.
+ * PARALLEL: new_len_d[NB]; token t (0-based, counting tokens already held) of a branch of sequence s
+ *   gets position stage_base[s] + t; branch_len and seq_len grow; slot_owner is tagged.  Entries may
+ *   be 0 (finished branch: its KV stays, it gets no query) or > 1 (chunk append).
+ * SERIAL:   new_len_d[B]; main-branch token gets position = number of tokens already in the sequence
+ *   (its flattened index); seq_len grows and stage_base follows it.  state->NB / branch arrays unused.
+ * MERGE:    new_len_d and out may be NULL; stage_base[s] <- seq_len[s].  No KV is read or written.
+ * pos_mode must be ASPD_POS_SAME_SEQ.  out->NQ must equal the sum of new_len (known to the caller;
+ * rows beyond it are dropped and ASPD_FAULT_ROW_COUNT is raised). */
+ASPD_API int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int32_t stage, int32_t pos_mode,
+                           const int32_t* new_len_d, aspd_step* out, void* stream);
+
+/* Bytes of device scratch the attention calls need for partial softmax results of split key
+ * ranges (host-only computation, needs no GPU).  Returns 0 on invalid arguments. */
+ASPD_API size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ);
+
+/* Sec. 3.2 Eq. 1-3, "The Parallel Branch's Perspective"; Sec. 3.3.  One new token per active branch
+ * (the step built with ASPD_STAGE_PARALLEL and new_len in {0,1}): row r attends slots
+ * [0, stage_base) plus the slots of its own branch up to and including its own.
+ * q_d, out_d: [NQ][num_q_heads][head_dim] in kv->dtype, 16-byte aligned.  lse_d: nullable
+ * [NQ][num_q_heads] float, natural-log sum of exp of the scaled scores.  workspace_d: 256-byte
+ * aligned.  The KV pages shared by the branches of a sequence are read once for all of them. */
+ASPD_API int aspd_attn_parallel_decode(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
+                              const void* q_d, void* out_d, float* lse_d, float sm_scale,
+                              void* workspace_d, size_t workspace_bytes, void* stream);
+
+/* Sec. 3.3 (the per-branch prefix the engine forces at the start of each branch) under the mask
+ * of Eq. 2-3: a step built with ASPD_STAGE_PARALLEL and any new_len >= 0.  Chunk token j of branch b
+ * attends [0, stage_base), b's earlier tokens, and b's chunk tokens up to and including j.
+ * Arguments as aspd_attn_parallel_decode. */
+ASPD_API int aspd_attn_branch_chunk(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
+                           const void* q_d, void* out_d, float* lse_d, float sm_scale,
+                           void* workspace_d, size_t workspace_bytes, void* stream);
+
+/* Sec. 3.2 "The Main Branch's Perspective"; Eq. 3 case 1.  Rows of a step built with
+ * ASPD_STAGE_SERIAL: each attends every slot of its sequence up to and including its own -
+ * serial prefix, all branches of all finished parallel stages, earlier main tokens.
+ * Arguments as aspd_attn_parallel_decode (state->NB and branch arrays unused). */
+ASPD_API int aspd_attn_serial_decode(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
+                            const void* q_d, void* out_d, float* lse_d, float sm_scale,
+                            void* workspace_d, size_t workspace_bytes, void* stream);
+
+/* Static string for a return code. */
+ASPD_API const char* aspd_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASPD_H */

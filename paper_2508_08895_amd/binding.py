@@ -1,0 +1,209 @@
+"""ctypes binding of libaspd.so: argument marshalling only.
+
+Every operation runs in the library's HIP kernels.  PyTorch is used for device memory
+and for the current stream, nothing else.  There is no fallback: if the shared library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaspd.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+F32, BF16 = 0, 1
+STAGE_PARALLEL, STAGE_SERIAL, STAGE_MERGE = 0, 1, 2
+POS_SAME_SEQ = 0
+FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES = 1, 2, 4, 8
+
+EXPORTS = ("aspd_build_branch_meta", "aspd_workspace_bytes", "aspd_attn_parallel_decode",
+           "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_status_string")
+
+
+class aspd_kv(C.Structure):
+    _fields_ = [("k_cache_d", C.c_void_p), ("v_cache_d", C.c_void_p), ("block_tables_d", C.c_void_p),
+                ("num_blocks", C.c_int32), ("block_size", C.c_int32), ("num_q_heads", C.c_int32),
+                ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("max_blocks_per_seq", C.c_int32),
+                ("dtype", C.c_int32)]
+
+
+class aspd_state(C.Structure):
+    _fields_ = [("B", C.c_int32), ("NB", C.c_int32), ("stage_base_d", C.c_void_p), ("seq_len_d", C.c_void_p),
+                ("cu_branches_d", C.c_void_p), ("branch_len_d", C.c_void_p), ("slot_owner_d", C.c_void_p),
+                ("owner_stride", C.c_int32), ("fault_d", C.c_void_p)]
+
+
+class aspd_step(C.Structure):
+    _fields_ = [("NQ", C.c_int32), ("cu_new_d", C.c_void_p), ("cu_seq_new_d", C.c_void_p),
+                ("q_seq_d", C.c_void_p), ("q_branch_d", C.c_void_p), ("position_ids_d", C.c_void_p),
+                ("logical_slot_d", C.c_void_p), ("slot_mapping_d", C.c_void_p), ("kv_len_d", C.c_void_p)]
+
+
+class AspdError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {status_string(code)} ({code})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2508_08895_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.aspd_build_branch_meta.restype = C.c_int
+        L.aspd_build_branch_meta.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_state), C.c_int32, C.c_int32,
+                                             C.c_void_p, C.POINTER(aspd_step), C.c_void_p]
+        L.aspd_workspace_bytes.restype = C.c_size_t
+        L.aspd_workspace_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
+        for name in ("aspd_attn_parallel_decode", "aspd_attn_branch_chunk", "aspd_attn_serial_decode"):
+            fn = getattr(L, name)
+            fn.restype = C.c_int
+            fn.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_state), C.POINTER(aspd_step), C.c_void_p,
+                           C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.aspd_status_string.restype = C.c_char_p
+        L.aspd_status_string.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().aspd_status_string(int(code)).decode()
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+_DTYPE = {torch.float32: F32, torch.bfloat16: BF16}
+
+
+@dataclass
+class KVCache:
+    """Device tensors of the paged cache: k, v [num_blocks][Hkv][16][D]; block_tables [B][max_blocks] int32."""
+    k: torch.Tensor
+    v: torch.Tensor
+    block_tables: torch.Tensor
+    num_q_heads: int
+
+    def struct(self) -> aspd_kv:
+        nb, hkv, bs, d = self.k.shape
+        return aspd_kv(_ptr(self.k), _ptr(self.v), _ptr(self.block_tables), nb, bs, self.num_q_heads, hkv, d,
+                       self.block_tables.shape[1], _DTYPE[self.k.dtype])
+
+
+class BatchState:
+    """Caller-owned decode state of a batch (device int arrays), see aspd_state in aspd.h."""
+
+    def __init__(self, B: int, owner_stride: int, device):
+        self.B = B
+        self.NB = 0
+        self.device = device
+        self.stage_base = torch.zeros(B, dtype=torch.int32, device=device)
+        self.seq_len = torch.zeros(B, dtype=torch.int32, device=device)
+        self.cu_branches = None
+        self.branch_len = None
+        self.owner_stride = int(owner_stride)
+        self.slot_owner = torch.zeros(B, self.owner_stride, dtype=torch.uint8, device=device)
+        self.fault = torch.zeros(1, dtype=torch.int32, device=device)
+
+    def open_parallel(self, cu_branches: torch.Tensor) -> None:
+        """New parallel stage: branch layout given by the caller, branch lengths start at zero."""
+        self.cu_branches = cu_branches.to(device=self.device, dtype=torch.int32)
+        self.NB = int(cu_branches[-1])
+        self.branch_len = torch.zeros(max(self.NB, 1), dtype=torch.int32, device=self.device)
+
+    def struct(self) -> aspd_state:
+        return aspd_state(self.B, self.NB, _ptr(self.stage_base), _ptr(self.seq_len), _ptr(self.cu_branches),
+                          _ptr(self.branch_len), _ptr(self.slot_owner), self.owner_stride, _ptr(self.fault))
+
+
+class Step:
+    """Outputs of one aspd_build_branch_meta call (device arrays sized for NQ rows)."""
+
+    def __init__(self, NQ: int, n_cu: int, B: int, device):
+        self.NQ = int(NQ)
+        i32 = dict(dtype=torch.int32, device=device)
+        n = max(self.NQ, 1)
+        self.cu_new = torch.zeros(n_cu + 1, **i32)
+        self.cu_seq_new = torch.zeros(B + 1, **i32)
+        self.q_seq = torch.zeros(n, **i32)
+        self.q_branch = torch.zeros(n, **i32)
+        self.position_ids = torch.zeros(n, **i32)
+        self.logical_slot = torch.zeros(n, **i32)
+        self.slot_mapping = torch.zeros(n, dtype=torch.int64, device=device)
+        self.kv_len = torch.zeros(n, **i32)
+
+    def struct(self) -> aspd_step:
+        return aspd_step(self.NQ, _ptr(self.cu_new), _ptr(self.cu_seq_new), _ptr(self.q_seq), _ptr(self.q_branch),
+                         _ptr(self.position_ids), _ptr(self.logical_slot), _ptr(self.slot_mapping),
+                         _ptr(self.kv_len))
+
+
+def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: torch.Tensor | None,
+                           NQ: int = 0, step: Step | None = None, stream=None) -> Step | None:
+    """See aspd.h.  `NQ` = sum of new_len, known to the caller.  Returns the Step (None for MERGE)."""
+    kvs, sts = kv.struct(), state.struct()
+    if stage == STAGE_MERGE:
+        rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, POS_SAME_SEQ, None, None,
+                                          _stream(stream))
+        if rc != OK:
+            raise AspdError(rc, "aspd_build_branch_meta")
+        return None
+    if step is None:
+        step = Step(NQ, state.NB if stage == STAGE_PARALLEL else state.B, state.B, state.device)
+    sps = step.struct()
+    rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, POS_SAME_SEQ, _ptr(new_len),
+                                      C.byref(sps), _stream(stream))
+    if rc != OK:
+        raise AspdError(rc, "aspd_build_branch_meta")
+    return step
+
+
+def aspd_workspace_bytes(kv: KVCache, B: int, NQ: int) -> int:
+    kvs = kv.struct()
+    return int(lib().aspd_workspace_bytes(C.byref(kvs), B, NQ))
+
+
+def _attn(name, kv, state, step, q, out, lse, sm_scale, workspace, stream):
+    kvs, sts, sps = kv.struct(), state.struct(), step.struct()
+    if out is None:
+        out = torch.empty_like(q)
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = getattr(lib(), name)(C.byref(kvs), C.byref(sts), C.byref(sps), _ptr(q), _ptr(out), _ptr(lse),
+                              C.c_float(sm_scale), _ptr(workspace), nbytes, _stream(stream))
+    if rc != OK:
+        raise AspdError(rc, name)
+    return out
+
+
+def aspd_attn_parallel_decode(kv, state, step, q, workspace, out=None, lse=None, sm_scale=0.0, stream=None):
+    return _attn("aspd_attn_parallel_decode", kv, state, step, q, out, lse, sm_scale, workspace, stream)
+
+
+def aspd_attn_branch_chunk(kv, state, step, q, workspace, out=None, lse=None, sm_scale=0.0, stream=None):
+    return _attn("aspd_attn_branch_chunk", kv, state, step, q, out, lse, sm_scale, workspace, stream)
+
+
+def aspd_attn_serial_decode(kv, state, step, q, workspace, out=None, lse=None, sm_scale=0.0, stream=None):
+    return _attn("aspd_attn_serial_decode", kv, state, step, q, out, lse, sm_scale, workspace, stream)
+
+
+def new_workspace(kv: KVCache, B: int, NQ: int) -> torch.Tensor:
+    """Device scratch of the size the attention calls ask for (256-byte aligned by the allocator)."""
+    return torch.empty(aspd_workspace_bytes(kv, B, NQ), dtype=torch.uint8, device=kv.k.device)

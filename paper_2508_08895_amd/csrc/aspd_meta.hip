@@ -1,0 +1,234 @@
+// aspd_build_branch_meta: position ids (ASPD Sec. 3.2, Eq. 4), cache slots and owner tags for the
+// tokens one append call adds, and the update of the batch's decode state (Sec. 3.3 stage switches).
+//
+// Pure integer work, one workgroup per sequence.  A workgroup needs two things from outside its own
+// sequence: the packed row of its first token (the number of tokens appended to earlier sequences)
+// and nothing else, so it sums new_len over the earlier branches itself instead of waiting for a
+// batch-wide scan: new_len is an input no workgroup writes, hence no ordering between workgroups.
+#include "aspd_common.h"
+
+namespace {
+
+constexpr int META_THREADS = 256;
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+// Sum over the workgroup; every thread gets the total.  `red` holds META_THREADS/64 ints.
+__device__ int block_sum(int v, int* red) {
+  v = wave_sum(v);
+  __syncthreads();  // red may still be read from an earlier call
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  int tot = 0;
+#pragma unroll
+  for (int w = 0; w < META_THREADS / 64; ++w) tot += red[w];
+  return tot;
+}
+
+__device__ __forceinline__ void raise_fault(int32_t* fault, int bits) {
+  if (fault) atomicOr(fault, bits);
+}
+
+// PARALLEL stage: new_len[NB].  Branch tokens take position stage_start + index-in-branch (Eq. 4,
+// second case) and are laid at the tail of the sequence ordered by (branch, token).
+__global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, StateView st, StepView sp,
+                                                                     const int32_t* __restrict__ new_len) {
+  __shared__ int red[META_THREADS / 64];
+  __shared__ int off[ASPD_MAX_BRANCHES_PER_SEQ + 2];  // exclusive scan of this sequence's new_len
+  __shared__ int held[ASPD_MAX_BRANCHES_PER_SEQ + 1]; // tokens each branch already holds
+  const int s = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int b0 = st.cu_branches[s];
+  const int b1 = st.cu_branches[s + 1];
+  const int L = st.stage_base[s];  // state is read here, ahead of the barriers below, and
+  const int T = st.seq_len[s];     // written only after the last of them
+  int K = b1 - b0;
+  if (K > ASPD_MAX_BRANCHES_PER_SEQ) {
+    if (tid == 0) raise_fault(st.fault, ASPD_FAULT_BRANCHES);
+    K = ASPD_MAX_BRANCHES_PER_SEQ;
+  }
+
+  // packed row of this sequence's first new token
+  int part = 0;
+  for (int i = tid; i < b0; i += META_THREADS) part += new_len[i];
+  const int base = block_sum(part, red);
+
+  // scan over the sequence's own branches (K <= 255: one branch per thread, serial scan by thread 0
+  // would do, but a log-step scan keeps the launch short for wide stages)
+  const int c_mine = (tid < K) ? new_len[b0 + tid] : 0;
+  if (tid < K) held[tid] = st.branch_len[b0 + tid];
+  if (tid <= K) off[tid] = 0;
+  __syncthreads();
+  {
+    // inclusive Hillis-Steele in registers + LDS over the first 256 threads
+    __shared__ int scan[META_THREADS];
+    scan[tid] = c_mine;
+    __syncthreads();
+    for (int d = 1; d < META_THREADS; d <<= 1) {
+      int v = (tid >= d) ? scan[tid - d] : 0;
+      __syncthreads();
+      scan[tid] += v;
+      __syncthreads();
+    }
+    if (tid < K) off[tid + 1] = scan[tid];
+    __syncthreads();
+  }
+  const int total = off[K];
+
+  if (tid < K) sp.cu_new[b0 + tid] = base + off[tid];
+  if (tid == 0) {
+    sp.cu_seq_new[s] = base;
+    if (s == st.B - 1) {
+      sp.cu_seq_new[st.B] = base + total;
+      sp.cu_new[b1] = base + total;
+    }
+  }
+
+  // capacity of this sequence in slots
+  const long cap_slots = (long)kv.max_blocks_per_seq * ASPD_BLOCK;
+  bool ok = true;
+  if ((long)T + total > cap_slots) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE); }
+  if ((long)T + total > st.owner_stride) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_OWNER_ROW); }
+  if (base + total > sp.NQ) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_ROW_COUNT); }
+  if (!ok) return;  // the sequence is left as it was
+
+  for (int idx = tid; idx < total; idx += META_THREADS) {
+    // branch of token idx: last k with off[k] <= idx
+    int lo = 0, hi = K - 1;
+    while (lo < hi) {
+      int mid = (lo + hi + 1) >> 1;
+      if (off[mid] <= idx) lo = mid; else hi = mid - 1;
+    }
+    const int k = lo;
+    const int t = held[k] + (idx - off[k]);  // 0-based index of the token within its branch
+    const int row = base + idx;
+    const int slot = T + idx;
+    const int blk = kv.block_tables[(long)s * kv.max_blocks_per_seq + slot / ASPD_BLOCK];
+    if (blk < 0 || blk >= kv.num_blocks) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE);
+    sp.q_seq[row] = s;
+    sp.q_branch[row] = b0 + k;
+    sp.position_ids[row] = L + t;
+    sp.logical_slot[row] = slot;
+    sp.slot_mapping[row] = (int64_t)blk * ASPD_BLOCK + slot % ASPD_BLOCK;
+    sp.kv_len[row] = L + t + 1;  // shared prefix + own branch up to and including itself
+    st.slot_owner[(long)s * st.owner_stride + slot] = (uint8_t)(k + 1);
+  }
+  // state update: every read of branch_len / seq_len happened before the barriers of the scan
+  __syncthreads();
+  if (tid < K) st.branch_len[b0 + tid] = held[tid] + c_mine;
+  if (tid == 0) st.seq_len[s] = T + total;
+}
+
+// SERIAL stage: new_len[B].  A main-branch token's position is the number of tokens decoded before
+// it, all branches of all earlier stages included (Eq. 4, first case): its flattened index.
+__global__ __launch_bounds__(META_THREADS) void meta_serial_kernel(KvView kv, StateView st, StepView sp,
+                                                                   const int32_t* __restrict__ new_len) {
+  __shared__ int red[META_THREADS / 64];
+  const int s = blockIdx.x;
+  const int tid = threadIdx.x;
+  int part = 0;
+  for (int i = tid; i < s; i += META_THREADS) part += new_len[i];
+  const int base = block_sum(part, red);
+  const int c = new_len[s];
+  const int T = st.seq_len[s];
+  if (tid == 0) {
+    sp.cu_new[s] = base;
+    sp.cu_seq_new[s] = base;
+    if (s == st.B - 1) {
+      sp.cu_new[st.B] = base + c;
+      sp.cu_seq_new[st.B] = base + c;
+    }
+  }
+  bool ok = true;
+  if ((long)T + c > (long)kv.max_blocks_per_seq * ASPD_BLOCK) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE); }
+  if (base + c > sp.NQ) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_ROW_COUNT); }
+  if (!ok) return;
+  for (int idx = tid; idx < c; idx += META_THREADS) {
+    const int row = base + idx;
+    const int slot = T + idx;
+    const int blk = kv.block_tables[(long)s * kv.max_blocks_per_seq + slot / ASPD_BLOCK];
+    if (blk < 0 || blk >= kv.num_blocks) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE);
+    sp.q_seq[row] = s;
+    sp.q_branch[row] = -1;
+    sp.position_ids[row] = slot;
+    sp.logical_slot[row] = slot;
+    sp.slot_mapping[row] = (int64_t)blk * ASPD_BLOCK + slot % ASPD_BLOCK;
+    sp.kv_len[row] = slot + 1;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    st.seq_len[s] = T + c;
+    st.stage_base[s] = T + c;  // a serial sequence has no branch region
+  }
+}
+
+// MERGE: the parallel stage ends.  Everything decoded so far becomes visible to all later queries;
+// the cache is reused as it is (Sec. 3.3: no re-prefill when switching back).
+__global__ void meta_merge_kernel(StateView st) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s < st.B) st.stage_base[s] = st.seq_len[s];
+}
+
+}  // namespace
+
+int aspd_check_kv(const aspd_kv* kv) {
+  if (!kv || !kv->k_cache_d || !kv->v_cache_d || !kv->block_tables_d) return ASPD_ERR_INVALID_ARG;
+  if (kv->num_blocks <= 0 || kv->max_blocks_per_seq <= 0 || kv->num_q_heads <= 0 || kv->num_kv_heads <= 0)
+    return ASPD_ERR_INVALID_ARG;
+  if (kv->block_size != ASPD_BLOCK) return ASPD_ERR_UNSUPPORTED;
+  if (kv->head_dim != 64 && kv->head_dim != 128) return ASPD_ERR_UNSUPPORTED;
+  if (kv->dtype != ASPD_F32 && kv->dtype != ASPD_BF16) return ASPD_ERR_UNSUPPORTED;
+  if (kv->num_q_heads % kv->num_kv_heads != 0) return ASPD_ERR_UNSUPPORTED;
+  if (((uintptr_t)kv->k_cache_d & 15) || ((uintptr_t)kv->v_cache_d & 15)) return ASPD_ERR_INVALID_ARG;
+  return ASPD_OK;
+}
+
+extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int32_t stage, int32_t pos_mode,
+                                      const int32_t* new_len_d, aspd_step* out, void* stream) {
+  int rc = aspd_check_kv(kv);
+  if (rc != ASPD_OK) return rc;
+  if (!state || state->B <= 0 || !state->stage_base_d || !state->seq_len_d) return ASPD_ERR_INVALID_ARG;
+  if (state->B > ASPD_MAX_BATCH) return ASPD_ERR_UNSUPPORTED;
+  if (pos_mode != ASPD_POS_SAME_SEQ) return ASPD_ERR_UNSUPPORTED;
+  hipStream_t hs = (hipStream_t)stream;
+  StateView sv = make_view(state);
+
+  if (stage == ASPD_STAGE_MERGE) {
+    hipLaunchKernelGGL(meta_merge_kernel, dim3((state->B + 255) / 256), dim3(256), 0, hs, sv);
+    ASPD_HIP_CHECK(hipGetLastError());
+    return ASPD_OK;
+  }
+  if (stage != ASPD_STAGE_PARALLEL && stage != ASPD_STAGE_SERIAL) return ASPD_ERR_INVALID_ARG;
+  if (!new_len_d || !out || out->NQ < 0) return ASPD_ERR_INVALID_ARG;
+  if (!out->cu_new_d || !out->cu_seq_new_d) return ASPD_ERR_INVALID_ARG;
+  if (out->NQ > 0 && (!out->q_seq_d || !out->q_branch_d || !out->position_ids_d || !out->logical_slot_d ||
+                      !out->slot_mapping_d || !out->kv_len_d))
+    return ASPD_ERR_INVALID_ARG;
+  KvView kvv = make_view(kv);
+  StepView spv = make_view(out);
+  if (stage == ASPD_STAGE_PARALLEL) {
+    if (state->NB <= 0 || !state->cu_branches_d || !state->branch_len_d || !state->slot_owner_d ||
+        state->owner_stride <= 0)
+      return ASPD_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(meta_parallel_kernel, dim3(state->B), dim3(META_THREADS), 0, hs, kvv, sv, spv, new_len_d);
+  } else {
+    hipLaunchKernelGGL(meta_serial_kernel, dim3(state->B), dim3(META_THREADS), 0, hs, kvv, sv, spv, new_len_d);
+  }
+  ASPD_HIP_CHECK(hipGetLastError());
+  return ASPD_OK;
+}
+
+extern "C" const char* aspd_status_string(int status) {
+  switch (status) {
+    case ASPD_OK: return "ok";
+    case ASPD_ERR_INVALID_ARG: return "invalid argument";
+    case ASPD_ERR_UNSUPPORTED: return "unsupported configuration";
+    case ASPD_ERR_WORKSPACE: return "workspace too small";
+    case ASPD_ERR_HIP: return "HIP call failed";
+    default: return "unknown status";
+  }
+}

@@ -1,0 +1,262 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Metadata and slot mapping must match bit-exactly; attention outputs within max-abs 1e-5 for fp32
+inputs and 2e-2 for bf16 inputs (fp32 accumulation), the tolerances the benchmark spec states."""
+import numpy as np
+import pytest
+import torch
+
+import aspd_workloads as W
+from oracle import attend
+from oracle_drive import table_with_prefix
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+LSE_TOL = {"f32": 2e-5, "bf16": 2e-3}
+
+
+@pytest.fixture(scope="module")
+def A():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2508_08895_amd import binding
+    binding.lib()  # fail loudly if the library is not built
+    return binding
+
+
+def _compare_attention(A, gb, tt, wl, step, meta, fn, rows=None, label=""):
+    from gpu_drive import assert_step_equal
+    assert_step_equal(step, meta)
+    q = wl.draw_q(meta.NQ)
+    lse = torch.full((meta.NQ, wl.num_q_heads), float("nan"), dtype=torch.float32, device=gb.dev)
+    out = fn(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace, lse=lse)
+    torch.cuda.synchronize()
+    ref, ref_lse = attend(tt, meta, q, wl.k_cache, wl.v_cache, rows=rows)
+    got = out.float().cpu().numpy().astype(np.float64)
+    got_lse = lse.cpu().numpy().astype(np.float64)
+    sel = np.arange(meta.NQ) if rows is None else np.asarray(rows)
+    assert np.isfinite(got[sel]).all(), label
+    err = np.abs(got[sel] - ref[sel]).max()
+    lerr = np.abs(got_lse[sel] - ref_lse[sel]).max()
+    print(f"[{label}] rows={sel.size} max|out-ref|={err:.3e} max|lse-ref|={lerr:.3e}", flush=True)
+    assert err <= TOL[wl.dtype], (label, err)
+    assert lerr <= LSE_TOL[wl.dtype], (label, lerr)
+    return err
+
+
+def _grow_both(A, wl, upto, check_every_step):
+    """Oracle table and GPU batch after prefix + interleaved growth to `upto` tokens per branch."""
+    from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
+    gb = GpuBatch(wl)
+    tt = table_with_prefix(wl)
+    step = gb.serial(wl.prefix_len)
+    tt.open_parallel(wl.num_branches)
+    gb.open_parallel()
+    hist = W.interleaved_history(upto)
+    for i, new_len in enumerate(hist):
+        meta = tt.append_parallel(new_len)
+        step = gb.parallel(new_len)
+        if check_every_step or i >= len(hist) - 2:
+            assert_step_equal(step, meta)
+    assert_state_equal(gb, tt)
+    return gb, tt
+
+
+# --------------------------------------------------------------------------------------------- config 1
+def test_config1_parallel_then_serial_fp32(A):
+    from gpu_drive import assert_state_equal
+    wl = W.config(1)
+    gb, tt = _grow_both(A, wl, wl.branch_len - 1, True)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    assert meta.position_ids.tolist() == [68, 72, 79]
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label="cfg1 parallel")
+    tt.merge()
+    gb.merge()
+    assert_state_equal(gb, tt)
+    one = np.ones(wl.B, dtype=np.int32)
+    meta = tt.append_serial(one)
+    step = gb.serial(one)
+    assert meta.position_ids.tolist() == [94] and meta.kv_len.tolist() == [95]
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label="cfg1 serial")
+    assert_state_equal(gb, tt)
+
+
+# --------------------------------------------------------------------------------------------- configs 2-4
+@pytest.mark.parametrize("index", [2, 3, 4])
+def test_config_parallel_decode_full_size(A, index):
+    wl = W.config(index)
+    gb, tt = _grow_both(A, wl, wl.branch_len - 1, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label=f"cfg{index} parallel")
+    if index == 4:
+        # merge, then serial steps over prefix + all branches (three of the 32 are checked here)
+        from gpu_drive import assert_state_equal
+        tt.merge()
+        gb.merge()
+        one = np.ones(wl.B, dtype=np.int32)
+        for i in range(3):
+            meta = tt.append_serial(one)
+            step = gb.serial(one)
+            _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label=f"cfg4 serial {i}")
+        assert_state_equal(gb, tt)
+
+
+# --------------------------------------------------------------------------------------------- config 5
+@pytest.mark.parametrize("scale,batch", [(0.125, 8), (1.0, 64)])
+def test_config5_chunk_then_decode(A, scale, batch):
+    wl = W.config(5, scale=scale, batch=batch)
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    chunk = np.full(wl.NB, 16, dtype=np.int32)
+    meta = tt.append_parallel(chunk)
+    step = gb.parallel(chunk)
+    rows = None
+    if scale == 1.0:   # full size: a seeded sample of rows the oracle computes one by one
+        rows = np.sort(np.random.default_rng(5).choice(meta.NQ, size=256, replace=False))
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, rows=rows,
+                       label=f"cfg5 chunk scale={scale}")
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    rows = None
+    if scale == 1.0:
+        rows = np.sort(np.random.default_rng(6).choice(meta.NQ, size=96, replace=False))
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, rows=rows,
+                       label=f"cfg5 decode scale={scale}")
+
+
+# --------------------------------------------------------------------------------------------- randomized small
+SMALL = [
+    dict(seed=101, dtype="bf16", head_dim=128, num_q_heads=32, num_kv_heads=8),
+    dict(seed=102, dtype="bf16", head_dim=128, num_q_heads=8, num_kv_heads=8, branches_range=(1, 12)),
+    dict(seed=103, dtype="bf16", head_dim=64, num_q_heads=16, num_kv_heads=4),
+    dict(seed=104, dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=4),
+    dict(seed=105, dtype="f32", head_dim=128, num_q_heads=8, num_kv_heads=2),
+    dict(seed=106, dtype="bf16", head_dim=128, num_q_heads=32, num_kv_heads=8, prefix_range=(0, 0)),
+    dict(seed=107, dtype="bf16", head_dim=128, num_q_heads=32, num_kv_heads=8, branches_range=(9, 14),
+         prefix_range=(100, 300)),
+    dict(seed=108, dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=1, branches_range=(1, 3)),
+]
+
+
+@pytest.mark.parametrize("kw", SMALL, ids=lambda k: f"seed{k['seed']}")
+def test_random_small_all_calls(A, kw):
+    from gpu_drive import assert_state_equal
+    wl = W.random_small(**kw)
+    gb, tt = _grow_both(A, wl, wl.branch_len, True)
+    rng = np.random.default_rng(kw["seed"])
+    # a ragged chunk, some branches getting nothing
+    chunk = rng.integers(0, 7, size=wl.NB).astype(np.int32)
+    if chunk.sum() == 0:
+        chunk[0] = 3
+    meta = tt.append_parallel(chunk)
+    step = gb.parallel(chunk)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label=f"{wl.name} chunk")
+    # a decode step in which some branches have finished
+    active = (rng.random(wl.NB) < 0.7).astype(np.int32)
+    if active.sum() == 0:
+        active[-1] = 1
+    meta = tt.append_parallel(active)
+    step = gb.parallel(active)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label=f"{wl.name} decode")
+    assert_state_equal(gb, tt)
+    # merge and two serial steps
+    tt.merge()
+    gb.merge()
+    for i in range(2):
+        one = np.ones(wl.B, dtype=np.int32)
+        meta = tt.append_serial(one)
+        step = gb.serial(one)
+        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label=f"{wl.name} serial {i}")
+    assert_state_equal(gb, tt)
+
+
+def test_second_parallel_round_sees_first_rounds_branches(A):
+    """Iterative serial-parallel switching (Sec. 3.3): a later stage attends earlier branches."""
+    from gpu_drive import assert_state_equal
+    wl = W.random_small(120, batch=2, extra_tokens_per_branch=30, extra_tokens_per_seq=40)
+    gb, tt = _grow_both(A, wl, wl.branch_len, True)
+    tt.merge()
+    gb.merge()
+    two = np.full(wl.B, 2, dtype=np.int32)
+    meta = tt.append_serial(two)     # two main tokens at once: the second must not see... it sees the first
+    step = gb.serial(two)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label="round2 serial x2")
+    tt.open_parallel(wl.num_branches)
+    gb.open_parallel()
+    for i in range(3):
+        ones = np.ones(wl.NB, dtype=np.int32)
+        meta = tt.append_parallel(ones)
+        step = gb.parallel(ones)
+        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label=f"round2 step {i}")
+    assert_state_equal(gb, tt)
+
+
+# --------------------------------------------------------------------------------------------- invariants on the GPU
+def test_sibling_kv_does_not_reach_a_branch(A):
+    """Perturbing the K/V of sibling branches leaves every output bit-identical (masked weights are
+    exactly zero), Sec. 3.2 "mutual invisibility across branches"."""
+    wl = W.random_small(130, batch=2, branches_range=(3, 5), branch_len_range=(5, 30))
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    q = wl.draw_q(meta.NQ).to(gb.dev)
+    base = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace).clone()
+    cu = wl.cu_branches
+    for r in range(meta.NQ):
+        s = int(meta.q_seq[r])
+        tag = int(meta.q_branch[r]) - int(cu[s]) + 1
+        k2, v2 = gb.kv.k.clone(), gb.kv.v.clone()
+        for j in range(int(wl.prefix_len[s]), len(tt.pos[s])):
+            if tt.branch[s][j] != tag:
+                ph = tt.physical_slot(s, j)
+                k2[ph // 16, :, ph % 16] = 1e30 if j % 2 else -3e4
+                v2[ph // 16, :, ph % 16] = -1e30
+        kv2 = A.KVCache(k2, v2, gb.kv.block_tables, gb.kv.num_q_heads)
+        out = A.aspd_attn_parallel_decode(kv2, gb.state, step, q, gb.workspace)
+        assert torch.equal(out[r], base[r]), r
+
+
+def test_repeat_calls_are_deterministic(A):
+    wl = W.random_small(131, batch=4)
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    step = gb.parallel(ones)
+    q = wl.draw_q(step.NQ).to(gb.dev)
+    a = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace).clone()
+    b = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace)
+    assert torch.equal(a, b)
+
+
+# --------------------------------------------------------------------------------------------- faults (host-forced)
+def test_outgrowing_the_block_table_raises_a_fault_and_writes_nothing(A):
+    from gpu_drive import GpuBatch
+    wl = W.random_small(140, batch=2, extra_tokens_per_branch=0, extra_tokens_per_seq=0)
+    gb = GpuBatch(wl)
+    gb.grow_to(wl.branch_len)
+    assert gb.fault() == 0
+    before = gb.state.seq_len.clone()
+    big = np.full(wl.NB, 64, dtype=np.int32)     # far beyond the capacity of every sequence
+    step = gb.parallel(big)
+    torch.cuda.synchronize()
+    assert gb.fault() & A.FAULT_BLOCK_TABLE
+    assert torch.equal(gb.state.seq_len, before)
+
+
+def test_row_count_mismatch_raises_a_fault(A):
+    from gpu_drive import GpuBatch
+    wl = W.random_small(141, batch=2)
+    gb = GpuBatch(wl)
+    gb.serial(wl.prefix_len)
+    gb.open_parallel()
+    ones = np.ones(wl.NB, dtype=np.int32)
+    new_len = torch.from_numpy(ones).to(gb.dev)
+    A.aspd_build_branch_meta(gb.kv, gb.state, A.STAGE_PARALLEL, new_len, NQ=max(wl.NB - 1, 0) or 1)
+    torch.cuda.synchronize()
+    if wl.NB > 1:
+        assert gb.fault() & A.FAULT_ROW_COUNT
