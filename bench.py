@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the ASPD attention hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch, per attention layer: the branch-chunk
+fill that opens a parallel stage (metadata + attention), one parallel-decode step (metadata +
+attention), the merge (metadata only), and the serial-decode steps that follow (metadata +
+attention each), all through the C ABI of libaspd.so on one HIP stream.  Inputs (KV pool, block
+tables, queries) are resident in HBM before the timed region.  The decode state is restored from a
+snapshot at the start of every step (four small device copies, inside the timed region) so that
+every step does identical work.
+
+Prints ONE JSON line (see README for the fields).  One GPU only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+# name -> (config index, chunk tokens per branch, serial steps after the merge, tokens every branch
+#          holds before the step relative to the config's branch_len)
+WORKLOADS = {
+    "cycle4": dict(index=4, chunk=16, serial=32, base_offset=-17,
+                   what="config 4 batch (B=4, 32q/8kv/128 bf16, prefix 16384, 6 branches of 32..192, paged 16): "
+                        "16-token branch chunk, parallel-decode step, merge, 32 serial-decode steps"),
+    "cfg2": dict(index=2, chunk=0, serial=0, base_offset=-1,
+                 what="config 2 (B=1, prefix 2048, 4 branches at 64): one parallel-decode step"),
+    "cfg3": dict(index=3, chunk=0, serial=0, base_offset=-1,
+                 what="config 3 (B=16 mixed): one parallel-decode step"),
+    "cfg4": dict(index=4, chunk=0, serial=32, base_offset=-1,
+                 what="config 4 (B=4, prefix 16384, 6 branches): parallel-decode step, merge, 32 serial-decode steps"),
+    "cfg5": dict(index=5, chunk=16, serial=0, base_offset=0,
+                 what="config 5 (B=64, prefix 1024..8192, 2..10 branches of 8..128): 16-token branch chunk, "
+                      "then one parallel-decode step"),
+}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cycle4", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is one-GPU only (the path shards by sequence or KV head without "
+              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import aspd_workloads as W
+    from paper_2508_08895_amd import binding as A
+
+    A.lib()  # fail loudly when the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    spec = WORKLOADS[args.workload]
+    t0 = time.time()
+    wl = W.config(spec["index"])
+    print(f"[bench] workload {args.workload}: generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    kv = A.KVCache(wl.k_cache.to(dev), wl.v_cache.to(dev), torch.from_numpy(wl.block_tables).to(dev),
+                   wl.num_q_heads)
+    state = A.BatchState(wl.B, wl.max_blocks_per_seq * 16, dev)
+    B, NB = wl.B, wl.NB
+    base_len = wl.branch_len + spec["base_offset"]
+    assert (base_len >= 0).all()
+
+    def dev_i32(x):
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
+
+    # ---- bring the cache state to the start of a step (untimed)
+    A.aspd_build_branch_meta(kv, state, A.STAGE_SERIAL, dev_i32(wl.prefix_len), NQ=int(wl.prefix_len.sum()))
+    state.open_parallel(torch.from_numpy(wl.cu_branches))
+    for new_len in W.interleaved_history(base_len):
+        A.aspd_build_branch_meta(kv, state, A.STAGE_PARALLEL, dev_i32(new_len), NQ=int(new_len.sum()))
+    torch.cuda.synchronize()
+    assert int(state.fault.item()) == 0
+    snap = [t.clone() for t in (state.stage_base, state.seq_len, state.branch_len, state.slot_owner)]
+    live = (state.stage_base, state.seq_len, state.branch_len, state.slot_owner)
+
+    # ---- pre-allocated per-call inputs and outputs
+    C, S = spec["chunk"], spec["serial"]
+    g = torch.Generator().manual_seed(W.SEED_BASE)
+
+    def rand_q(n):
+        return (torch.randn(n, wl.num_q_heads, wl.head_dim, generator=g) * wl.sigma).to(wl.torch_dtype).to(dev)
+
+    ws = A.new_workspace(kv, B, max(C * NB, NB, B))
+    calls = []  # (kind, stage, new_len_d, step, q, out, fn)
+    if C:
+        calls.append(("chunk", A.STAGE_PARALLEL, dev_i32(np.full(NB, C)), A.Step(C * NB, NB, B, dev),
+                      rand_q(C * NB), A.aspd_attn_branch_chunk))
+    calls.append(("parallel", A.STAGE_PARALLEL, dev_i32(np.ones(NB)), A.Step(NB, NB, B, dev), rand_q(NB),
+                  A.aspd_attn_parallel_decode))
+    if S:
+        calls.append(("merge", A.STAGE_MERGE, None, None, None, None))
+        ones_b = dev_i32(np.ones(B))
+        for _ in range(S):
+            calls.append(("serial", A.STAGE_SERIAL, ones_b, A.Step(B, B, B, dev), rand_q(B),
+                          A.aspd_attn_serial_decode))
+    outs = {id(c): (torch.empty_like(c[4]) if c[4] is not None else None) for c in calls}
+
+    def one_step(events=None):
+        for dst, src in zip(live, snap):
+            dst.copy_(src)
+        for c in calls:
+            kind, stage, new_len, step, q, fn = c
+            A.aspd_build_branch_meta(kv, state, stage, new_len, step=step)
+            if fn is None:
+                continue
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            fn(kv, state, step, q, ws, out=outs[id(c)])
+            if events is not None:
+                e1.record()
+                events.append((kind, e0, e1))
+
+    # ---- algorithmic bytes of every attention call (unique visible KV + Q and O + tables + tags)
+    elt = 2 if wl.dtype == "bf16" else 4
+    kv_tok_bytes = 2 * wl.num_kv_heads * wl.head_dim * elt
+    cu = wl.cu_branches
+    per_seq_branch_tokens = np.add.reduceat(base_len, cu[:-1]).astype(np.int64)
+    T = wl.prefix_len.astype(np.int64) + per_seq_branch_tokens
+    bytes_of, tokens_of = {}, {}
+    Tn = T.copy()
+    for c in calls:
+        kind = c[0]
+        if kind == "merge":
+            continue
+        if kind == "chunk":
+            Tn = Tn + C * wl.num_branches
+            nq = C * NB
+        elif kind == "parallel":
+            Tn = Tn + wl.num_branches
+            nq = NB
+        else:
+            Tn = Tn + 1
+            nq = B
+        b = int(Tn.sum()) * kv_tok_bytes + 2 * nq * wl.num_q_heads * wl.head_dim * elt \
+            + 4 * int(((Tn + 15) // 16).sum()) + (0 if kind == "serial" else int((Tn - wl.prefix_len).sum()))
+        bytes_of.setdefault(kind, []).append(b)
+        tokens_of.setdefault(kind, []).append(nq)
+    step_tokens = sum(sum(v) for v in tokens_of.values())
+
+    # ---- timed region
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed / args.steps * 1e3
+    assert int(state.fault.item()) == 0
+
+    # ---- per-call durations with events on the launch stream (second pass, same work)
+    events = []
+    for _ in range(args.steps):
+        one_step(events)
+    torch.cuda.synchronize()
+    dur = {}
+    for kind, e0, e1 in events:
+        dur.setdefault(kind, []).append(e0.elapsed_time(e1) * 1e-3)
+    per_call = {}
+    for kind, ds in dur.items():
+        avg = float(np.mean(ds))
+        bts = float(np.mean(bytes_of[kind]))
+        per_call[kind] = {"launches_per_step": len(bytes_of[kind]), "avg_us": round(avg * 1e6, 2),
+                          "min_us": round(float(np.min(ds)) * 1e6, 2),
+                          "query_tokens_per_launch": int(np.mean(tokens_of[kind])),
+                          "query_tokens_per_s": round(float(np.mean(tokens_of[kind])) / avg, 1),
+                          "algorithmic_MB": round(bts / 1e6, 3), "GBps": round(bts / avg / 1e9, 1),
+                          "frac_of_8TBps": round(bts / avg / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # the dominant kernel: the streaming decode launches (parallel + serial share one kernel)
+    dom = [k for k in ("parallel", "serial") if k in dur]
+    dom_time = sum(sum(dur[k]) for k in dom)
+    dom_launches = sum(len(dur[k]) for k in dom)
+    dom_bytes = sum(float(np.mean(bytes_of[k])) * len(dur[k]) for k in dom)
+    achieved = dom_bytes / dom_time / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel (parallel + serial decode launches)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "avg_launch_us": round(dom_time / dom_launches * 1e6, 2),
+                "algorithmic_bytes_per_launch": int(dom_bytes / dom_launches)}
+
+    # ---- CPU baseline: the oracle on the parallel-decode call of this workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl, base_len, C, np)
+
+    line = {"metric": "query tokens/s through the ASPD attention hot path, one attention layer "
+                      "(branch-query tokens/s of the parallel-decode call in per_call.parallel)",
+            "value": round(step_tokens / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+            "data": "synthetic", "config": {"workload": f"{args.workload}: {spec['what']}",
+                                           "query_tokens_per_step": int(step_tokens), "B": B, "NB": NB,
+                                           "kv_tokens": int(T.sum())},
+            "per_call": per_call, "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+def cpu_baseline(wl, base_len, chunk, np):
+    """The oracle as it stands, timed on this host for the parallel-decode call of the workload."""
+    import aspd_workloads as W
+    from oracle import TokenTable, attend
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    tt = TokenTable(wl.block_tables, wl.block_size)
+    tt.append_serial(wl.prefix_len)
+    tt.open_parallel(wl.num_branches)
+    target = base_len + chunk
+    # replay cheaply: one multi-token append per branch gives the same token set per branch; the
+    # arrangement differs from the interleaved one but the oracle's cost and result shape do not
+    tt.append_parallel(target)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    t0 = time.perf_counter()
+    meta = tt.append_parallel(ones)
+    q = wl.draw_q(meta.NQ)
+    rows = None
+    if meta.NQ > 48:  # bound the work: a seeded sample of the rows
+        rows = np.sort(np.random.default_rng(1).choice(meta.NQ, size=48, replace=False))
+    attend(tt, meta, q, wl.k_cache, wl.v_cache, rows=rows)
+    dt = time.perf_counter() - t0
+    n = meta.NQ if rows is None else len(rows)
+    return {"value": round(n / dt, 3), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"parallel-decode call: {n} of {meta.NQ} branch queries x {wl.num_q_heads} heads, "
+                      f"metadata + float64 dense-mask attention, {dt:.1f}s"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())
