@@ -51,6 +51,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cycle4", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is one-GPU only (the path shards by sequence or KV head without "
@@ -101,19 +102,19 @@ def main() -> int:
     ws = A.new_workspace(kv, B, max(C * NB, NB, B))
     calls = []  # (kind, stage, new_len_d, step, q, out, fn)
     if C:
-        calls.append(("chunk", A.STAGE_PARALLEL, dev_i32(np.full(NB, C)), A.Step(C * NB, NB, B, dev),
+        calls.append(("chunk", A.STAGE_PARALLEL, dev_i32(np.full(NB, C)), A.Step(C * NB, NB, B, dev, max_new_per_seq=int(C * wl.num_branches.max())),
                       rand_q(C * NB), A.aspd_attn_branch_chunk))
-    calls.append(("parallel", A.STAGE_PARALLEL, dev_i32(np.ones(NB)), A.Step(NB, NB, B, dev), rand_q(NB),
+    calls.append(("parallel", A.STAGE_PARALLEL, dev_i32(np.ones(NB)), A.Step(NB, NB, B, dev, max_new_per_seq=int(wl.num_branches.max())), rand_q(NB),
                   A.aspd_attn_parallel_decode))
     if S:
         calls.append(("merge", A.STAGE_MERGE, None, None, None, None))
         ones_b = dev_i32(np.ones(B))
         for _ in range(S):
-            calls.append(("serial", A.STAGE_SERIAL, ones_b, A.Step(B, B, B, dev), rand_q(B),
+            calls.append(("serial", A.STAGE_SERIAL, ones_b, A.Step(B, B, B, dev, max_new_per_seq=1), rand_q(B),
                           A.aspd_attn_serial_decode))
     outs = {id(c): (torch.empty_like(c[4]) if c[4] is not None else None) for c in calls}
 
-    def one_step(events=None):
+    def one_step(snaps=None):
         for dst, src in zip(live, snap):
             dst.copy_(src)
         for c in calls:
@@ -121,13 +122,9 @@ def main() -> int:
             A.aspd_build_branch_meta(kv, state, stage, new_len, step=step)
             if fn is None:
                 continue
-            if events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
+            if snaps is not None and kind not in snaps:   # state as the first call of this kind sees it
+                snaps[kind] = ([t.clone() for t in live], c)
             fn(kv, state, step, q, ws, out=outs[id(c)])
-            if events is not None:
-                e1.record()
-                events.append((kind, e0, e1))
 
     # ---- algorithmic bytes of every attention call (unique visible KV + Q and O + tables + tags)
     elt = 2 if wl.dtype == "bf16" else 4
@@ -156,32 +153,80 @@ def main() -> int:
         tokens_of.setdefault(kind, []).append(nq)
     step_tokens = sum(sum(v) for v in tokens_of.values())
 
+    # ---- the step as a HIP graph (every call only enqueues kernels on the current stream, so the
+    # whole step is capturable); replay must reproduce the eager outputs exactly
+    snaps = {}
+    one_step(snaps)
+    torch.cuda.synchronize()
+    eager_out = {k: v.clone() for k, v in outs.items() if v is not None}
+    run_step = one_step
+    graph = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            one_step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            one_step()
+        for v in outs.values():
+            if v is not None:
+                v.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in eager_out.items():
+            assert torch.equal(outs[k], v), "graph replay differs from the eager step"
+        run_step = graph.replay
+
     # ---- timed region
     for _ in range(args.warmup):
-        one_step()
+        run_step()
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for _ in range(args.steps):
-        one_step()
+        run_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed / args.steps * 1e3
     assert int(state.fault.item()) == 0
 
-    # ---- per-call durations with events on the launch stream (second pass, same work)
-    events = []
-    for _ in range(args.steps):
-        one_step(events)
-    torch.cuda.synchronize()
-    dur = {}
-    for kind, e0, e1 in events:
-        dur.setdefault(kind, []).append(e0.elapsed_time(e1) * 1e-3)
-    per_call = {}
-    for kind, ds in dur.items():
-        avg = float(np.mean(ds))
+    # ---- average launch duration of each kind of attention call: REP back-to-back launches of the
+    # call (state restored to what that call sees), captured once, timed with events on the
+    # launch stream
+    REP = 20
+    per_call, dur = {}, {}
+    for kind, (st_snap, c) in snaps.items():
+        _, stage, new_len, step, q, fn = c
+
+        def body():
+            for dst, src in zip(live, st_snap):
+                dst.copy_(src)
+            for _ in range(REP):
+                fn(kv, state, step, q, ws, out=outs[id(c)])
+
+        body()
+        runner = body
+        if not args.no_graph:
+            gk = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gk):
+                body()
+            runner = gk.replay
+        runner()
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            runner()
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1) * 1e-3 / REP)
+        avg = float(np.mean(times))
+        dur[kind] = avg
         bts = float(np.mean(bytes_of[kind]))
         per_call[kind] = {"launches_per_step": len(bytes_of[kind]), "avg_us": round(avg * 1e6, 2),
-                          "min_us": round(float(np.min(ds)) * 1e6, 2),
+                          "min_us": round(float(np.min(times)) * 1e6, 2),
                           "query_tokens_per_launch": int(np.mean(tokens_of[kind])),
                           "query_tokens_per_s": round(float(np.mean(tokens_of[kind])) / avg, 1),
                           "algorithmic_MB": round(bts / 1e6, 3), "GBps": round(bts / avg / 1e9, 1),
@@ -189,9 +234,9 @@ def main() -> int:
 
     # the dominant kernel: the streaming decode launches (parallel + serial share one kernel)
     dom = [k for k in ("parallel", "serial") if k in dur]
-    dom_time = sum(sum(dur[k]) for k in dom)
-    dom_launches = sum(len(dur[k]) for k in dom)
-    dom_bytes = sum(float(np.mean(bytes_of[k])) * len(dur[k]) for k in dom)
+    dom_launches = sum(len(bytes_of[k]) for k in dom)
+    dom_time = sum(dur[k] * len(bytes_of[k]) for k in dom)
+    dom_bytes = sum(float(np.sum(bytes_of[k])) for k in dom)
     achieved = dom_bytes / dom_time / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -216,7 +261,7 @@ def main() -> int:
             "value": round(step_tokens / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
-            "data": "synthetic", "config": {"workload": f"{args.workload}: {spec['what']}",
+            "data": "synthetic", "launch": "eager" if args.no_graph else "hip_graph", "config": {"workload": f"{args.workload}: {spec['what']}",
                                            "query_tokens_per_step": int(step_tokens), "B": B, "NB": NB,
                                            "kv_tokens": int(T.sum())},
             "per_call": per_call, "roofline": roofline, "cpu_baseline": cpu}

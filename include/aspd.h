@@ -110,6 +110,9 @@ typedef struct aspd_state {
  * q_d / out_d of the attention call that follows. */
 typedef struct aspd_step {
   int32_t  NQ;              /* host: total tokens appended (sum of new_len)                        */
+  int32_t  max_new_per_seq; /* host: upper bound of the tokens this step appends to any ONE sequence,
+                               0 = unknown.  A tuning hint for the attention calls only (it sizes the
+                               row tile); results do not depend on it, even when it is wrong.        */
   int32_t* cu_new_d;        /* [NB+1] (PARALLEL) or [B+1] (SERIAL): first row of each branch / sequence */
   int32_t* cu_seq_new_d;    /* [B+1] first row of each sequence                                    */
   int32_t* q_seq_d;         /* [NQ] sequence of the token                                          */
@@ -135,6 +138,13 @@ ASPD_API int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int32_
 /* Bytes of device scratch the attention calls need for partial softmax results of split key
  * ranges (host-only computation, needs no GPU).  Returns 0 on invalid arguments. */
 ASPD_API size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ);
+
+/* Prepares a freshly allocated workspace (256-byte aligned, at least aspd_workspace_bytes): enqueues
+ * a small kernel that clears the arrival counters at its head.  Call once after allocation, on the
+ * stream (or ordered before the stream) of the first attention call.  Attention calls leave the
+ * counters cleared, so one workspace serves any number of calls, one at a time: two attention
+ * calls that run concurrently must not share a workspace. */
+ASPD_API int aspd_workspace_init(void* workspace_d, size_t workspace_bytes, void* stream);
 
 /* Sec. 3.2 Eq. 1-3, "The Parallel Branch's Perspective"; Sec. 3.3.  One new token per active branch
  * (the step built with ASPD_STAGE_PARALLEL and new_len in {0,1}): row r attends slots

@@ -21,7 +21,7 @@ STAGE_PARALLEL, STAGE_SERIAL, STAGE_MERGE = 0, 1, 2
 POS_SAME_SEQ = 0
 FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES = 1, 2, 4, 8
 
-EXPORTS = ("aspd_build_branch_meta", "aspd_workspace_bytes", "aspd_attn_parallel_decode",
+EXPORTS = ("aspd_build_branch_meta", "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
            "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_status_string")
 
 
@@ -39,7 +39,7 @@ class aspd_state(C.Structure):
 
 
 class aspd_step(C.Structure):
-    _fields_ = [("NQ", C.c_int32), ("cu_new_d", C.c_void_p), ("cu_seq_new_d", C.c_void_p),
+    _fields_ = [("NQ", C.c_int32), ("max_new_per_seq", C.c_int32), ("cu_new_d", C.c_void_p), ("cu_seq_new_d", C.c_void_p),
                 ("q_seq_d", C.c_void_p), ("q_branch_d", C.c_void_p), ("position_ids_d", C.c_void_p),
                 ("logical_slot_d", C.c_void_p), ("slot_mapping_d", C.c_void_p), ("kv_len_d", C.c_void_p)]
 
@@ -70,6 +70,8 @@ def lib() -> C.CDLL:
             fn.restype = C.c_int
             fn.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_state), C.POINTER(aspd_step), C.c_void_p,
                            C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.aspd_workspace_init.restype = C.c_int
+        L.aspd_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.aspd_status_string.restype = C.c_char_p
         L.aspd_status_string.argtypes = [C.c_int]
         _lib = L
@@ -136,8 +138,9 @@ class BatchState:
 class Step:
     """Outputs of one aspd_build_branch_meta call (device arrays sized for NQ rows)."""
 
-    def __init__(self, NQ: int, n_cu: int, B: int, device):
+    def __init__(self, NQ: int, n_cu: int, B: int, device, max_new_per_seq: int = 0):
         self.NQ = int(NQ)
+        self.max_new_per_seq = int(max_new_per_seq)   # tuning hint, 0 = unknown
         i32 = dict(dtype=torch.int32, device=device)
         n = max(self.NQ, 1)
         self.cu_new = torch.zeros(n_cu + 1, **i32)
@@ -150,13 +153,14 @@ class Step:
         self.kv_len = torch.zeros(n, **i32)
 
     def struct(self) -> aspd_step:
-        return aspd_step(self.NQ, _ptr(self.cu_new), _ptr(self.cu_seq_new), _ptr(self.q_seq), _ptr(self.q_branch),
+        return aspd_step(self.NQ, self.max_new_per_seq, _ptr(self.cu_new), _ptr(self.cu_seq_new), _ptr(self.q_seq), _ptr(self.q_branch),
                          _ptr(self.position_ids), _ptr(self.logical_slot), _ptr(self.slot_mapping),
                          _ptr(self.kv_len))
 
 
 def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: torch.Tensor | None,
-                           NQ: int = 0, step: Step | None = None, stream=None) -> Step | None:
+                           NQ: int = 0, step: Step | None = None, stream=None,
+                           max_new_per_seq: int = 0) -> Step | None:
     """See aspd.h.  `NQ` = sum of new_len, known to the caller.  Returns the Step (None for MERGE)."""
     kvs, sts = kv.struct(), state.struct()
     if stage == STAGE_MERGE:
@@ -166,7 +170,8 @@ def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: 
             raise AspdError(rc, "aspd_build_branch_meta")
         return None
     if step is None:
-        step = Step(NQ, state.NB if stage == STAGE_PARALLEL else state.B, state.B, state.device)
+        step = Step(NQ, state.NB if stage == STAGE_PARALLEL else state.B, state.B, state.device,
+                    max_new_per_seq)
     sps = step.struct()
     rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, POS_SAME_SEQ, _ptr(new_len),
                                       C.byref(sps), _stream(stream))
@@ -204,6 +209,15 @@ def aspd_attn_serial_decode(kv, state, step, q, workspace, out=None, lse=None, s
     return _attn("aspd_attn_serial_decode", kv, state, step, q, out, lse, sm_scale, workspace, stream)
 
 
+def aspd_workspace_init(workspace: torch.Tensor, stream=None) -> None:
+    rc = lib().aspd_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if rc != OK:
+        raise AspdError(rc, "aspd_workspace_init")
+
+
 def new_workspace(kv: KVCache, B: int, NQ: int) -> torch.Tensor:
-    """Device scratch of the size the attention calls ask for (256-byte aligned by the allocator)."""
-    return torch.empty(aspd_workspace_bytes(kv, B, NQ), dtype=torch.uint8, device=kv.k.device)
+    """Device scratch of the size the attention calls ask for (256-byte aligned by the allocator),
+    prepared with aspd_workspace_init."""
+    ws = torch.empty(aspd_workspace_bytes(kv, B, NQ), dtype=torch.uint8, device=kv.k.device)
+    aspd_workspace_init(ws)
+    return ws

@@ -14,7 +14,8 @@
 // (the active branches of the sequence times the query heads of the KV-head's group) are processed
 // against a KV page while it is in the workgroup's LDS, so the shared prefix is fetched once for all
 // branches.  A segment that covers its item completely writes the output; otherwise it writes an
-// unnormalised partial (running max, sum, accumulator) and a second kernel combines the partials.
+// unnormalised partial (running max, sum, accumulator); the workgroup that delivers the last partial
+// of an item combines them, in the same launch.
 #include <algorithm>
 #include <cmath>
 #include <mutex>
@@ -31,14 +32,18 @@ constexpr int NT_MAX = 3;             // 16-row MFMA tiles per row group (bf16 p
 constexpr int BF16_ROWS = 16 * NT_MAX;
 constexpr int F32_ROWS = 4;           // rows per row group (fp32 vector path)
 constexpr int MIN_PAGES_PER_WG = 16;  // do not split finer than this
+constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
 constexpr int MAX_WG = 1024;          // upper bound of the grid (workspace is sized for it)
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+constexpr float LAZY = 6.f;           // log2 slack of the running softmax reference (bf16 path)
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // 16 bytes in registers (a native
+                                                                  // vector, so arrays of it stay in VGPRs)
 
 struct AttnArgs {
   KvView         kv;
@@ -53,7 +58,8 @@ struct AttnArgs {
   const void*    q;
   void*          out;
   float*         lse;
-  float*         partial;       // [2 * nwg][rows_per_group][D + 2]
+  float*         partial;       // [2 * nwg][rows_per_group][D + 4]: accumulator, running max, sum, pad
+  int*           counters;      // [nwg] arrivals per split item, zero between calls
   float          scale_log2;    // sm_scale * log2(e)
   int            B;
   int            nwg;
@@ -144,10 +150,20 @@ __device__ Item locate(const AttnArgs& a, const int* cu_units, int u, int* page)
 }
 
 __device__ __forceinline__ float* partial_slot(const AttnArgs& a, int wg, int starts_item, int D) {
-  return a.partial + ((long)(2 * wg + starts_item)) * a.rows_cap * (D + 2);
+  return a.partial + ((long)(2 * wg + starts_item)) * a.rows_cap * (D + 4);
 }
 
 __device__ __forceinline__ float exp2_safe_ref(float m) { return (m == -INFINITY) ? 0.f : m; }
+
+// Partials travel between workgroups that may sit on different XCDs, whose L2 caches are not kept
+// coherent for ordinary accesses.  Device-scope relaxed atomic stores write through and device-scope
+// atomic loads read past the local L2, so no cache write-back or invalidate is needed on this path.
+__device__ __forceinline__ void store_device_scope(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_device_scope(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // ---------------------------------------------------------------------------------------------
 // bf16 path: MFMA 16x16x32, transposed scores.
@@ -162,6 +178,7 @@ struct Bf16Cfg {
   static constexpr int CH = D / 8;              // 16-byte chunks per row
   static constexpr int PAGE_U4 = 16 * CH;       // uint4 per page
   static constexpr int LPP = PAGE_U4 / 64;      // loads per page per lane
+  static constexpr int RPL = 64 / CH;           // rows of a page one load covers
   static constexpr int KSTEPS = D / 32;
   static constexpr int MT = D / 16;
   static constexpr int STAGE_BYTES = 4 * PAGE_U4 * 16;  // K0 K1 V0 V1
@@ -174,35 +191,71 @@ __device__ __forceinline__ int v_swz(int row, int chunk) {
   return row * Bf16Cfg<D>::CH + ((((chunk >> 1) ^ (row & 3)) << 1) | (chunk & 1));
 }
 
+// One pair of pages in flight: K page 0, K page 1, V page 0, V page 1.
+template <int D>
+struct PairRegs {
+  u32x4 r[4][Bf16Cfg<D>::LPP];
+};
+
+template <int D>
+__device__ __forceinline__ void issue_pair(PairRegs<D>& pr, const AttnArgs& a, int h, int b0, int b1, int lane) {
+  using C = Bf16Cfg<D>;
+  const long o0 = ((long)b0 * a.kv.num_kv_heads + h) * C::PAGE_U4 + lane;
+  const long o1 = ((long)b1 * a.kv.num_kv_heads + h) * C::PAGE_U4 + lane;
+  const u32x4* k0 = (const u32x4*)a.kv.k + o0;
+  const u32x4* k1 = (const u32x4*)a.kv.k + o1;
+  const u32x4* v0 = (const u32x4*)a.kv.v + o0;
+  const u32x4* v1 = (const u32x4*)a.kv.v + o1;
+#pragma unroll
+  for (int i = 0; i < C::LPP; ++i) {
+    pr.r[0][i] = k0[i * 64];
+    pr.r[1][i] = k1[i * 64];
+    pr.r[2][i] = v0[i * 64];
+    pr.r[3][i] = v1[i * 64];
+  }
+}
+
+// Block ids of a wave's pairs: lane i holds the id of page (i & 1) of the wave's pair number
+// jbase + i / 2, so one gather serves 32 iterations.
+__device__ __forceinline__ int block_window(const AttnArgs& a, const int* bt, int page0, int page1, int wave,
+                                            int jbase, int lane) {
+  const int jj = jbase + (lane >> 1);
+  int P = page0 + 2 * (wave + NW * jj) + (lane & 1);
+  P = min(P, page1 - 1);
+  const int b = bt[P];
+  return min(max(b, 0), a.kv.num_blocks - 1);
+}
+
 template <int D, int NT>
 __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
                              bool complete, float* pslot) {
   using C = Bf16Cfg<D>;
+  constexpr int ROWS = 16 * NT;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 15;
   const int g = lane >> 4;
   const int R = it.nq * a.G;
 
-  uint4* stage = (uint4*)(smem + wave * C::STAGE_BYTES);                // this wave's K0 K1 V0 V1
-  uint4* qtile = (uint4*)(smem + NW * C::STAGE_BYTES);                  // [BF16_ROWS][CH] swizzled
-  int* rowslot = (int*)(smem + NW * C::STAGE_BYTES + BF16_ROWS * D * 2);
-  int* rowtag = rowslot + BF16_ROWS;
-  float* wm = (float*)(rowtag + BF16_ROWS);                             // [NW][BF16_ROWS]
-  float* wl = wm + NW * BF16_ROWS;
+  u32x4* stage = (u32x4*)(smem + wave * C::STAGE_BYTES);                // this wave's K0 K1 V0 V1
+  u32x4* qtile = (u32x4*)(smem + NW * C::STAGE_BYTES);                  // [ROWS][CH] swizzled
+  int* rowslot = (int*)(smem + NW * C::STAGE_BYTES + ROWS * D * 2);
+  int* rowtag = rowslot + ROWS;
+  float* wm = (float*)(rowtag + ROWS);                                  // [NW][ROWS]
+  float* wl = wm + NW * ROWS;
 
   __syncthreads();  // LDS of the previous segment is free
   // ---- Q tile and row descriptors into LDS (padding rows repeat the last row)
-  for (int i = tid; i < 16 * NT * C::CH; i += THREADS) {
+  for (int i = tid; i < ROWS * C::CH; i += THREADS) {
     const int r = i / C::CH, ch = i - r * C::CH;
     const int rr = min(r, R - 1);
     const int q = it.q0 + rr / a.G;
     const int head = it.h * a.G + rr % a.G;
-    const uint4* src = (const uint4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + ch;
+    const u32x4* src = (const u32x4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + ch;
     qtile[k_swz<D>(r, ch)] = *src;
   }
-  if (tid < 16 * NT) {
+  if (tid < ROWS) {
     const int rr = min(tid, R - 1);
     const int q = it.q0 + rr / a.G;
     rowslot[tid] = a.logical_slot[q];
@@ -221,6 +274,23 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   }
 #pragma unroll
   for (int off = 1; off < 16; off <<= 1) mask_from = min(mask_from, __shfl_xor(mask_from, off));
+  mask_from = __builtin_amdgcn_readfirstlane(mask_from);
+
+  // LDS addressing: every swizzled position used in the loop is one of a few lane-dependent bases
+  // plus a compile-time offset (which the LDS instructions carry as an immediate).
+  //   stage writes: lane owns 16-byte chunk (lane % CH) of row (lane / CH) + i * RPL
+  const int wrow = lane / C::CH, wch = lane % C::CH;
+  const int kw_lo = k_swz<D>(wrow, wch);                 // rows whose bit 2 equals wrow's
+  const int kw_hi = k_swz<D>(wrow ^ 4, wch) - 4 * C::CH;  // rows with bit 2 flipped, same row base
+  const int vw = v_swz<D>(wrow, wch);                    // V swizzle depends on row & 3 only
+  //   K / Q operand reads: row c, chunk 4t + g; t even and t odd differ in bit 2 of the chunk
+  const int kr_even = k_swz<D>(c, g);
+  const int kr_odd = k_swz<D>(c, 4 + g);
+  //   V transpose reads in 8-byte units: key 4g + c/4, d-tile mt swizzled by (key & 3) in its low 2 bits
+  const int vkey = 4 * g + (c >> 2);
+  int vu[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) vu[b] = vkey * (D / 4) + (((b ^ (vkey & 3)) << 2) | (c & 3));
 
   f32x4 acc[NT][C::MT];
   float m_run[NT], l_run[NT];
@@ -232,71 +302,91 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     for (int mt = 0; mt < C::MT; ++mt) acc[n][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  // This wave's pairs are wave, wave + NW, ...; `j` counts them.
   const int npairs = (page1 - page0 + 1) >> 1;
-  const long bt_base = (long)it.s * a.kv.max_blocks_per_seq;
+  const int my_pairs = (npairs > wave) ? (npairs - wave + NW - 1) / NW : 0;
+  const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
   const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
 
-  auto page_ptrs = [&](int pair, const uint4*& k0, const uint4*& k1, const uint4*& v0, const uint4*& v1) {
-    const int P0 = page0 + 2 * pair;
-    const int P1 = min(P0 + 1, page1 - 1);
-    int b0 = __builtin_amdgcn_readfirstlane(a.kv.block_tables[bt_base + P0]);
-    int b1 = __builtin_amdgcn_readfirstlane(a.kv.block_tables[bt_base + P1]);
-    b0 = min(max(b0, 0), a.kv.num_blocks - 1);
-    b1 = min(max(b1, 0), a.kv.num_blocks - 1);
-    const long o0 = ((long)b0 * a.kv.num_kv_heads + it.h) * C::PAGE_U4;
-    const long o1 = ((long)b1 * a.kv.num_kv_heads + it.h) * C::PAGE_U4;
-    k0 = (const uint4*)a.kv.k + o0; v0 = (const uint4*)a.kv.v + o0;
-    k1 = (const uint4*)a.kv.k + o1; v1 = (const uint4*)a.kv.v + o1;
-  };
+  int blk_cur = 0, blk_next = 0;
+  if (my_pairs > 0) blk_cur = block_window(a, bt, page0, page1, wave, 0, lane);
+  if (my_pairs > 32) blk_next = block_window(a, bt, page0, page1, wave, 32, lane);
 
-  uint4 ld[4][C::LPP];  // in-flight page pair: K0 K1 V0 V1
-  auto issue = [&](int pair) {
-    const uint4 *k0, *k1, *v0, *v1;
-    page_ptrs(pair, k0, k1, v0, v1);
-#pragma unroll
-    for (int i = 0; i < C::LPP; ++i) {
-      ld[0][i] = k0[i * 64 + lane];
-      ld[1][i] = k1[i * 64 + lane];
-      ld[2][i] = v0[i * 64 + lane];
-      ld[3][i] = v1[i * 64 + lane];
-    }
-  };
+  PairRegs<D> pr;
+  if (my_pairs > 0)
+    issue_pair<D>(pr, a, it.h, __builtin_amdgcn_readlane(blk_cur, 0), __builtin_amdgcn_readlane(blk_cur, 1), lane);
 
-  if (wave < npairs) issue(wave);
-  for (int pair = wave; pair < npairs; pair += NW) {
+  for (int j = 0; j < my_pairs; ++j) {
+    const int pair = wave + NW * j;
     // ---- registers -> this wave's LDS stage (swizzled)
 #pragma unroll
     for (int i = 0; i < C::LPP; ++i) {
-      const int idx = i * 64 + lane;
-      const int row = idx / C::CH, ch = idx % C::CH;
-      stage[0 * C::PAGE_U4 + k_swz<D>(row, ch)] = ld[0][i];
-      stage[1 * C::PAGE_U4 + k_swz<D>(row, ch)] = ld[1][i];
-      stage[2 * C::PAGE_U4 + v_swz<D>(row, ch)] = ld[2][i];
-      stage[3 * C::PAGE_U4 + v_swz<D>(row, ch)] = ld[3][i];
+      // load i of a page is rows i*RPL.. of it: the swizzled position is one of two lane-dependent
+      // bases plus a compile-time offset
+      const int kw = ((i * C::RPL) & 4) ? kw_hi : kw_lo;
+      stage[0 * C::PAGE_U4 + i * 64 + kw] = pr.r[0][i];
+      stage[1 * C::PAGE_U4 + i * 64 + kw] = pr.r[1][i];
+      stage[2 * C::PAGE_U4 + i * 64 + vw] = pr.r[2][i];
+      stage[3 * C::PAGE_U4 + i * 64 + vw] = pr.r[3][i];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (pair + NW < npairs) issue(pair + NW);  // next pair streams in while this one is computed
+    // ---- the next pair streams in while this one is computed
+    if (j + 1 < my_pairs) {
+      const int jn = j + 1;
+      if ((jn & 31) == 0) {
+        blk_cur = blk_next;
+        if (jn + 32 < my_pairs) blk_next = block_window(a, bt, page0, page1, wave, jn + 32, lane);
+      }
+      const int li = __builtin_amdgcn_readfirstlane((jn & 31) * 2);
+      issue_pair<D>(pr, a, it.h, __builtin_amdgcn_readlane(blk_cur, li), __builtin_amdgcn_readlane(blk_cur, li + 1),
+                    lane);
+    }
 
     const int P0 = page0 + 2 * pair;
     const bool second_valid = (P0 + 1) < page1;
 
-    // ---- S^T = K Q^T for both pages
+    // ---- S^T = K Q^T for both pages.  LDS operands are fetched KB k-steps (VB d-tiles below) at a
+    // time: large batches hide the LDS latency, small ones leave registers to wide row groups.
+    constexpr int KB = (NT == 1) ? C::KSTEPS : (NT == 2 ? 2 : 1);
+    constexpr int VB = (NT == 1) ? C::MT : (NT == 2 ? 4 : 2);
     f32x4 st[2][NT];
 #pragma unroll
-    for (int p = 0; p < 2; ++p)
+    for (int n = 0; n < NT; ++n) {
+      st[0][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+      st[1][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 #pragma unroll
-      for (int n = 0; n < NT; ++n) st[p][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t0 = 0; t0 < C::KSTEPS; t0 += KB) {
+      bf16x8 ka[KB], kb[KB];
 #pragma unroll
-    for (int t = 0; t < C::KSTEPS; ++t) {
-      const bf16x8 ka = *(const bf16x8*)&stage[0 * C::PAGE_U4 + k_swz<D>(c, 4 * t + g)];
-      const bf16x8 kb = *(const bf16x8*)&stage[1 * C::PAGE_U4 + k_swz<D>(c, 4 * t + g)];
+      for (int tt = 0; tt < KB; ++tt) {
+        const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
+        ka[tt] = *(const bf16x8*)&stage[0 * C::PAGE_U4 + kr];
+        kb[tt] = *(const bf16x8*)&stage[1 * C::PAGE_U4 + kr];
+      }
 #pragma unroll
       for (int n = 0; n < NT; ++n) {
-        const bf16x8 qb = *(const bf16x8*)&qtile[k_swz<D>(16 * n + c, 4 * t + g)];
-        st[0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb, st[0][n], 0, 0, 0);
-        st[1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qb, st[1][n], 0, 0, 0);
+#pragma unroll
+        for (int tt = 0; tt < KB; ++tt) {
+          const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
+          const bf16x8 qb = *(const bf16x8*)&qtile[16 * n * C::CH + kr];
+          st[0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[tt], qb, st[0][n], 0, 0, 0);
+          st[1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[tt], qb, st[1][n], 0, 0, 0);
+        }
       }
+    }
+
+    // ---- V^T operands through the LDS transpose read; the first batch is issued ahead of the
+    // softmax so that its latency is hidden
+    const s16x4* vs0 = (const s16x4*)(stage + 2 * C::PAGE_U4);
+    const s16x4* vs1 = (const s16x4*)(stage + 3 * C::PAGE_U4);
+#define ASPD_V_UNIT(mt) (vu[(mt) & 3] + 16 * ((mt) >> 2))
+    s16x4 va[VB], vb[VB];
+#pragma unroll
+    for (int mm = 0; mm < VB; ++mm) {
+      va[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs0 + ASPD_V_UNIT(mm)));
+      vb[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs1 + ASPD_V_UNIT(mm)));
     }
 
     // ---- mask (only pages that reach into the branch region or the tail need it)
@@ -308,73 +398,80 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
       own1 = *(const uint32_t*)(owner_row + min(slot0 + ASPD_BLOCK, a.owner_stride - 4));
     }
 
+    // Running softmax with a lazily updated reference: m_run[n] is a per-row reference exponent
+    // (log2 domain, scaled scores), not necessarily the row maximum.  It is raised, and the
+    // accumulators rescaled, only when a score exceeds it by more than LAZY (weights then stay
+    // below 2^LAZY, harmless in fp32 and in the bf16 P operand, whose precision is relative).
+    // The four lanes of a row always hold the same reference.
     s16x8 pb[NT];
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
       float sc[8];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        sc[e] = st[0][n][e] * a.scale_log2;
-        sc[4 + e] = st[1][n][e] * a.scale_log2;
+        sc[e] = st[0][n][e];
+        sc[4 + e] = st[1][n][e];
       }
       if (need_mask) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const int j = slot0 + (e & 3) + (e >> 2) * ASPD_BLOCK;
+          const int jk = slot0 + (e & 3) + (e >> 2) * ASPD_BLOCK;
           const int own = (int)(((e < 4 ? own0 : own1) >> (8 * (e & 3))) & 0xff);
-          bool vis = (j <= my_slot[n]) && (j < L || my_tag[n] == 0 || own == my_tag[n]);
+          bool vis = (jk <= my_slot[n]) && (jk < L || my_tag[n] == 0 || own == my_tag[n]);
           if (e >= 4 && !second_valid) vis = false;
           sc[e] = vis ? sc[e] : -INFINITY;
         }
       }
-      float mx = sc[0];
-#pragma unroll
-      for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sc[e]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[n], mx);
-      const float m_ref = exp2_safe_ref(m_new);
-      const float alpha = exp2f(m_run[n] - m_ref);
-      m_run[n] = m_new;
-      float psum = 0.f;
-      float pr[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        pr[e] = exp2f(sc[e] - m_ref);
-        psum += pr[e];
-      }
-      l_run[n] = l_run[n] * alpha + psum;
-      if (__any(alpha != 1.f)) {
+      float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+      mx *= a.scale_log2;  // scale > 0: the maximum commutes with it
+      if (__any(mx > m_run[n] + LAZY)) {
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[n], mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[n] - exp2_safe_ref(m_new));
+        m_run[n] = m_new;
+        l_run[n] *= alpha;
 #pragma unroll
         for (int mt = 0; mt < C::MT; ++mt) acc[n][mt] *= alpha;
       }
+      const float neg_ref = -exp2_safe_ref(m_run[n]);
+      float psum = 0.f;
       bf16x8 pv;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pv[e] = (__bf16)pr[e];
+      for (int e = 0; e < 8; ++e) {
+        const float w = __builtin_amdgcn_exp2f(fmaf(sc[e], a.scale_log2, neg_ref));
+        psum += w;
+        pv[e] = (__bf16)w;
+      }
+      l_run[n] += psum;
       pb[n] = __builtin_bit_cast(s16x8, pv);
     }
 
     // ---- O^T += V^T P^T
-    const s16x4* vs0 = (const s16x4*)(stage + 2 * C::PAGE_U4);
-    const s16x4* vs1 = (const s16x4*)(stage + 3 * C::PAGE_U4);
-    const int vkey = 4 * g + (c >> 2);
 #pragma unroll
-    for (int mt = 0; mt < C::MT; ++mt) {
-      // 8-byte units: a row has D/4 of them; 32-byte chunk mt is swizzled by the key
-      const int unit = vkey * (D / 4) + (((mt ^ (vkey & 3)) << 2) | (c & 3));
-      const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4*)(vs0 + unit));
-      const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-          (__attribute__((address_space(3))) s16x4*)(vs1 + unit));
-      s16x8 v8;
-      v8[0] = va[0]; v8[1] = va[1]; v8[2] = va[2]; v8[3] = va[3];
-      v8[4] = vb[0]; v8[5] = vb[1]; v8[6] = vb[2]; v8[7] = vb[3];
-      const bf16x8 vop = __builtin_bit_cast(bf16x8, v8);
+    for (int m0 = 0; m0 < C::MT; m0 += VB) {
+      if (m0 > 0) {
 #pragma unroll
-      for (int n = 0; n < NT; ++n)
-        acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, __builtin_bit_cast(bf16x8, pb[n]),
-                                                             acc[n][mt], 0, 0, 0);
+        for (int mm = 0; mm < VB; ++mm) {
+          va[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(vs0 + ASPD_V_UNIT(m0 + mm)));
+          vb[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(vs1 + ASPD_V_UNIT(m0 + mm)));
+        }
+      }
+#pragma unroll
+      for (int mm = 0; mm < VB; ++mm) {
+        s16x8 v8;
+        v8[0] = va[mm][0]; v8[1] = va[mm][1]; v8[2] = va[mm][2]; v8[3] = va[mm][3];
+        v8[4] = vb[mm][0]; v8[5] = vb[mm][1]; v8[6] = vb[mm][2]; v8[7] = vb[mm][3];
+        const bf16x8 vop = __builtin_bit_cast(bf16x8, v8);
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+          acc[n][m0 + mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, __builtin_bit_cast(bf16x8, pb[n]),
+                                                                    acc[n][m0 + mm], 0, 0, 0);
+      }
     }
+#undef ASPD_V_UNIT
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
@@ -385,8 +482,8 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     l_run[n] += __shfl_xor(l_run[n], 16);
     l_run[n] += __shfl_xor(l_run[n], 32);
     if (g == 0) {
-      wm[wave * BF16_ROWS + 16 * n + c] = m_run[n];
-      wl[wave * BF16_ROWS + 16 * n + c] = l_run[n];
+      wm[wave * ROWS + 16 * n + c] = m_run[n];
+      wl[wave * ROWS + 16 * n + c] = l_run[n];
     }
   }
   __syncthreads();  // also: every wave is done with its stage, which `red` aliases from here on
@@ -396,8 +493,8 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     {
       float mg = -INFINITY;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) mg = fmaxf(mg, wm[w * BF16_ROWS + 16 * n + c]);
-      const float f = exp2f(m_run[n] - exp2_safe_ref(mg));
+      for (int w = 0; w < NW; ++w) mg = fmaxf(mg, wm[w * ROWS + 16 * n + c]);
+      const float f = __builtin_amdgcn_exp2f(m_run[n] - exp2_safe_ref(mg));
 #pragma unroll
       for (int mt = 0; mt < C::MT; ++mt) {
         f32x4 v = acc[n][mt] * f;
@@ -412,11 +509,11 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
       const int r = 16 * n + row;
       float mg = -INFINITY;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) mg = fmaxf(mg, wm[w * BF16_ROWS + r]);
+      for (int w = 0; w < NW; ++w) mg = fmaxf(mg, wm[w * ROWS + r]);
       const float mref = exp2_safe_ref(mg);
       float lg = 0.f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) lg += wl[w * BF16_ROWS + r] * exp2f(wm[w * BF16_ROWS + r] - mref);
+      for (int w = 0; w < NW; ++w) lg += wl[w * ROWS + r] * __builtin_amdgcn_exp2f(wm[w * ROWS + r] - mref);
       float o[PER];
 #pragma unroll
       for (int e = 0; e < PER; ++e) {
@@ -430,16 +527,19 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
           const int head = it.h * a.G + r % a.G;
           const float inv = 1.f / lg;
           __bf16* dst = (__bf16*)a.out + ((long)q * a.kv.num_q_heads + head) * D + d0;
+          typedef __attribute__((ext_vector_type(PER))) __bf16 out_vec;
+          out_vec ov;
 #pragma unroll
-          for (int e = 0; e < PER; ++e) dst[e] = (__bf16)(o[e] * inv);
+          for (int e = 0; e < PER; ++e) ov[e] = (__bf16)(o[e] * inv);
+          *(out_vec*)dst = ov;
           if (a.lse && d0 == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (mg + log2f(lg)) * LN2;
         } else {
-          float* dst = pslot + (long)r * (D + 2);
+          float* dst = pslot + (long)r * (D + 4);
 #pragma unroll
-          for (int e = 0; e < PER; ++e) dst[d0 + e] = o[e];
+          for (int e = 0; e < PER; ++e) store_device_scope(dst + d0 + e, o[e]);
           if (d0 == 0) {
-            dst[D] = mg;
-            dst[D + 1] = lg;
+            store_device_scope(dst + D, mg);
+            store_device_scope(dst + D + 1, lg);
           }
         }
       }
@@ -448,13 +548,19 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   }
 }
 
-template <int D>
+template <int D, int NT>
+size_t bf16_smem_bytes(int B) {
+  return NW * Bf16Cfg<D>::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
+         (size_t)(B + 1) * 4;
+}
+
+template <int D, int NT>
 __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ int merge_flag;
   using C = Bf16Cfg<D>;
   // after the stages, the Q tile, row descriptors and wave statistics: the unit scan
-  int* cu_units = (int*)(smem + NW * C::STAGE_BYTES + BF16_ROWS * D * 2 + 2 * BF16_ROWS * 4 +
-                         2 * NW * BF16_ROWS * 4);
+  int* cu_units = (int*)(smem + NW * C::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
   const int total = build_units(a, cu_units, scratch);
   const int chunk = chunk_of(total, a.nwg);
@@ -467,19 +573,10 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int page1 = min(it.np, page0 + (end - u));
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    const int L = a.stage_base[it.s];
-    const int nt = (it.nq * a.G + 15) >> 4;
-    if (nt <= 1) segment_bf16<D, 1>(a, smem, it, page0, page1, L, complete, pslot);
-    else if (nt == 2) segment_bf16<D, 2>(a, smem, it, page0, page1, L, complete, pslot);
-    else segment_bf16<D, 3>(a, smem, it, page0, page1, L, complete, pslot);
+    segment_bf16<D, NT>(a, smem, it, page0, page1, a.stage_base[it.s], complete, pslot);
+    if (!complete) announce_partial<D, true>(a, it, chunk, &merge_flag);
     u += page1 - page0;
   }
-}
-
-template <int D>
-size_t bf16_smem_bytes(int B) {
-  return NW * Bf16Cfg<D>::STAGE_BYTES + BF16_ROWS * D * 2 + 2 * BF16_ROWS * 4 + 2 * NW * BF16_ROWS * 4 +
-         (size_t)(B + 1) * 4;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -602,11 +699,11 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
         ((float*)a.out)[((long)q * a.kv.num_q_heads + head) * D + d] = o / lg;
         if (a.lse && d == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (mg + log2f(lg)) * LN2;
       } else {
-        float* dst = pslot + (long)r * (D + 2);
-        dst[d] = o;
+        float* dst = pslot + (long)r * (D + 4);
+        store_device_scope(dst + d, o);
         if (d == 0) {
-          dst[D] = mg;
-          dst[D + 1] = lg;
+          store_device_scope(dst + D, mg);
+          store_device_scope(dst + D + 1, lg);
         }
       }
     }
@@ -621,6 +718,7 @@ size_t f32_smem_bytes(int B) {
 template <int D>
 __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ int merge_flag;
   int* cu_units = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4 +
                          (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4);
   int* scratch = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4);  // idle until the first segment ends
@@ -636,63 +734,113 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_f32<D>(a, smem, it, page0, page1, a.stage_base[it.s], complete, pslot);
+    if (!complete) announce_partial<D, false>(a, it, chunk, &merge_flag);
     u += page1 - page0;
   }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Merge of the partials of items that were split over several workgroups.  Workgroup w owns the
-// item that starts inside w's share and runs past its end; the item's partials are w's
-// "starts item" slot and the "continues item" slots of the following workgroups.
+// Items split over several workgroups: every workgroup that has written a partial for the item
+// announces it on the item's counter (indexed by the workgroup in whose share the item starts);
+// the one that arrives last combines all partials and writes the output.  No workgroup waits for
+// another.  The partials are the "starts item" slot of the first workgroup and the "continues
+// item" slots of the following ones.
 // ---------------------------------------------------------------------------------------------
 template <int D, bool BF16>
-__global__ __launch_bounds__(THREADS) void merge_kernel(AttnArgs a) {
-  __shared__ int cu_units[ASPD_MAX_BATCH + 1];
-  __shared__ int scratch[THREADS];
-  const int total = build_units(a, cu_units, scratch);
-  const int chunk = chunk_of(total, a.nwg);
-  const int w = blockIdx.x;
-  const long begin = (long)w * chunk;
-  if (begin >= total) return;
-  const int end = min((long)total, begin + chunk);
-  int page;
-  const Item it = locate(a, cu_units, end - 1, &page);
-  const int item_end = it.first_unit + it.np;
-  if (item_end <= end) return;               // the item finishes here: complete, or merged by its owner
-  if (it.first_unit < begin) return;         // started in an earlier workgroup: that one owns it
-  const int w_last = (item_end - 1) / chunk;
+__device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_last) {
+  constexpr int CPR = D / 4;  // float4 chunks per row
+  constexpr int BATCH = 8;    // partials fetched at once
   const int R = it.nq * a.G;
-  const int stride = a.rows_cap * (D + 2);
-  for (int i = threadIdx.x; i < R * D; i += THREADS) {
-    const int r = i / D, d = i - r * D;
-    float mg = -INFINITY;
-    for (int ww = w; ww <= w_last; ++ww) {
-      const float* p = a.partial + (long)(2 * ww + (ww == w ? 1 : 0)) * stride + (long)r * (D + 2);
-      mg = fmaxf(mg, p[D]);
-    }
-    const float mref = exp2_safe_ref(mg);
-    float lg = 0.f, o = 0.f;
-    for (int ww = w; ww <= w_last; ++ww) {
-      const float* p = a.partial + (long)(2 * ww + (ww == w ? 1 : 0)) * stride + (long)r * (D + 2);
-      const float f = exp2f(p[D] - mref);
-      lg += p[D + 1] * f;
-      o += p[d] * f;
+  const long stride = (long)a.rows_cap * (D + 4);
+  const int nparts = w_last - owner + 1;
+  for (int i = threadIdx.x; i < R * CPR; i += THREADS) {
+    const int r = i / CPR, cc = i - r * CPR;
+    float m = -INFINITY, l = 0.f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    for (int p0 = 0; p0 < nparts; p0 += BATCH) {
+      float pm[BATCH], pl[BATCH];
+      f32x4 po[BATCH];
+#pragma unroll
+      for (int k = 0; k < BATCH; ++k) {
+        const int ww = owner + min(p0 + k, nparts - 1);
+        const float* p = a.partial + (long)(2 * ww + (ww == owner ? 1 : 0)) * stride + (long)r * (D + 4);
+        pm[k] = load_device_scope(p + D);
+        pl[k] = load_device_scope(p + D + 1);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) po[k][e] = load_device_scope(p + 4 * cc + e);
+      }
+      float mb = m;
+#pragma unroll
+      for (int k = 0; k < BATCH; ++k)
+        if (p0 + k < nparts) mb = fmaxf(mb, pm[k]);
+      const float mref = exp2_safe_ref(mb);
+      const float f0 = __builtin_amdgcn_exp2f(m - mref);
+      l *= f0;
+      o *= f0;
+#pragma unroll
+      for (int k = 0; k < BATCH; ++k) {
+        if (p0 + k < nparts) {
+          const float f = __builtin_amdgcn_exp2f(pm[k] - mref);
+          l += pl[k] * f;
+          o += po[k] * f;
+        }
+      }
+      m = mb;
     }
     const int q = it.q0 + r / a.G;
     const int head = it.h * a.G + r % a.G;
-    const long oi = ((long)q * a.kv.num_q_heads + head) * D + d;
-    if (BF16) ((__bf16*)a.out)[oi] = (__bf16)(o / lg);
-    else ((float*)a.out)[oi] = o / lg;
-    if (a.lse && d == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (mg + log2f(lg)) * LN2;
+    const long oi = ((long)q * a.kv.num_q_heads + head) * D + 4 * cc;
+    const float inv = 1.f / l;
+    if (BF16) {
+      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+      bf16x4 ov;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(o[e] * inv);
+      *(bf16x4*)((__bf16*)a.out + oi) = ov;
+    } else {
+      *(f32x4*)((float*)a.out + oi) = o * inv;
+    }
+    if (a.lse && cc == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (m + log2f(l)) * LN2;
   }
+}
+
+// Called by every thread of the workgroup after it has written a partial of `it`.
+template <int D, bool BF16>
+__device__ void announce_partial(const AttnArgs& a, const Item& it, int chunk, int* flag /* LDS */) {
+  // the write-through stores of the partial have completed before the arrival is counted
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  const int owner = it.first_unit / chunk;
+  const int w_last = (it.first_unit + it.np - 1) / chunk;
+  if (threadIdx.x == 0) {
+    const int old = atomicAdd(a.counters + owner, 1);
+    const int last = (old == w_last - owner) ? 1 : 0;
+    if (last) atomicExch(a.counters + owner, 0);  // every part has arrived: leave it clean for the next call
+    *flag = last;
+  }
+  __syncthreads();
+  if (*flag == 0) return;
+  merge_item<D, BF16>(a, it, owner, w_last);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
-int rows_per_group(const aspd_kv* kv, int* qpg) {
+// Rows per row group and queries per row group.  For bf16 the group is `nt` MFMA tiles of 16 rows:
+// as few as the caller's bound on new tokens per sequence allows (fewer tiles leave more registers
+// for loads in flight), three when there is no bound.  A sequence with more rows than one group
+// holds is processed in several groups, whatever the hint said.
+int rows_per_group(const aspd_kv* kv, int max_new_per_seq, int* qpg, int* nt) {
   const int G = kv->num_q_heads / kv->num_kv_heads;
-  const int cap = (kv->dtype == ASPD_BF16) ? BF16_ROWS : F32_ROWS;
+  int cap = F32_ROWS;
+  *nt = 0;
+  if (kv->dtype == ASPD_BF16) {
+    int tiles = NT_MAX;
+    if (max_new_per_seq > 0) tiles = std::min(NT_MAX, (max_new_per_seq * G + 15) / 16);
+    while (tiles < NT_MAX && 16 * tiles < G) ++tiles;
+    cap = 16 * tiles;
+    *nt = tiles;
+  }
   if (G > cap) return 0;
   *qpg = cap / G;
   return cap;
@@ -709,6 +857,7 @@ int device_cu_count() {
 }
 
 constexpr int LDS_BYTES = 160 * 1024;  // per compute unit on gfx950
+constexpr int STATIC_LDS_RESERVE = 256;  // room for the kernels' few static LDS variables
 
 // Dynamic LDS above 64 KB has to be allowed once per kernel and device.
 int allow_big_lds(const void* kernel) {
@@ -718,7 +867,7 @@ int allow_big_lds(const void* kernel) {
   ASPD_HIP_CHECK(hipGetDevice(&dev));
   std::lock_guard<std::mutex> lock(mu);
   if (done.count({dev, kernel})) return ASPD_OK;
-  ASPD_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+  ASPD_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES - STATIC_LDS_RESERVE));
   done.insert({dev, kernel});
   return ASPD_OK;
 }
@@ -732,7 +881,7 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   if (rc != ASPD_OK) return rc;
   if (!state || !step || state->B <= 0 || !state->stage_base_d || !state->seq_len_d) return ASPD_ERR_INVALID_ARG;
   if (state->B > ASPD_MAX_BATCH) return ASPD_ERR_UNSUPPORTED;
-  if (step->NQ < 0 || !step->cu_seq_new_d) return ASPD_ERR_INVALID_ARG;
+  if (step->NQ < 0 || step->max_new_per_seq < 0 || !step->cu_seq_new_d) return ASPD_ERR_INVALID_ARG;
   if (step->NQ == 0) return ASPD_OK;
   if (!step->q_branch_d || !step->logical_slot_d || !q_d || !out_d) return ASPD_ERR_INVALID_ARG;
   if (((uintptr_t)q_d & 15) || ((uintptr_t)out_d & 15)) return ASPD_ERR_INVALID_ARG;
@@ -744,8 +893,8 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
         ((uintptr_t)state->slot_owner_d & 3))
       return ASPD_ERR_INVALID_ARG;
   }
-  int qpg = 0;
-  const int rows_cap = rows_per_group(kv, &qpg);
+  int qpg = 0, nt = 0;
+  const int rows_cap = rows_per_group(kv, step->max_new_per_seq, &qpg, &nt);
   if (rows_cap == 0) return ASPD_ERR_UNSUPPORTED;
   const size_t need = aspd_workspace_bytes(kv, state->B, step->NQ);
   if (need == 0) return ASPD_ERR_INVALID_ARG;
@@ -765,7 +914,8 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   a.q = q_d;
   a.out = out_d;
   a.lse = lse_d;
-  a.partial = (float*)workspace_d;
+  a.counters = (int*)workspace_d;
+  a.partial = (float*)((char*)workspace_d + COUNTER_BYTES);
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)kv->head_dim) : sm_scale) * LOG2E;
   a.B = state->B;
   a.G = kv->num_q_heads / kv->num_kv_heads;
@@ -782,22 +932,30 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
 
   hipStream_t hs = (hipStream_t)stream;
   const int D = kv->head_dim;
-#define ASPD_LAUNCH(KERNEL, MERGE, SMEM)                                             \
+#define ASPD_LAUNCH(KERNEL, SMEM)                                                    \
   do {                                                                               \
     rc = allow_big_lds((const void*)KERNEL);                                         \
     if (rc != ASPD_OK) return rc;                                                    \
-    if ((SMEM) > (size_t)LDS_BYTES) return ASPD_ERR_UNSUPPORTED;                     \
+    if ((SMEM) > (size_t)(LDS_BYTES - STATIC_LDS_RESERVE)) return ASPD_ERR_UNSUPPORTED;                     \
     hipLaunchKernelGGL(KERNEL, dim3(a.nwg), dim3(THREADS), SMEM, hs, a);             \
-    ASPD_HIP_CHECK(hipGetLastError());                                               \
-    hipLaunchKernelGGL(MERGE, dim3(a.nwg), dim3(THREADS), 0, hs, a);                 \
     ASPD_HIP_CHECK(hipGetLastError());                                               \
   } while (0)
   if (kv->dtype == ASPD_BF16) {
-    if (D == 128) ASPD_LAUNCH(attn_bf16_kernel<128>, (merge_kernel<128, true>), bf16_smem_bytes<128>(state->B));
-    else ASPD_LAUNCH(attn_bf16_kernel<64>, (merge_kernel<64, true>), bf16_smem_bytes<64>(state->B));
+#define ASPD_BF16_CASE(DD, NN)                                                                          \
+  ASPD_LAUNCH((attn_bf16_kernel<DD, NN>), (bf16_smem_bytes<DD, NN>(state->B)))
+    if (D == 128) {
+      if (nt == 1) ASPD_BF16_CASE(128, 1);
+      else if (nt == 2) ASPD_BF16_CASE(128, 2);
+      else ASPD_BF16_CASE(128, 3);
+    } else {
+      if (nt == 1) ASPD_BF16_CASE(64, 1);
+      else if (nt == 2) ASPD_BF16_CASE(64, 2);
+      else ASPD_BF16_CASE(64, 3);
+    }
+#undef ASPD_BF16_CASE
   } else {
-    if (D == 128) ASPD_LAUNCH(attn_f32_kernel<128>, (merge_kernel<128, false>), f32_smem_bytes<128>(state->B));
-    else ASPD_LAUNCH(attn_f32_kernel<64>, (merge_kernel<64, false>), f32_smem_bytes<64>(state->B));
+    if (D == 128) ASPD_LAUNCH(attn_f32_kernel<128>, f32_smem_bytes<128>(state->B));
+    else ASPD_LAUNCH(attn_f32_kernel<64>, f32_smem_bytes<64>(state->B));
   }
 #undef ASPD_LAUNCH
   return ASPD_OK;
@@ -809,11 +967,27 @@ extern "C" size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ)
   if (!kv || B <= 0 || NQ < 0 || kv->num_kv_heads <= 0 || kv->num_q_heads <= 0) return 0;
   if (kv->head_dim != 64 && kv->head_dim != 128) return 0;
   if (kv->dtype != ASPD_F32 && kv->dtype != ASPD_BF16) return 0;
-  int qpg = 0;
-  const int rows_cap = rows_per_group(kv, &qpg);
+  int qpg = 0, nt = 0;
+  const int rows_cap = rows_per_group(kv, 0, &qpg, &nt);  // the widest row group
   if (rows_cap == 0) return 0;
   // two partial slots per workgroup of the largest grid any device would get
-  return (size_t)2 * MAX_WG * rows_cap * (kv->head_dim + 2) * sizeof(float);
+  return COUNTER_BYTES + (size_t)2 * MAX_WG * rows_cap * (kv->head_dim + 4) * sizeof(float);
+}
+
+namespace {
+__global__ void zero_counters_kernel(int* counters) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < MAX_WG) counters[i] = 0;
+}
+}  // namespace
+
+extern "C" int aspd_workspace_init(void* workspace_d, size_t workspace_bytes, void* stream) {
+  if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
+  if (workspace_bytes < (size_t)COUNTER_BYTES) return ASPD_ERR_WORKSPACE;
+  hipLaunchKernelGGL(zero_counters_kernel, dim3(MAX_WG / 256), dim3(256), 0, (hipStream_t)stream,
+                     (int*)workspace_d);
+  ASPD_HIP_CHECK(hipGetLastError());
+  return ASPD_OK;
 }
 
 extern "C" int aspd_attn_parallel_decode(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,

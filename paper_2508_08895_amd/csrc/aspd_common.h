@@ -35,6 +35,7 @@ struct StateView {
 
 struct StepView {
   int32_t  NQ;
+  int32_t  max_new_per_seq;
   int32_t* cu_new;
   int32_t* cu_seq_new;
   int32_t* q_seq;
@@ -54,7 +55,7 @@ static inline StateView make_view(const aspd_state* st) {
                    st->slot_owner_d, st->owner_stride, st->fault_d};
 }
 static inline StepView make_view(const aspd_step* sp) {
-  return StepView{sp->NQ, sp->cu_new_d, sp->cu_seq_new_d, sp->q_seq_d, sp->q_branch_d, sp->position_ids_d,
+  return StepView{sp->NQ, sp->max_new_per_seq, sp->cu_new_d, sp->cu_seq_new_d, sp->q_seq_d, sp->q_branch_d, sp->position_ids_d,
                   sp->logical_slot_d, sp->slot_mapping_d, sp->kv_len_d};
 }
 

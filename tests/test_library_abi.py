@@ -39,11 +39,18 @@ def _kv(**over):
     return A.aspd_kv(**base)
 
 
+def test_workspace_init_rejects_bad_arguments():
+    L = A.lib()
+    assert L.aspd_workspace_init(None, 1 << 20, None) == A.ERR_INVALID_ARG
+    assert L.aspd_workspace_init(0x1010, 1 << 20, None) == A.ERR_INVALID_ARG
+    assert L.aspd_workspace_init(0x1000, 16, None) == A.ERR_WORKSPACE
+
+
 def test_workspace_bytes_is_host_only():
     L = A.lib()
     kv = _kv()
     n = L.aspd_workspace_bytes(C.byref(kv), 4, 16)
-    assert n > 0 and n % 256 == 0
+    assert n > 0 and n % 16 == 0
     assert L.aspd_workspace_bytes(C.byref(_kv(head_dim=96)), 4, 16) == 0
     assert L.aspd_workspace_bytes(C.byref(kv), 0, 16) == 0
     assert L.aspd_workspace_bytes(None, 4, 16) == 0
@@ -65,7 +72,7 @@ def test_bad_cache_descriptors_are_rejected_before_launch(over, code):
     kv = _kv(**over)
     st = A.aspd_state(B=1, NB=1, stage_base_d=0x10, seq_len_d=0x20, cu_branches_d=0x30, branch_len_d=0x40,
                       slot_owner_d=0x50, owner_stride=64, fault_d=None)
-    sp = A.aspd_step(NQ=1, cu_new_d=0x10, cu_seq_new_d=0x10, q_seq_d=0x10, q_branch_d=0x10,
+    sp = A.aspd_step(NQ=1, max_new_per_seq=0, cu_new_d=0x10, cu_seq_new_d=0x10, q_seq_d=0x10, q_branch_d=0x10,
                      position_ids_d=0x10, logical_slot_d=0x10, slot_mapping_d=0x10, kv_len_d=0x10)
     assert L.aspd_build_branch_meta(C.byref(kv), C.byref(st), A.STAGE_PARALLEL, 0, 0x100, C.byref(sp), None) == code
     for name in ("aspd_attn_parallel_decode", "aspd_attn_branch_chunk", "aspd_attn_serial_decode"):
@@ -78,7 +85,7 @@ def test_bad_state_and_step_are_rejected_before_launch():
     kv = _kv()
     good_st = dict(B=1, NB=1, stage_base_d=0x10, seq_len_d=0x20, cu_branches_d=0x30, branch_len_d=0x40,
                    slot_owner_d=0x50, owner_stride=64, fault_d=None)
-    good_sp = dict(NQ=1, cu_new_d=0x10, cu_seq_new_d=0x10, q_seq_d=0x10, q_branch_d=0x10, position_ids_d=0x10,
+    good_sp = dict(NQ=1, max_new_per_seq=0, cu_new_d=0x10, cu_seq_new_d=0x10, q_seq_d=0x10, q_branch_d=0x10, position_ids_d=0x10,
                    logical_slot_d=0x10, slot_mapping_d=0x10, kv_len_d=0x10)
 
     def meta(st_over=None, sp_over=None, stage=A.STAGE_PARALLEL, pos=0, new_len=0x100):
