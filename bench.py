@@ -232,6 +232,22 @@ def main() -> int:
                           "algorithmic_MB": round(bts / 1e6, 3), "GBps": round(bts / avg / 1e9, 1),
                           "frac_of_8TBps": round(bts / avg / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # ---- what a plain read-only stream reaches on this device (2 GiB, larger than any cache)
+    probe_src = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    probe_src.zero_()
+    probe_sink = torch.empty(64 << 10, dtype=torch.uint8, device=dev)
+    for _ in range(2):
+        A.aspd_probe_read_bandwidth(probe_src, probe_sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        A.aspd_probe_read_bandwidth(probe_src, probe_sink)
+    e1.record()
+    torch.cuda.synchronize()
+    read_ceiling = 5 * probe_src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del probe_src
+
     # the dominant kernel: the streaming decode launches (parallel + serial share one kernel)
     dom = [k for k in ("parallel", "serial") if k in dur]
     dom_launches = sum(len(bytes_of[k]) for k in dom)
@@ -249,6 +265,8 @@ def main() -> int:
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_launch_us": round(dom_time / dom_launches * 1e6, 2),
+                "plain_read_stream_GBps": round(read_ceiling, 1),
+                "frac_of_plain_read_stream": round(achieved / read_ceiling, 4),
                 "algorithmic_bytes_per_launch": int(dom_bytes / dom_launches)}
 
     # ---- CPU baseline: the oracle on the parallel-decode call of this workload

@@ -172,6 +172,13 @@ ASPD_API int aspd_attn_serial_decode(const aspd_kv* kv, const aspd_state* state,
                             const void* q_d, void* out_d, float* lse_d, float sm_scale,
                             void* workspace_d, size_t workspace_bytes, void* stream);
 
+/* Measurement aid, not part of the method: enqueues one plain, fully coalesced read of
+ * bytes / 16 * 16 bytes from src_d (16-byte aligned) and writes one 32-bit word per workgroup to
+ * sink_d (room for 64 KiB is enough on any device).  Benchmarks time it to report what a read-only
+ * stream reaches on the device at hand, next to the 8 TB/s datasheet figure, and profilers use its
+ * known size to calibrate HBM byte counters. */
+ASPD_API int aspd_probe_read_bandwidth(const void* src_d, size_t bytes, void* sink_d, void* stream);
+
 /* Static string for a return code. */
 ASPD_API const char* aspd_status_string(int status);
 

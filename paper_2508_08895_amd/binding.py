@@ -22,7 +22,7 @@ POS_SAME_SEQ = 0
 FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES = 1, 2, 4, 8
 
 EXPORTS = ("aspd_build_branch_meta", "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
-           "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_status_string")
+           "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_probe_read_bandwidth", "aspd_status_string")
 
 
 class aspd_kv(C.Structure):
@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
                            C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
         L.aspd_workspace_init.restype = C.c_int
         L.aspd_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+        L.aspd_probe_read_bandwidth.restype = C.c_int
+        L.aspd_probe_read_bandwidth.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.aspd_status_string.restype = C.c_char_p
         L.aspd_status_string.argtypes = [C.c_int]
         _lib = L
@@ -213,6 +215,12 @@ def aspd_workspace_init(workspace: torch.Tensor, stream=None) -> None:
     rc = lib().aspd_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     if rc != OK:
         raise AspdError(rc, "aspd_workspace_init")
+
+
+def aspd_probe_read_bandwidth(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    rc = lib().aspd_probe_read_bandwidth(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream))
+    if rc != OK:
+        raise AspdError(rc, "aspd_probe_read_bandwidth")
 
 
 def new_workspace(kv: KVCache, B: int, NQ: int) -> torch.Tensor:

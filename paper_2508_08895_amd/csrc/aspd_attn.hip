@@ -26,8 +26,10 @@
 
 namespace {
 
-constexpr int NW = 4;                 // waves per workgroup
+constexpr int NW = 4;                 // waves per workgroup, fp32 kernel (two workgroups per compute unit)
 constexpr int THREADS = NW * 64;
+constexpr int NW_BF16 = 8;            // waves per workgroup, bf16 kernel (one workgroup per compute unit:
+                                      // half as many partials to combine for a split item)
 constexpr int NT_MAX = 3;             // 16-row MFMA tiles per row group (bf16 path)
 constexpr int BF16_ROWS = 16 * NT_MAX;
 constexpr int F32_ROWS = 4;           // rows per row group (fp32 vector path)
@@ -88,6 +90,7 @@ __device__ __forceinline__ int groups_of(const AttnArgs& a, int s) {
 }
 
 // cu_units[0..B] = exclusive scan of pages * KV heads * row groups per sequence.  Returns the total.
+template <int THREADS>
 __device__ int build_units(const AttnArgs& a, int* cu_units, int* scratch /*THREADS ints*/) {
   constexpr int PER = ASPD_MAX_BATCH / THREADS;  // sequences per thread
   const int tid = threadIdx.x;
@@ -197,7 +200,10 @@ struct PairRegs {
   u32x4 r[4][Bf16Cfg<D>::LPP];
 };
 
-template <int D>
+// STREAM: the pages are read once by this launch, so they are fetched with non-temporal loads, which
+// on this device sustain a visibly higher read rate than ordinary loads; launches that revisit pages
+// (several row groups per KV head) use ordinary loads and find them in the L2 / memory-side cache.
+template <int D, bool STREAM>
 __device__ __forceinline__ void issue_pair(PairRegs<D>& pr, const AttnArgs& a, int h, int b0, int b1, int lane) {
   using C = Bf16Cfg<D>;
   const long o0 = ((long)b0 * a.kv.num_kv_heads + h) * C::PAGE_U4 + lane;
@@ -208,15 +214,23 @@ __device__ __forceinline__ void issue_pair(PairRegs<D>& pr, const AttnArgs& a, i
   const u32x4* v1 = (const u32x4*)a.kv.v + o1;
 #pragma unroll
   for (int i = 0; i < C::LPP; ++i) {
-    pr.r[0][i] = k0[i * 64];
-    pr.r[1][i] = k1[i * 64];
-    pr.r[2][i] = v0[i * 64];
-    pr.r[3][i] = v1[i * 64];
+    if (STREAM) {
+      pr.r[0][i] = __builtin_nontemporal_load(k0 + i * 64);
+      pr.r[1][i] = __builtin_nontemporal_load(k1 + i * 64);
+      pr.r[2][i] = __builtin_nontemporal_load(v0 + i * 64);
+      pr.r[3][i] = __builtin_nontemporal_load(v1 + i * 64);
+    } else {
+      pr.r[0][i] = k0[i * 64];
+      pr.r[1][i] = k1[i * 64];
+      pr.r[2][i] = v0[i * 64];
+      pr.r[3][i] = v1[i * 64];
+    }
   }
 }
 
 // Block ids of a wave's pairs: lane i holds the id of page (i & 1) of the wave's pair number
 // jbase + i / 2, so one gather serves 32 iterations.
+template <int NW>
 __device__ __forceinline__ int block_window(const AttnArgs& a, const int* bt, int page0, int page1, int wave,
                                             int jbase, int lane) {
   const int jj = jbase + (lane >> 1);
@@ -226,11 +240,12 @@ __device__ __forceinline__ int block_window(const AttnArgs& a, const int* bt, in
   return min(max(b, 0), a.kv.num_blocks - 1);
 }
 
-template <int D, int NT>
+template <int D, int NT, int NW, bool STREAM>
 __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
                              bool complete, float* pslot) {
   using C = Bf16Cfg<D>;
   constexpr int ROWS = 16 * NT;
+  constexpr int THREADS = NW * 64;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -309,12 +324,12 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
 
   int blk_cur = 0, blk_next = 0;
-  if (my_pairs > 0) blk_cur = block_window(a, bt, page0, page1, wave, 0, lane);
-  if (my_pairs > 32) blk_next = block_window(a, bt, page0, page1, wave, 32, lane);
+  if (my_pairs > 0) blk_cur = block_window<NW>(a, bt, page0, page1, wave, 0, lane);
+  if (my_pairs > 32) blk_next = block_window<NW>(a, bt, page0, page1, wave, 32, lane);
 
   PairRegs<D> pr;
   if (my_pairs > 0)
-    issue_pair<D>(pr, a, it.h, __builtin_amdgcn_readlane(blk_cur, 0), __builtin_amdgcn_readlane(blk_cur, 1), lane);
+    issue_pair<D, STREAM>(pr, a, it.h, __builtin_amdgcn_readlane(blk_cur, 0), __builtin_amdgcn_readlane(blk_cur, 1), lane);
 
   for (int j = 0; j < my_pairs; ++j) {
     const int pair = wave + NW * j;
@@ -336,10 +351,10 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
       const int jn = j + 1;
       if ((jn & 31) == 0) {
         blk_cur = blk_next;
-        if (jn + 32 < my_pairs) blk_next = block_window(a, bt, page0, page1, wave, jn + 32, lane);
+        if (jn + 32 < my_pairs) blk_next = block_window<NW>(a, bt, page0, page1, wave, jn + 32, lane);
       }
       const int li = __builtin_amdgcn_readfirstlane((jn & 31) * 2);
-      issue_pair<D>(pr, a, it.h, __builtin_amdgcn_readlane(blk_cur, li), __builtin_amdgcn_readlane(blk_cur, li + 1),
+      issue_pair<D, STREAM>(pr, a, it.h, __builtin_amdgcn_readlane(blk_cur, li), __builtin_amdgcn_readlane(blk_cur, li + 1),
                     lane);
     }
 
@@ -548,21 +563,22 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   }
 }
 
-template <int D, int NT>
+template <int D, int NT, int NW>
 size_t bf16_smem_bytes(int B) {
   return NW * Bf16Cfg<D>::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
          (size_t)(B + 1) * 4;
 }
 
-template <int D, int NT>
-__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_kernel(AttnArgs a) {
+template <int D, int NT, int NW, bool STREAM>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int merge_flag;
   using C = Bf16Cfg<D>;
+  constexpr int THREADS = NW * 64;
   // after the stages, the Q tile, row descriptors and wave statistics: the unit scan
   int* cu_units = (int*)(smem + NW * C::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
-  const int total = build_units(a, cu_units, scratch);
+  const int total = build_units<THREADS>(a, cu_units, scratch);
   const int chunk = chunk_of(total, a.nwg);
   const int begin = blockIdx.x * chunk;
   const int end = min(total, begin + chunk);
@@ -573,8 +589,8 @@ __global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int page1 = min(it.np, page0 + (end - u));
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    segment_bf16<D, NT>(a, smem, it, page0, page1, a.stage_base[it.s], complete, pslot);
-    if (!complete) announce_partial<D, true>(a, it, chunk, &merge_flag);
+    segment_bf16<D, NT, NW, STREAM>(a, smem, it, page0, page1, a.stage_base[it.s], complete, pslot);
+    if (!complete) announce_partial<D, true, THREADS>(a, it, chunk, &merge_flag);
     u += page1 - page0;
   }
 }
@@ -722,7 +738,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
   int* cu_units = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4 +
                          (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4);
   int* scratch = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4);  // idle until the first segment ends
-  const int total = build_units(a, cu_units, scratch);
+  const int total = build_units<THREADS>(a, cu_units, scratch);
   const int chunk = chunk_of(total, a.nwg);
   const int begin = blockIdx.x * chunk;
   const int end = min(total, begin + chunk);
@@ -734,7 +750,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_f32<D>(a, smem, it, page0, page1, a.stage_base[it.s], complete, pslot);
-    if (!complete) announce_partial<D, false>(a, it, chunk, &merge_flag);
+    if (!complete) announce_partial<D, false, THREADS>(a, it, chunk, &merge_flag);
     u += page1 - page0;
   }
 }
@@ -746,7 +762,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
 // another.  The partials are the "starts item" slot of the first workgroup and the "continues
 // item" slots of the following ones.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool BF16>
+template <int D, bool BF16, int THREADS>
 __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_last) {
   constexpr int CPR = D / 4;  // float4 chunks per row
   constexpr int BATCH = 8;    // partials fetched at once
@@ -805,7 +821,7 @@ __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_l
 }
 
 // Called by every thread of the workgroup after it has written a partial of `it`.
-template <int D, bool BF16>
+template <int D, bool BF16, int THREADS>
 __device__ void announce_partial(const AttnArgs& a, const Item& it, int chunk, int* flag /* LDS */) {
   // the write-through stores of the partial have completed before the arrival is counted
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -820,7 +836,7 @@ __device__ void announce_partial(const AttnArgs& a, const Item& it, int chunk, i
   }
   __syncthreads();
   if (*flag == 0) return;
-  merge_item<D, BF16>(a, it, owner, w_last);
+  merge_item<D, BF16, THREADS>(a, it, owner, w_last);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -922,27 +938,37 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   a.qpg = qpg;
   a.rows_cap = rows_cap;
 
-  // Grid: two workgroups per compute unit, never more than the pages can feed.
+  // Grid: as many workgroups as stay resident at once (one of 8 waves per compute unit for bf16, two of
+  // 4 waves for fp32), never more than the pages can feed.
   const long groups_max = (long)state->B + step->NQ / qpg;
   const long units_max = groups_max * kv->num_kv_heads * kv->max_blocks_per_seq;
-  long nwg = 2L * device_cu_count();
+  long nwg = (kv->dtype == ASPD_BF16 ? 1L : 2L) * device_cu_count();
+  // pages are read once when no sequence can have more than one row group
+  const bool stream_once = step->max_new_per_seq > 0 && step->max_new_per_seq <= qpg;
   nwg = std::min(nwg, (units_max + MIN_PAGES_PER_WG - 1) / MIN_PAGES_PER_WG);
   nwg = std::max(1L, std::min(nwg, (long)MAX_WG));
   a.nwg = (int)nwg;
 
   hipStream_t hs = (hipStream_t)stream;
   const int D = kv->head_dim;
-#define ASPD_LAUNCH(KERNEL, SMEM)                                                    \
+#define ASPD_LAUNCH(KERNEL, NTHREADS, SMEM)                                          \
   do {                                                                               \
     rc = allow_big_lds((const void*)KERNEL);                                         \
     if (rc != ASPD_OK) return rc;                                                    \
     if ((SMEM) > (size_t)(LDS_BYTES - STATIC_LDS_RESERVE)) return ASPD_ERR_UNSUPPORTED;                     \
-    hipLaunchKernelGGL(KERNEL, dim3(a.nwg), dim3(THREADS), SMEM, hs, a);             \
+    hipLaunchKernelGGL(KERNEL, dim3(a.nwg), dim3(NTHREADS), SMEM, hs, a);            \
     ASPD_HIP_CHECK(hipGetLastError());                                               \
   } while (0)
   if (kv->dtype == ASPD_BF16) {
-#define ASPD_BF16_CASE(DD, NN)                                                                          \
-  ASPD_LAUNCH((attn_bf16_kernel<DD, NN>), (bf16_smem_bytes<DD, NN>(state->B)))
+#define ASPD_BF16_CASE(DD, NN)                                                                            \
+  do {                                                                                                    \
+    if (stream_once)                                                                                      \
+      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, NW_BF16, true>), NW_BF16 * 64,                                \
+                  (bf16_smem_bytes<DD, NN, NW_BF16>(state->B)));                                          \
+    else                                                                                                  \
+      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, NW_BF16, false>), NW_BF16 * 64,                               \
+                  (bf16_smem_bytes<DD, NN, NW_BF16>(state->B)));                                          \
+  } while (0)
     if (D == 128) {
       if (nt == 1) ASPD_BF16_CASE(128, 1);
       else if (nt == 2) ASPD_BF16_CASE(128, 2);
@@ -954,8 +980,8 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
     }
 #undef ASPD_BF16_CASE
   } else {
-    if (D == 128) ASPD_LAUNCH(attn_f32_kernel<128>, f32_smem_bytes<128>(state->B));
-    else ASPD_LAUNCH(attn_f32_kernel<64>, f32_smem_bytes<64>(state->B));
+    if (D == 128) ASPD_LAUNCH(attn_f32_kernel<128>, THREADS, f32_smem_bytes<128>(state->B));
+    else ASPD_LAUNCH(attn_f32_kernel<64>, THREADS, f32_smem_bytes<64>(state->B));
   }
 #undef ASPD_LAUNCH
   return ASPD_OK;
@@ -980,6 +1006,42 @@ __global__ void zero_counters_kernel(int* counters) {
   if (i < MAX_WG) counters[i] = 0;
 }
 }  // namespace
+
+namespace {
+// Plain streaming read (non-temporal loads, the fastest plain read on this device): every lane loads 16 bytes per step, consecutive lanes consecutive addresses,
+// each workgroup a contiguous share.  The XOR of everything read goes to one word per workgroup so
+// that the loads cannot be dropped.
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ src, size_t n16,
+                                                         unsigned* __restrict__ sink) {
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t lo = per * blockIdx.x;
+  const size_t hi = lo + per < n16 ? lo + per : n16;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  size_t i = lo + threadIdx.x;
+  for (; i + 3 * 256 < hi; i += 4 * 256) {
+    const u32x4 a0 = __builtin_nontemporal_load(src + i), a1 = __builtin_nontemporal_load(src + i + 256),
+                a2 = __builtin_nontemporal_load(src + i + 512), a3 = __builtin_nontemporal_load(src + i + 768);
+    acc ^= a0 ^ a1 ^ a2 ^ a3;
+  }
+  for (; i < hi; i += 256) acc ^= src[i];
+  unsigned x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x ^= __shfl_xor(x, off);
+  __shared__ unsigned part[4];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = x;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+}  // namespace
+
+extern "C" int aspd_probe_read_bandwidth(const void* src_d, size_t bytes, void* sink_d, void* stream) {
+  if (!src_d || !sink_d || ((uintptr_t)src_d & 15) || bytes < 16) return ASPD_ERR_INVALID_ARG;
+  const int grid = 8 * device_cu_count();
+  hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src_d,
+                     bytes / 16, (unsigned*)sink_d);
+  ASPD_HIP_CHECK(hipGetLastError());
+  return ASPD_OK;
+}
 
 extern "C" int aspd_workspace_init(void* workspace_d, size_t workspace_bytes, void* stream) {
   if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
