@@ -197,7 +197,7 @@ def config(index: int, *, scale: float = 1.0, batch: int | None = None) -> Workl
     if index == 5:
         return make_workload("cfg5_b64_chunk", seed, **_LLM7B, prefix_range=(sc(1024), sc(8192)),
                              branches_range=(2, 10), branch_len_range=(8, 128), batch=batch or 64,
-                             pool_factor=1.1, extra_tokens_per_branch=17, extra_tokens_per_seq=0)
+                             pool_factor=1.1, extra_tokens_per_branch=17, extra_tokens_per_seq=8)
     raise ValueError(f"no configuration {index}")
 
 

@@ -59,7 +59,7 @@ extern "C" {
 
 #define ASPD_POS_SAME_SEQ 0 /* Eq. 4 as adopted by the paper (Sec. 4.5.3, "Same-Sequential")     */
 
-#define ASPD_MAX_BATCH             1024 /* sequences per call                                      */
+#define ASPD_MAX_BATCH             512  /* sequences per call                                      */
 #define ASPD_MAX_BRANCHES_PER_SEQ  255  /* owner tags are one byte                                 */
 
 /* bits of *aspd_state.fault_d */

@@ -80,76 +80,186 @@ struct Item {
   int first_unit;   // flattened index of the item's page 0
 };
 
-__device__ __forceinline__ int pages_of(const AttnArgs& a, int s) {
-  int np = (a.seq_len[s] + ASPD_BLOCK - 1) / ASPD_BLOCK;
+// Per-sequence scalars, fetched once per workgroup into LDS so that walking from segment to segment
+// needs no further dependent global loads.
+struct Sched {
+  int* cu_units;  // [B+1] exclusive scan of pages * row groups * KV heads
+  int* T;         // [B]   seq_len
+  int* L;         // [B]   stage_base
+  int* q0;        // [B+1] cu_seq_new
+};
+__device__ __forceinline__ Sched sched_at(int* base, int B) {
+  Sched sc;
+  sc.cu_units = base;
+  sc.T = base + (B + 1);
+  sc.L = sc.T + B;
+  sc.q0 = sc.L + B;
+  return sc;
+}
+constexpr int sched_ints(int B) { return 4 * B + 2; }
+
+__device__ __forceinline__ int pages_of(const AttnArgs& a, const Sched& sc, int s) {
+  int np = (sc.T[s] + ASPD_BLOCK - 1) / ASPD_BLOCK;
   return min(np, a.kv.max_blocks_per_seq);
 }
-__device__ __forceinline__ int groups_of(const AttnArgs& a, int s) {
-  int nq = a.cu_seq_new[s + 1] - a.cu_seq_new[s];
+__device__ __forceinline__ int groups_of(const AttnArgs& a, const Sched& sc, int s) {
+  int nq = sc.q0[s + 1] - sc.q0[s];
   return (nq + a.qpg - 1) / a.qpg;
 }
 
-// cu_units[0..B] = exclusive scan of pages * KV heads * row groups per sequence.  Returns the total.
+// Fills the LDS tables.  Returns the total number of page units; *min_np gets the page count of the
+// shortest item.
 template <int THREADS>
-__device__ int build_units(const AttnArgs& a, int* cu_units, int* scratch /*THREADS ints*/) {
-  constexpr int PER = ASPD_MAX_BATCH / THREADS;  // sequences per thread
+__device__ int build_units(const AttnArgs& a, const Sched& sc, int* scratch /*THREADS + THREADS / 64 ints*/,
+                           int* min_np) {
+  constexpr int PER = (ASPD_MAX_BATCH + THREADS - 1) / THREADS;  // sequences per thread
   const int tid = threadIdx.x;
   int mine[PER];
   int sum = 0;
+  int shortest = 0x7fffffff;
 #pragma unroll
   for (int j = 0; j < PER; ++j) {
-    int s = tid * PER + j;
-    mine[j] = (s < a.B) ? pages_of(a, s) * groups_of(a, s) * a.kv.num_kv_heads : 0;
+    const int s = tid * PER + j;
+    mine[j] = 0;
+    if (s < a.B) {
+      const int T = a.seq_len[s];
+      const int q0 = a.cu_seq_new[s];
+      const int q1 = a.cu_seq_new[s + 1];
+      sc.T[s] = T;
+      sc.L[s] = a.stage_base[s];
+      sc.q0[s] = q0;
+      if (s == a.B - 1) sc.q0[a.B] = q1;
+      const int np = min((T + ASPD_BLOCK - 1) / ASPD_BLOCK, a.kv.max_blocks_per_seq);
+      const int ng = (q1 - q0 + a.qpg - 1) / a.qpg;
+      mine[j] = np * ng * a.kv.num_kv_heads;
+      if (mine[j] > 0) shortest = min(shortest, np);
+    }
     sum += mine[j];
   }
-  scratch[tid] = sum;
-  __syncthreads();
-  for (int d = 1; d < THREADS; d <<= 1) {
-    int v = (tid >= d) ? scratch[tid - d] : 0;
-    __syncthreads();
-    scratch[tid] += v;
-    __syncthreads();
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) shortest = min(shortest, __shfl_xor(shortest, off));
+  if ((tid & 63) == 0) scratch[THREADS + (tid >> 6)] = shortest;
+  // scan: inside the wave by shuffles, across the waves through LDS (one barrier)
+  int incl = sum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int v = __shfl_up(incl, off);
+    if ((tid & 63) >= off) incl += v;
   }
-  int run = scratch[tid] - sum;  // exclusive
+  if ((tid & 63) == 63) scratch[tid >> 6] = incl;
+  __syncthreads();
+  int run = incl - sum;  // exclusive within the wave
+  int total = 0;
+  int mn = 0x7fffffff;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) {
+    const int t = scratch[w];
+    if (w < (tid >> 6)) run += t;
+    total += t;
+    mn = min(mn, scratch[THREADS + w]);
+  }
 #pragma unroll
   for (int j = 0; j < PER; ++j) {
-    int s = tid * PER + j;
-    if (s < a.B) cu_units[s] = run;
+    const int s = tid * PER + j;
+    if (s < a.B) sc.cu_units[s] = run;
     run += mine[j];
   }
-  const int total = scratch[THREADS - 1];
-  if (tid == 0) cu_units[a.B] = total;
+  if (tid == 0) sc.cu_units[a.B] = total;
+  *min_np = mn;
   __syncthreads();
   return total;
 }
 
-__device__ __forceinline__ int chunk_of(int total, int nwg) {
-  int c = (total + nwg - 1) / nwg;
-  return max(c, MIN_PAGES_PER_WG);
-}
-
 // The item that holds flattened page `u`, and the page's index within it.
-__device__ Item locate(const AttnArgs& a, const int* cu_units, int u, int* page) {
+__device__ Item locate(const AttnArgs& a, const Sched& sc, int u, int* page) {
   int lo = 0, hi = a.B - 1;
   while (lo < hi) {
     int mid = (lo + hi + 1) >> 1;
-    if (cu_units[mid] <= u) lo = mid; else hi = mid - 1;
+    if (sc.cu_units[mid] <= u) lo = mid; else hi = mid - 1;
   }
   Item it;
   it.s = lo;
-  it.np = pages_of(a, lo);
-  const int rel = u - cu_units[lo];
+  it.np = pages_of(a, sc, lo);
+  const int rel = u - sc.cu_units[lo];
   const int idx = rel / it.np;
   *page = rel - idx * it.np;
-  const int ngroups = groups_of(a, lo);
+  const int ngroups = groups_of(a, sc, lo);
   it.h = idx / ngroups;       // row groups of one KV head are neighbours: they read the same pages
   it.rg = idx - it.h * ngroups;
-  it.first_unit = cu_units[lo] + idx * it.np;
-  const int qs = a.cu_seq_new[lo];
-  const int nq = a.cu_seq_new[lo + 1] - qs;
+  it.first_unit = sc.cu_units[lo] + idx * it.np;
+  const int qs = sc.q0[lo];
+  const int nq = sc.q0[lo + 1] - qs;
   it.q0 = qs + it.rg * a.qpg;
   it.nq = min(a.qpg, nq - it.rg * a.qpg);
   return it;
+}
+
+// Shares of the page space, one per workgroup used.  Two regimes, chosen per launch:
+//
+// ALIGNED (every item at least two shares long: few long sequences).  Item i gets the workgroups
+// [rnd(U_i), rnd(U_i + np_i)) with U_i its first flattened page and rnd(x) = x * n / total rounded to
+// nearest, and is cut evenly among them.  Every workgroup then has exactly one segment, and shares
+// differ by a page or two.
+//
+// FLATTENED (ragged batches).  Workgroup w nominally takes [w * total / n, (w + 1) * total / n); a
+// boundary within an eighth of a share of an item boundary is moved onto it, because a sliver of a
+// neighbouring item would cost a whole extra segment (start-up, reduction, a partial to be merged)
+// for a few pages.
+struct Shares {
+  int total, n, tol;
+  bool aligned;
+  double per_page;  // n / total: workgroups per page
+  double share;     // total / n: pages per workgroup
+  // Any monotone map with rnd(0) = 0 and rnd(total) = n serves, as long as every caller uses this one;
+  // double arithmetic avoids 64-bit integer division.
+  __device__ __forceinline__ int rnd(int x) const { return min(n, (int)((double)x * per_page + 0.5)); }
+  __device__ __forceinline__ int nominal_begin(int w) const { return min(total, (int)((double)w * share)); }
+  __device__ __forceinline__ int nominal_owner(int u) const { return min(n - 1, (int)((double)u * per_page)); }
+};
+__device__ __forceinline__ Shares make_shares(int total, int nwg, int min_np) {
+  Shares sh;
+  sh.total = total;
+  sh.n = max(1, min(nwg, total / MIN_PAGES_PER_WG));
+  sh.tol = (total / sh.n) >> 3;
+  sh.aligned = (double)min_np * sh.n >= 2.0 * total;
+  sh.per_page = (double)sh.n / (double)max(total, 1);
+  sh.share = (double)total / (double)sh.n;
+  return sh;
+}
+__device__ int share_begin(const AttnArgs& a, const Sched& sc, const Shares& sh, int w) {
+  if (w <= 0) return 0;
+  if (w >= sh.n) return sh.total;
+  const int nominal = sh.nominal_begin(w);
+  int page;
+  Item it = locate(a, sc, nominal, &page);
+  if (sh.aligned) {
+    // rounding moves an item's first workgroup by half a share at most: the item that holds the
+    // nominal boundary, or its neighbour
+    if (w < sh.rnd(it.first_unit)) it = locate(a, sc, it.first_unit - 1, &page);
+    else if (w >= sh.rnd(it.first_unit + it.np)) it = locate(a, sc, it.first_unit + it.np, &page);
+    const int w0 = sh.rnd(it.first_unit);
+    const int k = sh.rnd(it.first_unit + it.np) - w0;
+    return it.first_unit + (int)((unsigned)(w - w0) * (unsigned)it.np / (unsigned)k);
+  }
+  if (page <= sh.tol) return it.first_unit;
+  if (it.np - page <= sh.tol) return it.first_unit + it.np;
+  return nominal;
+}
+// The workgroup whose share holds flattened page u.
+__device__ int share_owner(const AttnArgs& a, const Sched& sc, const Shares& sh, int u) {
+  if (sh.aligned) {
+    int page;
+    const Item it = locate(a, sc, u, &page);
+    const int w0 = sh.rnd(it.first_unit);
+    const int k = sh.rnd(it.first_unit + it.np) - w0;
+    return w0 + (int)((((unsigned)page + 1u) * (unsigned)k - 1u) / (unsigned)it.np);
+  }
+  // nominal owner, corrected against the actual boundaries (rounding and moved boundaries shift it
+  // by a workgroup or two at most)
+  int w = sh.nominal_owner(u);
+  while (w > 0 && u < share_begin(a, sc, sh, w)) --w;
+  while (w < sh.n - 1 && u >= share_begin(a, sc, sh, w + 1)) ++w;
+  return w;
 }
 
 __device__ __forceinline__ float* partial_slot(const AttnArgs& a, int wg, int starts_item, int D) {
@@ -228,17 +338,7 @@ __device__ __forceinline__ void issue_pair(PairRegs<D>& pr, const AttnArgs& a, i
   }
 }
 
-// Block ids of a wave's pairs: lane i holds the id of page (i & 1) of the wave's pair number
-// jbase + i / 2, so one gather serves 32 iterations.
-template <int NW>
-__device__ __forceinline__ int block_window(const AttnArgs& a, const int* bt, int page0, int page1, int wave,
-                                            int jbase, int lane) {
-  const int jj = jbase + (lane >> 1);
-  int P = page0 + 2 * (wave + NW * jj) + (lane & 1);
-  P = min(P, page1 - 1);
-  const int b = bt[P];
-  return min(max(b, 0), a.kv.num_blocks - 1);
-}
+constexpr int BLK_WIN = 2048;  // pages of a segment whose block ids are staged in LDS at once
 
 template <int D, int NT, int NW, bool STREAM>
 __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
@@ -259,23 +359,57 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   int* rowtag = rowslot + ROWS;
   float* wm = (float*)(rowtag + ROWS);                                  // [NW][ROWS]
   float* wl = wm + NW * ROWS;
+  int* blk_lds = (int*)(wl + NW * ROWS);                                // [BLK_WIN] block ids of the window
+  int* pair_counter = blk_lds + BLK_WIN;                                // next pair nobody has taken yet
 
-  __syncthreads();  // LDS of the previous segment is free
-  // ---- Q tile and row descriptors into LDS (padding rows repeat the last row)
-  for (int i = tid; i < ROWS * C::CH; i += THREADS) {
-    const int r = i / C::CH, ch = i - r * C::CH;
-    const int rr = min(r, R - 1);
-    const int q = it.q0 + rr / a.G;
-    const int head = it.h * a.G + rr % a.G;
-    const u32x4* src = (const u32x4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + ch;
-    qtile[k_swz<D>(r, ch)] = *src;
+  // ---- segment start-up.  Three dependent memory round trips are needed at least (lengths ->
+  // block ids -> pages); the Q rows and row descriptors are fetched alongside the block ids.
+  const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
+  const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
+  constexpr int BPT = BLK_WIN / THREADS;  // block ids per thread and window
+  int blkreg[BPT];
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) {
+    const int P = min(page0 + tid + k * THREADS, page1 - 1);
+    blkreg[k] = bt[P];
   }
+  constexpr int QL = (ROWS * C::CH + THREADS - 1) / THREADS;  // Q chunks per thread (padding rows repeat the last row)
+  u32x4 qreg[QL];
+#pragma unroll
+  for (int k = 0; k < QL; ++k) {
+    const int i = tid + k * THREADS;
+    if (i < ROWS * C::CH) {
+      const int r = i / C::CH, ch = i - r * C::CH;
+      const int rr = min(r, R - 1);
+      const int q = it.q0 + rr / a.G;
+      const int head = it.h * a.G + rr % a.G;
+      qreg[k] = *((const u32x4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + ch);
+    }
+  }
+  int d_slot = 0, d_tag = 0;
   if (tid < ROWS) {
     const int rr = min(tid, R - 1);
     const int q = it.q0 + rr / a.G;
-    rowslot[tid] = a.logical_slot[q];
+    d_slot = a.logical_slot[q];
     const int qb = a.q_branch[q];
-    rowtag[tid] = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
+    d_tag = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
+  }
+
+  __syncthreads();  // LDS of the previous segment is free
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) blk_lds[tid + k * THREADS] = min(max(blkreg[k], 0), a.kv.num_blocks - 1);
+  if (tid == 0) *pair_counter = NW;
+#pragma unroll
+  for (int k = 0; k < QL; ++k) {
+    const int i = tid + k * THREADS;
+    if (i < ROWS * C::CH) {
+      const int r = i / C::CH, ch = i - r * C::CH;
+      qtile[k_swz<D>(r, ch)] = qreg[k];
+    }
+  }
+  if (tid < ROWS) {
+    rowslot[tid] = d_slot;
+    rowtag[tid] = d_tag;
   }
   __syncthreads();
 
@@ -317,49 +451,60 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     for (int mt = 0; mt < C::MT; ++mt) acc[n][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // This wave's pairs are wave, wave + NW, ...; `j` counts them.
-  const int npairs = (page1 - page0 + 1) >> 1;
-  const int my_pairs = (npairs > wave) ? (npairs - wave + NW - 1) / NW : 0;
-  const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
-  const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
-
-  int blk_cur = 0, blk_next = 0;
-  if (my_pairs > 0) blk_cur = block_window<NW>(a, bt, page0, page1, wave, 0, lane);
-  if (my_pairs > 32) blk_next = block_window<NW>(a, bt, page0, page1, wave, 32, lane);
-
+  // ---- the stream.  Pairs of pages are handed out dynamically: a wave that gets its data sooner
+  // takes the next pair sooner, so the waves of the workgroup finish together whatever the memory
+  // system does to each of them.  A wave always knows its next pair (and has its loads in flight)
+  // while it computes the current one.
   PairRegs<D> pr;
-  if (my_pairs > 0)
-    issue_pair<D, STREAM>(pr, a, it.h, __builtin_amdgcn_readlane(blk_cur, 0), __builtin_amdgcn_readlane(blk_cur, 1), lane);
-
-  for (int j = 0; j < my_pairs; ++j) {
-    const int pair = wave + NW * j;
-    // ---- registers -> this wave's LDS stage (swizzled)
+  for (int wbase = page0; wbase < page1; wbase += BLK_WIN) {  // windows of block ids; normally one
+    const int wend = min(page1, wbase + BLK_WIN);
+    const int wpages = wend - wbase;
+    const int npairs = (wpages + 1) >> 1;
+    if (wbase != page0) {
+      __syncthreads();  // every wave is done with the previous window's ids and counter
 #pragma unroll
-    for (int i = 0; i < C::LPP; ++i) {
-      // load i of a page is rows i*RPL.. of it: the swizzled position is one of two lane-dependent
-      // bases plus a compile-time offset
-      const int kw = ((i * C::RPL) & 4) ? kw_hi : kw_lo;
-      stage[0 * C::PAGE_U4 + i * 64 + kw] = pr.r[0][i];
-      stage[1 * C::PAGE_U4 + i * 64 + kw] = pr.r[1][i];
-      stage[2 * C::PAGE_U4 + i * 64 + vw] = pr.r[2][i];
-      stage[3 * C::PAGE_U4 + i * 64 + vw] = pr.r[3][i];
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    // ---- the next pair streams in while this one is computed
-    if (j + 1 < my_pairs) {
-      const int jn = j + 1;
-      if ((jn & 31) == 0) {
-        blk_cur = blk_next;
-        if (jn + 32 < my_pairs) blk_next = block_window<NW>(a, bt, page0, page1, wave, jn + 32, lane);
+      for (int k = 0; k < BPT; ++k) {
+        const int P = min(wbase + tid + k * THREADS, page1 - 1);
+        blk_lds[tid + k * THREADS] = min(max(bt[P], 0), a.kv.num_blocks - 1);
       }
-      const int li = __builtin_amdgcn_readfirstlane((jn & 31) * 2);
-      issue_pair<D, STREAM>(pr, a, it.h, __builtin_amdgcn_readlane(blk_cur, li), __builtin_amdgcn_readlane(blk_cur, li + 1),
-                    lane);
+      if (tid == 0) *pair_counter = NW;
+      __syncthreads();
     }
+    auto take = [&]() -> int {  // next pair nobody has taken (may be past the end)
+      int v = 0;
+      if (lane == 0) v = atomicAdd(pair_counter, 1);
+      return __builtin_amdgcn_readfirstlane(v);
+    };
+    auto issue = [&](int p) {
+      const int b0 = __builtin_amdgcn_readfirstlane(blk_lds[2 * p]);
+      const int b1 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * p + 1, wpages - 1)]);
+      issue_pair<D, STREAM>(pr, a, it.h, b0, b1, lane);
+    };
+    int cur = wave;
+    if (cur < npairs) issue(cur);
+    int nxt = take();
+    while (cur < npairs) {
+      // ---- registers -> this wave's LDS stage (swizzled)
+#pragma unroll
+      for (int i = 0; i < C::LPP; ++i) {
+        // load i of a page is rows i*RPL.. of it: the swizzled position is one of two lane-dependent
+        // bases plus a compile-time offset
+        const int kw = ((i * C::RPL) & 4) ? kw_hi : kw_lo;
+        stage[0 * C::PAGE_U4 + i * 64 + kw] = pr.r[0][i];
+        stage[1 * C::PAGE_U4 + i * 64 + kw] = pr.r[1][i];
+        stage[2 * C::PAGE_U4 + i * 64 + vw] = pr.r[2][i];
+        stage[3 * C::PAGE_U4 + i * 64 + vw] = pr.r[3][i];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      // ---- the next pair streams in while this one is computed
+      const int pair = cur;
+      if (nxt < npairs) issue(nxt);
+      cur = nxt;
+      nxt = take();
 
-    const int P0 = page0 + 2 * pair;
-    const bool second_valid = (P0 + 1) < page1;
+      const int P0 = wbase + 2 * pair;
+      const bool second_valid = (P0 + 1) < wend;
 
     // ---- S^T = K Q^T for both pages.  LDS operands are fetched KB k-steps (VB d-tiles below) at a
     // time: large batches hide the LDS latency, small ones leave registers to wide row groups.
@@ -489,6 +634,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
 #undef ASPD_V_UNIT
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
+    }
   }
 
   // ---- combine the waves of the workgroup
@@ -502,7 +648,9 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     }
   }
   __syncthreads();  // also: every wave is done with its stage, which `red` aliases from here on
-  float* red = (float*)smem;  // [NW][16][D]
+  float* red = (float*)smem;  // [NW][16][D + 4]: rows padded by four banks so that the 16 rows a wave
+                              // writes at once fall on different banks
+  constexpr int RS = D + 4;
 #pragma unroll
   for (int n = 0; n < NT; ++n) {
     {
@@ -513,7 +661,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
 #pragma unroll
       for (int mt = 0; mt < C::MT; ++mt) {
         f32x4 v = acc[n][mt] * f;
-        *(f32x4*)&red[(wave * 16 + c) * D + 16 * mt + 4 * g] = v;
+        *(f32x4*)&red[(wave * 16 + c) * RS + 16 * mt + 4 * g] = v;
       }
     }
     __syncthreads();
@@ -534,7 +682,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
       for (int e = 0; e < PER; ++e) {
         o[e] = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) o[e] += red[(w * 16 + row) * D + d0 + e];
+        for (int w = 0; w < NW; ++w) o[e] += red[(w * 16 + row) * RS + d0 + e];
       }
       if (r < R) {
         if (complete) {
@@ -566,7 +714,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
 template <int D, int NT, int NW>
 size_t bf16_smem_bytes(int B) {
   return NW * Bf16Cfg<D>::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
-         (size_t)(B + 1) * 4;
+         (BLK_WIN + 4) * 4 + (size_t)sched_ints(B) * 4;
 }
 
 template <int D, int NT, int NW, bool STREAM>
@@ -576,21 +724,24 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   using C = Bf16Cfg<D>;
   constexpr int THREADS = NW * 64;
   // after the stages, the Q tile, row descriptors and wave statistics: the unit scan
-  int* cu_units = (int*)(smem + NW * C::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4);
+  int* sched_base = (int*)(smem + NW * C::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
+                          (BLK_WIN + 4) * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
-  const int total = build_units<THREADS>(a, cu_units, scratch);
-  const int chunk = chunk_of(total, a.nwg);
-  const int begin = blockIdx.x * chunk;
-  const int end = min(total, begin + chunk);
-  int u = begin;
+  const Sched sc = sched_at(sched_base, a.B);
+  int min_np;
+  const int total = build_units<THREADS>(a, sc, scratch, &min_np);
+  const Shares sh = make_shares(total, a.nwg, min_np);
+  if ((int)blockIdx.x >= sh.n) return;
+  const int end = share_begin(a, sc, sh, blockIdx.x + 1);
+  int u = share_begin(a, sc, sh, blockIdx.x);
   while (u < end) {
     int page0;
-    const Item it = locate(a, cu_units, u, &page0);
+    const Item it = locate(a, sc, u, &page0);
     const int page1 = min(it.np, page0 + (end - u));
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    segment_bf16<D, NT, NW, STREAM>(a, smem, it, page0, page1, a.stage_base[it.s], complete, pslot);
-    if (!complete) announce_partial<D, true, THREADS>(a, it, chunk, &merge_flag);
+    segment_bf16<D, NT, NW, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
+    if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, &merge_flag);
     u += page1 - page0;
   }
 }
@@ -728,29 +879,31 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
 
 template <int D>
 size_t f32_smem_bytes(int B) {
-  return F32_ROWS * D * 4 + 2 * F32_ROWS * 4 + (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4 + (size_t)(B + 1) * 4;
+  return F32_ROWS * D * 4 + 2 * F32_ROWS * 4 + (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4 + (size_t)sched_ints(B) * 4;
 }
 
 template <int D>
 __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int merge_flag;
-  int* cu_units = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4 +
-                         (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4);
+  int* sched_base = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4 +
+                          (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4);
   int* scratch = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4);  // idle until the first segment ends
-  const int total = build_units<THREADS>(a, cu_units, scratch);
-  const int chunk = chunk_of(total, a.nwg);
-  const int begin = blockIdx.x * chunk;
-  const int end = min(total, begin + chunk);
-  int u = begin;
+  const Sched sc = sched_at(sched_base, a.B);
+  int min_np;
+  const int total = build_units<THREADS>(a, sc, scratch, &min_np);
+  const Shares sh = make_shares(total, a.nwg, min_np);
+  if ((int)blockIdx.x >= sh.n) return;
+  const int end = share_begin(a, sc, sh, blockIdx.x + 1);
+  int u = share_begin(a, sc, sh, blockIdx.x);
   while (u < end) {
     int page0;
-    const Item it = locate(a, cu_units, u, &page0);
+    const Item it = locate(a, sc, u, &page0);
     const int page1 = min(it.np, page0 + (end - u));
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    segment_f32<D>(a, smem, it, page0, page1, a.stage_base[it.s], complete, pslot);
-    if (!complete) announce_partial<D, false, THREADS>(a, it, chunk, &merge_flag);
+    segment_f32<D>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
+    if (!complete) announce_partial<D, false, THREADS>(a, sc, it, sh, &merge_flag);
     u += page1 - page0;
   }
 }
@@ -765,69 +918,93 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
 template <int D, bool BF16, int THREADS>
 __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_last) {
   constexpr int CPR = D / 4;  // float4 chunks per row
-  constexpr int BATCH = 8;    // partials fetched at once
+  constexpr int BATCH = 8;    // partials fetched at once, per element
+  constexpr int ELEMS = 2;    // (row, chunk) elements a thread combines concurrently
   const int R = it.nq * a.G;
   const long stride = (long)a.rows_cap * (D + 4);
   const int nparts = w_last - owner + 1;
-  for (int i = threadIdx.x; i < R * CPR; i += THREADS) {
-    const int r = i / CPR, cc = i - r * CPR;
-    float m = -INFINITY, l = 0.f;
-    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+  const int total = R * CPR;
+  // The loads bypass the local L2 and are latency-bound: a thread keeps the loads of up to ELEMS
+  // elements x BATCH partials in flight at once.
+  for (int i0 = threadIdx.x; i0 < total; i0 += ELEMS * THREADS) {
+    int r[ELEMS], cc[ELEMS];
+    float m[ELEMS], l[ELEMS];
+    f32x4 o[ELEMS];
+#pragma unroll
+    for (int x = 0; x < ELEMS; ++x) {
+      const int i = min(i0 + x * THREADS, total - 1);  // a clamped duplicate is computed and not stored
+      r[x] = i / CPR;
+      cc[x] = i - r[x] * CPR;
+      m[x] = -INFINITY;
+      l[x] = 0.f;
+      o[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     for (int p0 = 0; p0 < nparts; p0 += BATCH) {
-      float pm[BATCH], pl[BATCH];
-      f32x4 po[BATCH];
+      float pm[ELEMS][BATCH], pl[ELEMS][BATCH];
+      f32x4 po[ELEMS][BATCH];
 #pragma unroll
-      for (int k = 0; k < BATCH; ++k) {
-        const int ww = owner + min(p0 + k, nparts - 1);
-        const float* p = a.partial + (long)(2 * ww + (ww == owner ? 1 : 0)) * stride + (long)r * (D + 4);
-        pm[k] = load_device_scope(p + D);
-        pl[k] = load_device_scope(p + D + 1);
+      for (int x = 0; x < ELEMS; ++x) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) po[k][e] = load_device_scope(p + 4 * cc + e);
-      }
-      float mb = m;
+        for (int k = 0; k < BATCH; ++k) {
+          const int ww = owner + min(p0 + k, nparts - 1);
+          const float* p = a.partial + (long)(2 * ww + (ww == owner ? 1 : 0)) * stride + (long)r[x] * (D + 4);
+          pm[x][k] = load_device_scope(p + D);
+          pl[x][k] = load_device_scope(p + D + 1);
 #pragma unroll
-      for (int k = 0; k < BATCH; ++k)
-        if (p0 + k < nparts) mb = fmaxf(mb, pm[k]);
-      const float mref = exp2_safe_ref(mb);
-      const float f0 = __builtin_amdgcn_exp2f(m - mref);
-      l *= f0;
-      o *= f0;
-#pragma unroll
-      for (int k = 0; k < BATCH; ++k) {
-        if (p0 + k < nparts) {
-          const float f = __builtin_amdgcn_exp2f(pm[k] - mref);
-          l += pl[k] * f;
-          o += po[k] * f;
+          for (int e = 0; e < 4; ++e) po[x][k][e] = load_device_scope(p + 4 * cc[x] + e);
         }
       }
-      m = mb;
-    }
-    const int q = it.q0 + r / a.G;
-    const int head = it.h * a.G + r % a.G;
-    const long oi = ((long)q * a.kv.num_q_heads + head) * D + 4 * cc;
-    const float inv = 1.f / l;
-    if (BF16) {
-      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-      bf16x4 ov;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(o[e] * inv);
-      *(bf16x4*)((__bf16*)a.out + oi) = ov;
-    } else {
-      *(f32x4*)((float*)a.out + oi) = o * inv;
+      for (int x = 0; x < ELEMS; ++x) {
+        float mb = m[x];
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k)
+          if (p0 + k < nparts) mb = fmaxf(mb, pm[x][k]);
+        const float mref = exp2_safe_ref(mb);
+        const float f0 = __builtin_amdgcn_exp2f(m[x] - mref);
+        l[x] *= f0;
+        o[x] *= f0;
+#pragma unroll
+        for (int k = 0; k < BATCH; ++k) {
+          if (p0 + k < nparts) {
+            const float f = __builtin_amdgcn_exp2f(pm[x][k] - mref);
+            l[x] += pl[x][k] * f;
+            o[x] += po[x][k] * f;
+          }
+        }
+        m[x] = mb;
+      }
     }
-    if (a.lse && cc == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (m + log2f(l)) * LN2;
+#pragma unroll
+    for (int x = 0; x < ELEMS; ++x) {
+      if (i0 + x * THREADS >= total) continue;
+      const int q = it.q0 + r[x] / a.G;
+      const int head = it.h * a.G + r[x] % a.G;
+      const long oi = ((long)q * a.kv.num_q_heads + head) * D + 4 * cc[x];
+      const float inv = 1.f / l[x];
+      if (BF16) {
+        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+        bf16x4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(o[x][e] * inv);
+        *(bf16x4*)((__bf16*)a.out + oi) = ov;
+      } else {
+        *(f32x4*)((float*)a.out + oi) = o[x] * inv;
+      }
+      if (a.lse && cc[x] == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (m[x] + log2f(l[x])) * LN2;
+    }
   }
 }
 
 // Called by every thread of the workgroup after it has written a partial of `it`.
 template <int D, bool BF16, int THREADS>
-__device__ void announce_partial(const AttnArgs& a, const Item& it, int chunk, int* flag /* LDS */) {
+__device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh,
+                                 int* flag /* LDS */) {
   // the write-through stores of the partial have completed before the arrival is counted
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  const int owner = it.first_unit / chunk;
-  const int w_last = (it.first_unit + it.np - 1) / chunk;
+  const int owner = share_owner(a, sc, sh, it.first_unit);
+  const int w_last = share_owner(a, sc, sh, it.first_unit + it.np - 1);
   if (threadIdx.x == 0) {
     const int old = atomicAdd(a.counters + owner, 1);
     const int last = (old == w_last - owner) ? 1 : 0;
