@@ -198,8 +198,10 @@ def test_second_parallel_round_sees_first_rounds_branches(A):
 
 # --------------------------------------------------------------------------------------------- invariants on the GPU
 def test_sibling_kv_does_not_reach_a_branch(A):
-    """Perturbing the K/V of sibling branches leaves every output bit-identical (masked weights are
-    exactly zero), Sec. 3.2 "mutual invisibility across branches"."""
+    """Perturbing the K/V of sibling branches (to huge finite values) must not change any output:
+    masked weights are exactly zero, Sec. 3.2 "mutual invisibility across branches".  The bf16 kernel
+    hands page pairs to waves dynamically, so two runs may sum in a different order: outputs are
+    compared to a few bf16 ulps, while a leak of a sibling key would show up at the 1e30 scale."""
     wl = W.random_small(130, batch=2, branches_range=(3, 5), branch_len_range=(5, 30))
     gb, tt = _grow_both(A, wl, wl.branch_len, False)
     ones = np.ones(wl.NB, dtype=np.int32)
@@ -219,10 +221,12 @@ def test_sibling_kv_does_not_reach_a_branch(A):
                 v2[ph // 16, :, ph % 16] = -1e30
         kv2 = A.KVCache(k2, v2, gb.kv.block_tables, gb.kv.num_q_heads)
         out = A.aspd_attn_parallel_decode(kv2, gb.state, step, q, gb.workspace)
-        assert torch.equal(out[r], base[r]), r
+        assert torch.isfinite(out[r].float()).all(), r
+        assert (out[r].float() - base[r].float()).abs().max().item() <= 4e-3, r
 
 
-def test_repeat_calls_are_deterministic(A):
+def test_repeat_calls_agree(A):
+    """Two runs of the same call agree to rounding (see the note on summation order above)."""
     wl = W.random_small(131, batch=4)
     gb, tt = _grow_both(A, wl, wl.branch_len, False)
     ones = np.ones(wl.NB, dtype=np.int32)
@@ -230,7 +234,35 @@ def test_repeat_calls_are_deterministic(A):
     q = wl.draw_q(step.NQ).to(gb.dev)
     a = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace).clone()
     b = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace)
+    assert (a.float() - b.float()).abs().max().item() <= 4e-3
+
+
+def test_fp32_repeat_calls_are_bit_identical(A):
+    """The fp32 kernel assigns pages to waves statically: same inputs, same bits."""
+    wl = W.random_small(132, dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=4, batch=3)
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    step = gb.parallel(ones)
+    q = wl.draw_q(step.NQ).to(gb.dev)
+    a = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace).clone()
+    b = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace)
     assert torch.equal(a, b)
+
+
+def test_hint_does_not_change_results(A):
+    """max_new_per_seq only sizes the row tile: a wrong or missing hint gives the same result."""
+    wl = W.random_small(133, batch=3, branches_range=(5, 7))
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    q = wl.draw_q(meta.NQ)
+    ref, _ = attend(tt, meta, q, wl.k_cache, wl.v_cache)
+    for hint in (0, 1, 2, 7, 100):
+        step.max_new_per_seq = hint
+        out = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace)
+        err = np.abs(out.float().cpu().numpy() - ref).max()
+        assert err <= TOL[wl.dtype], (hint, err)
 
 
 # --------------------------------------------------------------------------------------------- faults (host-forced)
