@@ -277,6 +277,16 @@ __device__ __forceinline__ void store_device_scope(float* p, float v) {
 __device__ __forceinline__ float load_device_scope(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// The same write-through store, 16 or 8 bytes wide (4-byte write-through stores cost a partial-line
+// write each).  Callers order it like the 4-byte form: a later s_waitcnt vmcnt(0) covers it.
+__device__ __forceinline__ void store_device_scope_x4(float* p, f32x4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_device_scope_x2(float* p, float a, float b) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  const f32x2 v = {a, b};
+  asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+}
 
 // ---------------------------------------------------------------------------------------------
 // bf16 path: MFMA 16x16x32, transposed scores.
@@ -698,12 +708,13 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
           if (a.lse && d0 == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (mg + log2f(lg)) * LN2;
         } else {
           float* dst = pslot + (long)r * (D + 4);
+          if constexpr (PER == 4) {
+            store_device_scope_x4(dst + d0, f32x4{o[0], o[1], o[2], o[3]});
+          } else {
 #pragma unroll
-          for (int e = 0; e < PER; ++e) store_device_scope(dst + d0 + e, o[e]);
-          if (d0 == 0) {
-            store_device_scope(dst + D, mg);
-            store_device_scope(dst + D + 1, lg);
+            for (int e = 0; e < PER; e += 2) store_device_scope_x2(dst + d0 + e, o[e], o[e + 1]);
           }
+          if (d0 == 0) store_device_scope_x2(dst + D, mg, lg);
         }
       }
     }
@@ -924,7 +935,7 @@ __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_l
   const long stride = (long)a.rows_cap * (D + 4);
   const int nparts = w_last - owner + 1;
   const int total = R * CPR;
-  // The loads bypass the local L2 and are latency-bound: a thread keeps the loads of up to ELEMS
+  // The loads miss the caches and are latency-bound: a thread keeps the loads of up to ELEMS
   // elements x BATCH partials in flight at once.
   for (int i0 = threadIdx.x; i0 < total; i0 += ELEMS * THREADS) {
     int r[ELEMS], cc[ELEMS];
@@ -948,10 +959,10 @@ __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_l
         for (int k = 0; k < BATCH; ++k) {
           const int ww = owner + min(p0 + k, nparts - 1);
           const float* p = a.partial + (long)(2 * ww + (ww == owner ? 1 : 0)) * stride + (long)r[x] * (D + 4);
-          pm[x][k] = load_device_scope(p + D);
-          pl[x][k] = load_device_scope(p + D + 1);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) po[x][k][e] = load_device_scope(p + 4 * cc[x] + e);
+          const f32x4 ml = *(const f32x4*)(p + D);  // reference, sum, padding
+          pm[x][k] = ml[0];
+          pl[x][k] = ml[1];
+          po[x][k] = *(const f32x4*)(p + 4 * cc[x]);
         }
       }
 #pragma unroll
@@ -1013,6 +1024,13 @@ __device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item&
   }
   __syncthreads();
   if (*flag == 0) return;
+  // Only the merging workgroup pays for an acquire at device scope (it drops whatever stale copies of
+  // the partial slots its caches may hold from earlier launches); the partials themselves were
+  // written through by their producers, so ordinary wide loads now fetch them.
+  // One wave issues it for the workgroup: the invalidate acts on the compute unit's L1 and the XCD's L2,
+  // which all waves of the workgroup share.
+  if (threadIdx.x < 64) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  __syncthreads();
   merge_item<D, BF16, THREADS>(a, it, owner, w_last);
 }
 
