@@ -28,8 +28,16 @@ namespace {
 
 constexpr int NW = 4;                 // waves per workgroup, fp32 kernel (two workgroups per compute unit)
 constexpr int THREADS = NW * 64;
-constexpr int NW_BF16 = 8;            // waves per workgroup, bf16 kernel (one workgroup per compute unit:
-                                      // half as many partials to combine for a split item)
+// bf16 kernel, one workgroup per compute unit.  Row groups of one 16-row tile: 8 waves (two per SIMD),
+// one page pair in flight per wave.  Wider row groups: 4 waves (one per SIMD, so 512 registers each),
+// three pairs in flight per wave: their longer compute per pair would otherwise leave the memory
+// pipeline idle, and their accumulators do not fit next to the loads in flight in 256 registers.
+#ifndef ASPD_TUNE_NW1
+#define ASPD_TUNE_NW1 8
+#define ASPD_TUNE_PF1 1
+#endif
+#define BF16_NW(NT_) ((NT_) == 1 ? ASPD_TUNE_NW1 : 4)
+#define BF16_PF(NT_) ((NT_) == 1 ? ASPD_TUNE_PF1 : ((NT_) == 2 ? 3 : 2))
 constexpr int NT_MAX = 3;             // 16-row MFMA tiles per row group (bf16 path)
 constexpr int BF16_ROWS = 16 * NT_MAX;
 constexpr int F32_ROWS = 4;           // rows per row group (fp32 vector path)
@@ -318,13 +326,16 @@ __device__ __forceinline__ int v_swz(int row, int chunk) {
 template <int D>
 struct PairRegs {
   u32x4 r[4][Bf16Cfg<D>::LPP];
+  uint32_t own[2];  // owner tags of this lane's four keys in either page (pairs that need masking only)
 };
 
 // STREAM: the pages are read once by this launch, so they are fetched with non-temporal loads, which
 // on this device sustain a visibly higher read rate than ordinary loads; launches that revisit pages
 // (several row groups per KV head) use ordinary loads and find them in the L2 / memory-side cache.
 template <int D, bool STREAM>
-__device__ __forceinline__ void issue_pair(PairRegs<D>& pr, const AttnArgs& a, int h, int b0, int b1, int lane) {
+__device__ __forceinline__ void issue_pair(PairRegs<D>& pr, const AttnArgs& a, int h, int b0, int b1, int lane,
+                                           const uint8_t* own_p0 /* tags of the lane's keys in page 0, or null */,
+                                           int own_step /* bytes from there to the same keys in page 1 */) {
   using C = Bf16Cfg<D>;
   const long o0 = ((long)b0 * a.kv.num_kv_heads + h) * C::PAGE_U4 + lane;
   const long o1 = ((long)b1 * a.kv.num_kv_heads + h) * C::PAGE_U4 + lane;
@@ -346,11 +357,16 @@ __device__ __forceinline__ void issue_pair(PairRegs<D>& pr, const AttnArgs& a, i
       pr.r[3][i] = v1[i * 64];
     }
   }
+  // Fetched with the pages, so that waiting for the tags never means waiting for younger pairs.
+  if (own_p0) {
+    pr.own[0] = *(const uint32_t*)own_p0;
+    pr.own[1] = *(const uint32_t*)(own_p0 + own_step);
+  }
 }
 
 constexpr int BLK_WIN = 2048;  // pages of a segment whose block ids are staged in LDS at once
 
-template <int D, int NT, int NW, bool STREAM>
+template <int D, int NT, int NW, int PF, bool STREAM>
 __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
                              bool complete, float* pslot) {
   using C = Bf16Cfg<D>;
@@ -408,7 +424,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   __syncthreads();  // LDS of the previous segment is free
 #pragma unroll
   for (int k = 0; k < BPT; ++k) blk_lds[tid + k * THREADS] = min(max(blkreg[k], 0), a.kv.num_blocks - 1);
-  if (tid == 0) *pair_counter = NW;
+  if (tid == 0) *pair_counter = 0;
 #pragma unroll
   for (int k = 0; k < QL; ++k) {
     const int i = tid + k * THREADS;
@@ -463,9 +479,18 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
 
   // ---- the stream.  Pairs of pages are handed out dynamically: a wave that gets its data sooner
   // takes the next pair sooner, so the waves of the workgroup finish together whatever the memory
-  // system does to each of them.  A wave always knows its next pair (and has its loads in flight)
-  // while it computes the current one.
-  PairRegs<D> pr;
+  // system does to each of them.  A wave keeps PF pairs in flight in a ring of register sets (the
+  // ring is unrolled so that every set has fixed registers); the set it has just emptied into its
+  // LDS stage is refilled at once, before the pair is computed.
+  PairRegs<D> pr[PF];
+  int idx[PF];
+  // owner tags are needed (and fetched) only for pairs that reach past mask_from
+  auto own_ptr = [&](int P0) -> const uint8_t* {
+    return (owner_row && (P0 + 2) * ASPD_BLOCK > mask_from) ? owner_row + P0 * ASPD_BLOCK + 4 * g : nullptr;
+  };
+  auto own_step = [&](int P0) -> int {
+    return min(ASPD_BLOCK, a.owner_stride - 4 - (P0 * ASPD_BLOCK + 4 * g));  // stays inside the owner row
+  };
   for (int wbase = page0; wbase < page1; wbase += BLK_WIN) {  // windows of block ids; normally one
     const int wend = min(page1, wbase + BLK_WIN);
     const int wpages = wend - wbase;
@@ -477,7 +502,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
         const int P = min(wbase + tid + k * THREADS, page1 - 1);
         blk_lds[tid + k * THREADS] = min(max(bt[P], 0), a.kv.num_blocks - 1);
       }
-      if (tid == 0) *pair_counter = NW;
+      if (tid == 0) *pair_counter = 0;
       __syncthreads();
     }
     auto take = [&]() -> int {  // next pair nobody has taken (may be past the end)
@@ -485,41 +510,58 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
       if (lane == 0) v = atomicAdd(pair_counter, 1);
       return __builtin_amdgcn_readfirstlane(v);
     };
-    auto issue = [&](int p) {
-      const int b0 = __builtin_amdgcn_readfirstlane(blk_lds[2 * p]);
-      const int b1 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * p + 1, wpages - 1)]);
-      issue_pair<D, STREAM>(pr, a, it.h, b0, b1, lane);
-    };
-    int cur = wave;
-    if (cur < npairs) issue(cur);
-    int nxt = take();
-    while (cur < npairs) {
+#pragma unroll
+    for (int sl = 0; sl < PF; ++sl) {
+      idx[sl] = take();
+      if (idx[sl] < npairs) {
+        const int b0 = __builtin_amdgcn_readfirstlane(blk_lds[2 * idx[sl]]);
+        const int b1 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * idx[sl] + 1, wpages - 1)]);
+        issue_pair<D, STREAM>(pr[sl], a, it.h, b0, b1, lane, own_ptr(wbase + 2 * idx[sl]), own_step(wbase + 2 * idx[sl]));
+      }
+    }
+    int ahead = take();  // always one hand-out ahead, so that a refill never waits for the counter
+    bool more = true;
+    while (more) {
+#pragma unroll
+      for (int sl = 0; sl < PF; ++sl) {
+        // pairs are handed out in increasing order: once the oldest outstanding one is past the end,
+        // all are
+        if (idx[sl] >= npairs) {
+          more = false;
+          break;
+        }
       // ---- registers -> this wave's LDS stage (swizzled)
 #pragma unroll
       for (int i = 0; i < C::LPP; ++i) {
         // load i of a page is rows i*RPL.. of it: the swizzled position is one of two lane-dependent
         // bases plus a compile-time offset
         const int kw = ((i * C::RPL) & 4) ? kw_hi : kw_lo;
-        stage[0 * C::PAGE_U4 + i * 64 + kw] = pr.r[0][i];
-        stage[1 * C::PAGE_U4 + i * 64 + kw] = pr.r[1][i];
-        stage[2 * C::PAGE_U4 + i * 64 + vw] = pr.r[2][i];
-        stage[3 * C::PAGE_U4 + i * 64 + vw] = pr.r[3][i];
+        stage[0 * C::PAGE_U4 + i * 64 + kw] = pr[sl].r[0][i];
+        stage[1 * C::PAGE_U4 + i * 64 + kw] = pr[sl].r[1][i];
+        stage[2 * C::PAGE_U4 + i * 64 + vw] = pr[sl].r[2][i];
+        stage[3 * C::PAGE_U4 + i * 64 + vw] = pr[sl].r[3][i];
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      // ---- the next pair streams in while this one is computed
-      const int pair = cur;
-      if (nxt < npairs) issue(nxt);
-      cur = nxt;
-      nxt = take();
+      // ---- refill the set: the next pair streams in while this one is computed
+      const int pair = idx[sl];
+      idx[sl] = ahead;
+      const uint32_t own0 = pr[sl].own[0], own1 = pr[sl].own[1];  // of the pair about to be computed
+      if (ahead < npairs) {
+        const int b0 = __builtin_amdgcn_readfirstlane(blk_lds[2 * ahead]);
+        const int b1 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * ahead + 1, wpages - 1)]);
+        issue_pair<D, STREAM>(pr[sl], a, it.h, b0, b1, lane, own_ptr(wbase + 2 * ahead), own_step(wbase + 2 * ahead));
+      }
+      ahead = take();
 
       const int P0 = wbase + 2 * pair;
       const bool second_valid = (P0 + 1) < wend;
 
     // ---- S^T = K Q^T for both pages.  LDS operands are fetched KB k-steps (VB d-tiles below) at a
     // time: large batches hide the LDS latency, small ones leave registers to wide row groups.
-    constexpr int KB = (NT == 1) ? C::KSTEPS : (NT == 2 ? 2 : 1);
-    constexpr int VB = (NT == 1) ? C::MT : (NT == 2 ? 4 : 2);
+    constexpr bool ROOMY = (NW <= 4);  // one wave per SIMD: 512 registers
+    constexpr int KB = (NT == 1 || ROOMY) ? C::KSTEPS : (NT == 2 ? 2 : 1);
+    constexpr int VB = (NT == 1 || ROOMY) ? C::MT : (NT == 2 ? 4 : 2);
     f32x4 st[2][NT];
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
@@ -562,11 +604,6 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     // ---- mask (only pages that reach into the branch region or the tail need it)
     const int slot0 = P0 * ASPD_BLOCK + 4 * g;  // first of this lane's four keys in page 0
     const bool need_mask = (P0 + 2) * ASPD_BLOCK > mask_from || !second_valid;
-    uint32_t own0 = 0, own1 = 0;
-    if (need_mask && owner_row) {
-      own0 = *(const uint32_t*)(owner_row + slot0);
-      own1 = *(const uint32_t*)(owner_row + min(slot0 + ASPD_BLOCK, a.owner_stride - 4));
-    }
 
     // Running softmax with a lazily updated reference: m_run[n] is a per-row reference exponent
     // (log2 domain, scaled scores), not necessarily the row maximum.  It is raised, and the
@@ -644,6 +681,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
 #undef ASPD_V_UNIT
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
+      }
     }
   }
 
@@ -728,8 +766,9 @@ size_t bf16_smem_bytes(int B) {
          (BLK_WIN + 4) * 4 + (size_t)sched_ints(B) * 4;
 }
 
-template <int D, int NT, int NW, bool STREAM>
-__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bf16_kernel(AttnArgs a) {
+template <int D, int NT, int NW, int PF, bool STREAM>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void attn_bf16_kernel(
+    AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int merge_flag;
   using C = Bf16Cfg<D>;
@@ -751,7 +790,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int page1 = min(it.np, page0 + (end - u));
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    segment_bf16<D, NT, NW, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
+    segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
     if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, &merge_flag);
     u += page1 - page0;
   }
@@ -1158,11 +1197,11 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
 #define ASPD_BF16_CASE(DD, NN)                                                                            \
   do {                                                                                                    \
     if (stream_once)                                                                                      \
-      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, NW_BF16, true>), NW_BF16 * 64,                                \
-                  (bf16_smem_bytes<DD, NN, NW_BF16>(state->B)));                                          \
+      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, BF16_NW(NN), BF16_PF(NN), true>), BF16_NW(NN) * 64,           \
+                  (bf16_smem_bytes<DD, NN, BF16_NW(NN)>(state->B)));                                      \
     else                                                                                                  \
-      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, NW_BF16, false>), NW_BF16 * 64,                               \
-                  (bf16_smem_bytes<DD, NN, NW_BF16>(state->B)));                                          \
+      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, BF16_NW(NN), BF16_PF(NN), false>), BF16_NW(NN) * 64,          \
+                  (bf16_smem_bytes<DD, NN, BF16_NW(NN)>(state->B)));                                      \
   } while (0)
     if (D == 128) {
       if (nt == 1) ASPD_BF16_CASE(128, 1);
