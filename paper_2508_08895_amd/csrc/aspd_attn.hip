@@ -42,6 +42,8 @@ constexpr int NT_MAX = 3;             // 16-row MFMA tiles per row group (bf16 p
 constexpr int BF16_ROWS = 16 * NT_MAX;
 constexpr int F32_ROWS = 4;           // rows per row group (fp32 vector path)
 constexpr int MIN_PAGES_PER_WG = 16;  // do not split finer than this
+constexpr int ROWS_NW = 8;            // waves per workgroup of the row-splitting (chunk) kernel
+constexpr int MAX_WG_ROWS = 256;      // its largest grid (its partial slots are ROWS_NW * 48 rows each)
 constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
 constexpr int MAX_WG = 1024;          // upper bound of the grid (workspace is sized for it)
 constexpr float LOG2E = 1.4426950408889634f;
@@ -364,6 +366,146 @@ __device__ __forceinline__ void issue_pair(PairRegs<D>& pr, const AttnArgs& a, i
   }
 }
 
+// Running state of the rows one wave owns: output accumulators (transposed: [d][row]), softmax
+// reference and sum per row, and what each row may see.
+template <int D, int NT>
+struct RowState {
+  f32x4 acc[NT][D / 16];
+  float m_run[NT], l_run[NT];
+  int slot[NT], tag[NT];
+};
+
+// One pair of pages (32 keys) against NT 16-row tiles: scores, mask, running softmax, accumulation.
+// `stage` holds K page 0, K page 1, V page 0, V page 1 (swizzled), `qtile` the rows' Q (swizzled).
+// kr_even / kr_odd / vu are the lane's LDS bases (see the caller).  KB k-steps of K and VB d-tiles of
+// V are fetched from LDS at a time: large batches hide the LDS latency, small ones save registers.
+template <int D, int NT, int KB, int VB>
+__device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qtile, RowState<D, NT>& ts,
+                                             int kr_even, int kr_odd, const int (&vu)[4], int g, int L,
+                                             int mask_from, int P0, bool second_valid, uint32_t own0,
+                                             uint32_t own1, float scale_log2) {
+  using C = Bf16Cfg<D>;
+    // ---- S^T = K Q^T for both pages.  LDS operands are fetched KB k-steps (VB d-tiles below) at a
+    // time: large batches hide the LDS latency, small ones leave registers to wide row groups.
+    f32x4 st[2][NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+      st[0][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+      st[1][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int t0 = 0; t0 < C::KSTEPS; t0 += KB) {
+      bf16x8 ka[KB], kb[KB];
+#pragma unroll
+      for (int tt = 0; tt < KB; ++tt) {
+        const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
+        ka[tt] = *(const bf16x8*)&stage[0 * C::PAGE_U4 + kr];
+        kb[tt] = *(const bf16x8*)&stage[1 * C::PAGE_U4 + kr];
+      }
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+#pragma unroll
+        for (int tt = 0; tt < KB; ++tt) {
+          const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
+          const bf16x8 qb = *(const bf16x8*)&qtile[16 * n * C::CH + kr];
+          st[0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[tt], qb, st[0][n], 0, 0, 0);
+          st[1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[tt], qb, st[1][n], 0, 0, 0);
+        }
+      }
+    }
+
+    // ---- V^T operands through the LDS transpose read; the first batch is issued ahead of the
+    // softmax so that its latency is hidden
+    const s16x4* vs0 = (const s16x4*)(stage + 2 * C::PAGE_U4);
+    const s16x4* vs1 = (const s16x4*)(stage + 3 * C::PAGE_U4);
+#define ASPD_V_UNIT(mt) (vu[(mt) & 3] + 16 * ((mt) >> 2))
+    s16x4 va[VB], vb[VB];
+#pragma unroll
+    for (int mm = 0; mm < VB; ++mm) {
+      va[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs0 + ASPD_V_UNIT(mm)));
+      vb[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs1 + ASPD_V_UNIT(mm)));
+    }
+
+    // ---- mask (only pages that reach into the branch region or the tail need it)
+    const int slot0 = P0 * ASPD_BLOCK + 4 * g;  // first of this lane's four keys in page 0
+    const bool need_mask = (P0 + 2) * ASPD_BLOCK > mask_from || !second_valid;
+
+    // Running softmax with a lazily updated reference: ts.m_run[n] is a per-row reference exponent
+    // (log2 domain, scaled scores), not necessarily the row maximum.  It is raised, and the
+    // accumulators rescaled, only when a score exceeds it by more than LAZY (weights then stay
+    // below 2^LAZY, harmless in fp32 and in the bf16 P operand, whose precision is relative).
+    // The four lanes of a row always hold the same reference.
+    s16x8 pb[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+      float sc[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sc[e] = st[0][n][e];
+        sc[4 + e] = st[1][n][e];
+      }
+      if (need_mask) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int jk = slot0 + (e & 3) + (e >> 2) * ASPD_BLOCK;
+          const int own = (int)(((e < 4 ? own0 : own1) >> (8 * (e & 3))) & 0xff);
+          bool vis = (jk <= ts.slot[n]) && (jk < L || ts.tag[n] == 0 || own == ts.tag[n]);
+          if (e >= 4 && !second_valid) vis = false;
+          sc[e] = vis ? sc[e] : -INFINITY;
+        }
+      }
+      float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+      mx *= scale_log2;  // scale > 0: the maximum commutes with it
+      if (__any(mx > ts.m_run[n] + LAZY)) {
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(ts.m_run[n], mx);
+        const float alpha = __builtin_amdgcn_exp2f(ts.m_run[n] - exp2_safe_ref(m_new));
+        ts.m_run[n] = m_new;
+        ts.l_run[n] *= alpha;
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) ts.acc[n][mt] *= alpha;
+      }
+      const float neg_ref = -exp2_safe_ref(ts.m_run[n]);
+      float psum = 0.f;
+      bf16x8 pv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float w = __builtin_amdgcn_exp2f(fmaf(sc[e], scale_log2, neg_ref));
+        psum += w;
+        pv[e] = (__bf16)w;
+      }
+      ts.l_run[n] += psum;
+      pb[n] = __builtin_bit_cast(s16x8, pv);
+    }
+
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int m0 = 0; m0 < C::MT; m0 += VB) {
+      if (m0 > 0) {
+#pragma unroll
+        for (int mm = 0; mm < VB; ++mm) {
+          va[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(vs0 + ASPD_V_UNIT(m0 + mm)));
+          vb[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(vs1 + ASPD_V_UNIT(m0 + mm)));
+        }
+      }
+#pragma unroll
+      for (int mm = 0; mm < VB; ++mm) {
+        s16x8 v8;
+        v8[0] = va[mm][0]; v8[1] = va[mm][1]; v8[2] = va[mm][2]; v8[3] = va[mm][3];
+        v8[4] = vb[mm][0]; v8[5] = vb[mm][1]; v8[6] = vb[mm][2]; v8[7] = vb[mm][3];
+        const bf16x8 vop = __builtin_bit_cast(bf16x8, v8);
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+          ts.acc[n][m0 + mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, __builtin_bit_cast(bf16x8, pb[n]),
+                                                                    ts.acc[n][m0 + mm], 0, 0, 0);
+      }
+    }
+#undef ASPD_V_UNIT
+}
+
 constexpr int BLK_WIN = 2048;  // pages of a segment whose block ids are staged in LDS at once
 
 template <int D, int NT, int NW, int PF, bool STREAM>
@@ -439,13 +581,13 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   }
   __syncthreads();
 
-  int my_slot[NT], my_tag[NT];
+  RowState<D, NT> ts;
   int mask_from = L;  // keys below this slot are visible to every row of the group
 #pragma unroll
   for (int n = 0; n < NT; ++n) {
-    my_slot[n] = rowslot[16 * n + c];
-    my_tag[n] = rowtag[16 * n + c];
-    mask_from = min(mask_from, my_slot[n]);
+    ts.slot[n] = rowslot[16 * n + c];
+    ts.tag[n] = rowtag[16 * n + c];
+    mask_from = min(mask_from, ts.slot[n]);
   }
 #pragma unroll
   for (int off = 1; off < 16; off <<= 1) mask_from = min(mask_from, __shfl_xor(mask_from, off));
@@ -467,14 +609,12 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
 #pragma unroll
   for (int b = 0; b < 4; ++b) vu[b] = vkey * (D / 4) + (((b ^ (vkey & 3)) << 2) | (c & 3));
 
-  f32x4 acc[NT][C::MT];
-  float m_run[NT], l_run[NT];
 #pragma unroll
   for (int n = 0; n < NT; ++n) {
-    m_run[n] = -INFINITY;
-    l_run[n] = 0.f;
+    ts.m_run[n] = -INFINITY;
+    ts.l_run[n] = 0.f;
 #pragma unroll
-    for (int mt = 0; mt < C::MT; ++mt) acc[n][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int mt = 0; mt < C::MT; ++mt) ts.acc[n][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
   // ---- the stream.  Pairs of pages are handed out dynamically: a wave that gets its data sooner
@@ -557,128 +697,11 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
       const int P0 = wbase + 2 * pair;
       const bool second_valid = (P0 + 1) < wend;
 
-    // ---- S^T = K Q^T for both pages.  LDS operands are fetched KB k-steps (VB d-tiles below) at a
-    // time: large batches hide the LDS latency, small ones leave registers to wide row groups.
-    constexpr bool ROOMY = (NW <= 4);  // one wave per SIMD: 512 registers
-    constexpr int KB = (NT == 1 || ROOMY) ? C::KSTEPS : (NT == 2 ? 2 : 1);
-    constexpr int VB = (NT == 1 || ROOMY) ? C::MT : (NT == 2 ? 4 : 2);
-    f32x4 st[2][NT];
-#pragma unroll
-    for (int n = 0; n < NT; ++n) {
-      st[0][n] = f32x4{0.f, 0.f, 0.f, 0.f};
-      st[1][n] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-#pragma unroll
-    for (int t0 = 0; t0 < C::KSTEPS; t0 += KB) {
-      bf16x8 ka[KB], kb[KB];
-#pragma unroll
-      for (int tt = 0; tt < KB; ++tt) {
-        const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
-        ka[tt] = *(const bf16x8*)&stage[0 * C::PAGE_U4 + kr];
-        kb[tt] = *(const bf16x8*)&stage[1 * C::PAGE_U4 + kr];
-      }
-#pragma unroll
-      for (int n = 0; n < NT; ++n) {
-#pragma unroll
-        for (int tt = 0; tt < KB; ++tt) {
-          const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
-          const bf16x8 qb = *(const bf16x8*)&qtile[16 * n * C::CH + kr];
-          st[0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[tt], qb, st[0][n], 0, 0, 0);
-          st[1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[tt], qb, st[1][n], 0, 0, 0);
-        }
-      }
-    }
-
-    // ---- V^T operands through the LDS transpose read; the first batch is issued ahead of the
-    // softmax so that its latency is hidden
-    const s16x4* vs0 = (const s16x4*)(stage + 2 * C::PAGE_U4);
-    const s16x4* vs1 = (const s16x4*)(stage + 3 * C::PAGE_U4);
-#define ASPD_V_UNIT(mt) (vu[(mt) & 3] + 16 * ((mt) >> 2))
-    s16x4 va[VB], vb[VB];
-#pragma unroll
-    for (int mm = 0; mm < VB; ++mm) {
-      va[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs0 + ASPD_V_UNIT(mm)));
-      vb[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs1 + ASPD_V_UNIT(mm)));
-    }
-
-    // ---- mask (only pages that reach into the branch region or the tail need it)
-    const int slot0 = P0 * ASPD_BLOCK + 4 * g;  // first of this lane's four keys in page 0
-    const bool need_mask = (P0 + 2) * ASPD_BLOCK > mask_from || !second_valid;
-
-    // Running softmax with a lazily updated reference: m_run[n] is a per-row reference exponent
-    // (log2 domain, scaled scores), not necessarily the row maximum.  It is raised, and the
-    // accumulators rescaled, only when a score exceeds it by more than LAZY (weights then stay
-    // below 2^LAZY, harmless in fp32 and in the bf16 P operand, whose precision is relative).
-    // The four lanes of a row always hold the same reference.
-    s16x8 pb[NT];
-#pragma unroll
-    for (int n = 0; n < NT; ++n) {
-      float sc[8];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        sc[e] = st[0][n][e];
-        sc[4 + e] = st[1][n][e];
-      }
-      if (need_mask) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int jk = slot0 + (e & 3) + (e >> 2) * ASPD_BLOCK;
-          const int own = (int)(((e < 4 ? own0 : own1) >> (8 * (e & 3))) & 0xff);
-          bool vis = (jk <= my_slot[n]) && (jk < L || my_tag[n] == 0 || own == my_tag[n]);
-          if (e >= 4 && !second_valid) vis = false;
-          sc[e] = vis ? sc[e] : -INFINITY;
-        }
-      }
-      float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-      mx *= a.scale_log2;  // scale > 0: the maximum commutes with it
-      if (__any(mx > m_run[n] + LAZY)) {
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[n], mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run[n] - exp2_safe_ref(m_new));
-        m_run[n] = m_new;
-        l_run[n] *= alpha;
-#pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) acc[n][mt] *= alpha;
-      }
-      const float neg_ref = -exp2_safe_ref(m_run[n]);
-      float psum = 0.f;
-      bf16x8 pv;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float w = __builtin_amdgcn_exp2f(fmaf(sc[e], a.scale_log2, neg_ref));
-        psum += w;
-        pv[e] = (__bf16)w;
-      }
-      l_run[n] += psum;
-      pb[n] = __builtin_bit_cast(s16x8, pv);
-    }
-
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int m0 = 0; m0 < C::MT; m0 += VB) {
-      if (m0 > 0) {
-#pragma unroll
-        for (int mm = 0; mm < VB; ++mm) {
-          va[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(vs0 + ASPD_V_UNIT(m0 + mm)));
-          vb[mm] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (__attribute__((address_space(3))) s16x4*)(vs1 + ASPD_V_UNIT(m0 + mm)));
-        }
-      }
-#pragma unroll
-      for (int mm = 0; mm < VB; ++mm) {
-        s16x8 v8;
-        v8[0] = va[mm][0]; v8[1] = va[mm][1]; v8[2] = va[mm][2]; v8[3] = va[mm][3];
-        v8[4] = vb[mm][0]; v8[5] = vb[mm][1]; v8[6] = vb[mm][2]; v8[7] = vb[mm][3];
-        const bf16x8 vop = __builtin_bit_cast(bf16x8, v8);
-#pragma unroll
-        for (int n = 0; n < NT; ++n)
-          acc[n][m0 + mm] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, __builtin_bit_cast(bf16x8, pb[n]),
-                                                                    acc[n][m0 + mm], 0, 0, 0);
-      }
-    }
-#undef ASPD_V_UNIT
+      constexpr bool ROOMY = (NW <= 4);  // one wave per SIMD: 512 registers
+      constexpr int KB = (NT == 1 || ROOMY) ? C::KSTEPS : (NT == 2 ? 2 : 1);
+      constexpr int VB = (NT == 1 || ROOMY) ? C::MT : (NT == 2 ? 4 : 2);
+      pair_compute<D, NT, KB, VB>(stage, qtile, ts, kr_even, kr_odd, vu, g, L, mask_from, P0, second_valid, own0,
+                                  own1, a.scale_log2);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
       }
@@ -688,11 +711,11 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   // ---- combine the waves of the workgroup
 #pragma unroll
   for (int n = 0; n < NT; ++n) {
-    l_run[n] += __shfl_xor(l_run[n], 16);
-    l_run[n] += __shfl_xor(l_run[n], 32);
+    ts.l_run[n] += __shfl_xor(ts.l_run[n], 16);
+    ts.l_run[n] += __shfl_xor(ts.l_run[n], 32);
     if (g == 0) {
-      wm[wave * ROWS + 16 * n + c] = m_run[n];
-      wl[wave * ROWS + 16 * n + c] = l_run[n];
+      wm[wave * ROWS + 16 * n + c] = ts.m_run[n];
+      wl[wave * ROWS + 16 * n + c] = ts.l_run[n];
     }
   }
   __syncthreads();  // also: every wave is done with its stage, which `red` aliases from here on
@@ -705,10 +728,10 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
       float mg = -INFINITY;
 #pragma unroll
       for (int w = 0; w < NW; ++w) mg = fmaxf(mg, wm[w * ROWS + 16 * n + c]);
-      const float f = __builtin_amdgcn_exp2f(m_run[n] - exp2_safe_ref(mg));
+      const float f = __builtin_amdgcn_exp2f(ts.m_run[n] - exp2_safe_ref(mg));
 #pragma unroll
       for (int mt = 0; mt < C::MT; ++mt) {
-        f32x4 v = acc[n][mt] * f;
+        f32x4 v = ts.acc[n][mt] * f;
         *(f32x4*)&red[(wave * 16 + c) * RS + 16 * mt + 4 * g] = v;
       }
     }
@@ -791,6 +814,247 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
+    if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, &merge_flag);
+    u += page1 - page0;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// bf16, many rows per KV head (branch chunks): the waves of a workgroup split the ROWS instead of
+// the keys.  Every pair of pages is loaded once per workgroup, cooperatively, into a double-buffered
+// LDS stage that all waves read; each wave keeps its own 16*NT rows (Q tile, accumulators, softmax
+// state) for the whole segment, so there is no reduction across waves.  One barrier per pair.
+// With NW waves a row group holds NW * 16 * NT rows, and the pages of a KV head are fetched once per
+// that many rows.  The product per pair is compute-bound here (rows x 32 keys x D on the MFMA
+// units), which is why the waves share the loads rather than the keys.
+// A wave skips the arithmetic for pairs that none of its rows can see (the chunks and earlier
+// tokens of other branches).
+// ---------------------------------------------------------------------------------------------
+template <int D, int NT, int NW>
+size_t rows_smem_bytes(int B) {
+  return 2 * Bf16Cfg<D>::STAGE_BYTES + (size_t)NW * 16 * NT * D * 2 + 2 * NW * 16 * NT * 4 + (BLK_WIN + 4) * 4 +
+         (size_t)sched_ints(B) * 4;
+}
+
+template <int D, int NT, int NW>
+__device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
+                             bool complete, float* pslot) {
+  using C = Bf16Cfg<D>;
+  constexpr int ROWS = 16 * NT;        // rows per wave
+  constexpr int THREADS = NW * 64;
+  constexpr int PER_PAGE = THREADS / 4;  // threads that share the load of one page
+  static_assert(C::PAGE_U4 % PER_PAGE == 0, "page not divisible among its loaders");
+  constexpr int LPT = C::PAGE_U4 / PER_PAGE;  // 16-byte loads per thread and page
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int c = lane & 15;
+  const int g = lane >> 4;
+  const int R = it.nq * a.G;                       // rows of the whole row group
+  const int Rw = min(ROWS, R - wave * ROWS);       // rows this wave owns (<= 0: none)
+  const bool wave_active = Rw > 0;
+
+  u32x4* stage0 = (u32x4*)smem;                                          // [2][K0 K1 V0 V1]
+  u32x4* qtile = (u32x4*)(smem + 2 * C::STAGE_BYTES) + wave * ROWS * C::CH;  // this wave's [ROWS][CH]
+  int* rowslot = (int*)(smem + 2 * C::STAGE_BYTES + (size_t)NW * ROWS * D * 2);
+  int* rowtag = rowslot + NW * ROWS;
+  int* blk_lds = rowtag + NW * ROWS;
+
+  const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
+  const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
+
+  // ---- start-up: block ids of the first window, this wave's Q rows and row descriptors
+  constexpr int BPT = BLK_WIN / THREADS;
+  int blkreg[BPT];
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) blkreg[k] = bt[min(page0 + tid + k * THREADS, page1 - 1)];
+  constexpr int QL = ROWS * C::CH / 64;  // Q chunks per lane
+  u32x4 qreg[QL];
+#pragma unroll
+  for (int k = 0; k < QL; ++k) {
+    const int i = lane + k * 64;
+    const int r = i / C::CH, ch = i - r * C::CH;
+    const int rr = min(wave * ROWS + r, R - 1);  // padding rows (and idle waves) repeat the last row
+    const int q = it.q0 + rr / a.G;
+    const int head = it.h * a.G + rr % a.G;
+    qreg[k] = *((const u32x4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + ch);
+  }
+  int d_slot = 0, d_tag = 0;
+  if (lane < ROWS) {
+    const int rr = min(wave * ROWS + lane, R - 1);
+    const int q = it.q0 + rr / a.G;
+    d_slot = a.logical_slot[q];
+    const int qb = a.q_branch[q];
+    d_tag = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
+  }
+  __syncthreads();  // LDS of the previous segment is free
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) blk_lds[tid + k * THREADS] = min(max(blkreg[k], 0), a.kv.num_blocks - 1);
+#pragma unroll
+  for (int k = 0; k < QL; ++k) {
+    const int i = lane + k * 64;
+    const int r = i / C::CH, ch = i - r * C::CH;
+    qtile[k_swz<D>(r, ch)] = qreg[k];
+  }
+  if (lane < ROWS) {
+    rowslot[wave * ROWS + lane] = d_slot;
+    rowtag[wave * ROWS + lane] = d_tag;
+  }
+  __syncthreads();
+
+  RowState<D, NT> ts;
+  int mask_from = L;
+  int tag_lo = 0x7fffffff, tag_hi = 0;  // range of branch tags among this wave's rows
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    ts.slot[n] = rowslot[wave * ROWS + 16 * n + c];
+    ts.tag[n] = rowtag[wave * ROWS + 16 * n + c];
+    mask_from = min(mask_from, ts.slot[n]);
+    tag_lo = min(tag_lo, ts.tag[n]);
+    tag_hi = max(tag_hi, ts.tag[n]);
+    ts.m_run[n] = -INFINITY;
+    ts.l_run[n] = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt) ts.acc[n][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) {
+    mask_from = min(mask_from, __shfl_xor(mask_from, off));
+    tag_lo = min(tag_lo, __shfl_xor(tag_lo, off));
+    tag_hi = max(tag_hi, __shfl_xor(tag_hi, off));
+  }
+  mask_from = __builtin_amdgcn_readfirstlane(mask_from);
+  tag_lo = __builtin_amdgcn_readfirstlane(tag_lo);
+  tag_hi = __builtin_amdgcn_readfirstlane(tag_hi);
+
+  // LDS bases of this lane (same swizzles as the streaming kernel)
+  const int kr_even = k_swz<D>(c, g);
+  const int kr_odd = k_swz<D>(c, 4 + g);
+  const int vkey = 4 * g + (c >> 2);
+  int vu[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) vu[b] = vkey * (D / 4) + (((b ^ (vkey & 3)) << 2) | (c & 3));
+  // cooperative load: thread t loads chunks [lt * LPT, lt * LPT + LPT) ... of page (t / PER_PAGE),
+  // consecutive threads consecutive 16 bytes
+  const int lpage = tid / PER_PAGE;          // 0: K0, 1: K1, 2: V0, 3: V1
+  const int lt = tid - lpage * PER_PAGE;
+  int lpos[LPT];                             // swizzled positions inside the page
+#pragma unroll
+  for (int k = 0; k < LPT; ++k) {
+    const int i = lt + k * PER_PAGE;         // chunk index inside the page
+    const int row = i / C::CH, ch = i - row * C::CH;
+    lpos[k] = (lpage < 2) ? k_swz<D>(row, ch) : v_swz<D>(row, ch);
+  }
+
+  u32x4 nxt[LPT];
+  for (int wbase = page0; wbase < page1; wbase += BLK_WIN) {  // windows of block ids; normally one
+    const int wend = min(page1, wbase + BLK_WIN);
+    const int wpages = wend - wbase;
+    const int npairs = (wpages + 1) >> 1;
+    if (wbase != page0) {
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < BPT; ++k)
+        blk_lds[tid + k * THREADS] = min(max(bt[min(wbase + tid + k * THREADS, page1 - 1)], 0), a.kv.num_blocks - 1);
+      __syncthreads();
+    }
+    auto issue = [&](int p) {  // this thread's slice of pair p
+      const int pg = min(2 * p + (lpage & 1), wpages - 1);
+      const int b = blk_lds[pg];
+      const u32x4* src = (const u32x4*)(lpage < 2 ? a.kv.k : a.kv.v) + ((long)b * a.kv.num_kv_heads + it.h) * C::PAGE_U4;
+#pragma unroll
+      for (int k = 0; k < LPT; ++k) nxt[k] = src[lt + k * PER_PAGE];
+    };
+    issue(0);
+    for (int p = 0; p < npairs; ++p) {
+      u32x4* stage = stage0 + (p & 1) * (C::STAGE_BYTES / 16);
+#pragma unroll
+      for (int k = 0; k < LPT; ++k) stage[lpage * C::PAGE_U4 + lpos[k]] = nxt[k];
+      if (p + 1 < npairs) issue(p + 1);
+      __syncthreads();  // the pair is staged; everyone is done with the other buffer's previous pair
+
+      const int P0 = wbase + 2 * p;
+      const bool second_valid = (P0 + 1) < wend;
+      if (!wave_active) continue;
+      const bool need_mask = (P0 + 2) * ASPD_BLOCK > mask_from || !second_valid;
+      uint32_t own0 = 0, own1 = 0;
+      if (need_mask && owner_row) {
+        const int slot0 = P0 * ASPD_BLOCK + 4 * g;
+        own0 = *(const uint32_t*)(owner_row + slot0);
+        own1 = *(const uint32_t*)(owner_row + min(slot0 + ASPD_BLOCK, a.owner_stride - 4));
+        // pairs wholly inside the branch region: skip if no key belongs to a branch of this wave's rows
+        if (P0 * ASPD_BLOCK >= L && tag_lo > 0) {
+          bool mine = false;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int own = (int)(((e < 4 ? own0 : own1) >> (8 * (e & 3))) & 0xff);
+            mine |= (own >= tag_lo && own <= tag_hi);
+          }
+          if (!__any(mine)) continue;
+        }
+      }
+      constexpr int KB = (NT == 1) ? C::KSTEPS : (NT == 2 ? 2 : 1);
+      constexpr int VB = (NT == 1) ? C::MT : (NT == 2 ? 4 : 2);
+      pair_compute<D, NT, KB, VB>(stage, qtile, ts, kr_even, kr_odd, vu, g, L, mask_from, P0, second_valid, own0,
+                                  own1, a.scale_log2);
+    }
+  }
+
+  // ---- every wave writes its own rows
+  if (!wave_active) return;
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    ts.l_run[n] += __shfl_xor(ts.l_run[n], 16);
+    ts.l_run[n] += __shfl_xor(ts.l_run[n], 32);
+    const int r = wave * ROWS + 16 * n + c;  // row inside the row group
+    if (16 * n + c >= Rw) continue;
+    if (complete) {
+      const int q = it.q0 + r / a.G;
+      const int head = it.h * a.G + r % a.G;
+      const float inv = 1.f / ts.l_run[n];
+      __bf16* dst = (__bf16*)a.out + ((long)q * a.kv.num_q_heads + head) * D;
+      typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) {
+        bf16x4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(ts.acc[n][mt][e] * inv);
+        *(bf16x4*)(dst + 16 * mt + 4 * g) = ov;
+      }
+      if (a.lse && g == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (ts.m_run[n] + log2f(ts.l_run[n])) * LN2;
+    } else {
+      float* dst = pslot + (long)r * (D + 4);
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) store_device_scope_x4(dst + 16 * mt + 4 * g, ts.acc[n][mt]);
+      if (g == 0) store_device_scope_x2(dst + D, ts.m_run[n], ts.l_run[n]);
+    }
+  }
+}
+
+template <int D, int NT, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void attn_bf16_rows_kernel(
+    AttnArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ int merge_flag;
+  using C = Bf16Cfg<D>;
+  constexpr int THREADS = NW * 64;
+  int* sched_base = (int*)(smem + 2 * C::STAGE_BYTES + (size_t)NW * 16 * NT * D * 2 + 2 * NW * 16 * NT * 4 +
+                          (BLK_WIN + 4) * 4);
+  int* scratch = (int*)smem;  // the stage area is idle until the first segment
+  const Sched sc = sched_at(sched_base, a.B);
+  int min_np;
+  const int total = build_units<THREADS>(a, sc, scratch, &min_np);
+  const Shares sh = make_shares(total, a.nwg, min_np);
+  if ((int)blockIdx.x >= sh.n) return;
+  const int end = share_begin(a, sc, sh, blockIdx.x + 1);
+  int u = share_begin(a, sc, sh, blockIdx.x);
+  while (u < end) {
+    int page0;
+    const Item it = locate(a, sc, u, &page0);
+    const int page1 = min(it.np, page0 + (end - u));
+    const bool complete = (page0 == 0) && (page1 == it.np);
+    float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
+    segment_rows<D, NT, NW>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
     if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, &merge_flag);
     u += page1 - page0;
   }
@@ -1144,8 +1408,17 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
       return ASPD_ERR_INVALID_ARG;
   }
   int qpg = 0, nt = 0;
-  const int rows_cap = rows_per_group(kv, step->max_new_per_seq, &qpg, &nt);
+  int rows_cap = rows_per_group(kv, step->max_new_per_seq, &qpg, &nt);
   if (rows_cap == 0) return ASPD_ERR_UNSUPPORTED;
+  // Branch chunks bring many rows per KV head: the waves then split the rows (one fetch of the pages per
+  // ROWS_NW * 48 rows) instead of the keys.
+  const int G_ = kv->num_q_heads / kv->num_kv_heads;
+  const bool by_rows = mode == MODE_CHUNK && kv->dtype == ASPD_BF16 && G_ <= 16 * NT_MAX &&
+                       (step->max_new_per_seq == 0 || step->max_new_per_seq * G_ > 16 * NT_MAX);
+  if (by_rows) {
+    rows_cap = ROWS_NW * 16 * NT_MAX;
+    qpg = rows_cap / G_;
+  }
   const size_t need = aspd_workspace_bytes(kv, state->B, step->NQ);
   if (need == 0) return ASPD_ERR_INVALID_ARG;
   if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
@@ -1177,6 +1450,7 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   const long groups_max = (long)state->B + step->NQ / qpg;
   const long units_max = groups_max * kv->num_kv_heads * kv->max_blocks_per_seq;
   long nwg = (kv->dtype == ASPD_BF16 ? 1L : 2L) * device_cu_count();
+  if (by_rows) nwg = std::min(nwg, (long)MAX_WG_ROWS);
   // pages are read once when no sequence can have more than one row group
   const bool stream_once = step->max_new_per_seq > 0 && step->max_new_per_seq <= qpg;
   nwg = std::min(nwg, (units_max + MIN_PAGES_PER_WG - 1) / MIN_PAGES_PER_WG);
@@ -1193,7 +1467,14 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
     hipLaunchKernelGGL(KERNEL, dim3(a.nwg), dim3(NTHREADS), SMEM, hs, a);            \
     ASPD_HIP_CHECK(hipGetLastError());                                               \
   } while (0)
-  if (kv->dtype == ASPD_BF16) {
+  if (by_rows) {
+    if (D == 128)
+      ASPD_LAUNCH((attn_bf16_rows_kernel<128, NT_MAX, ROWS_NW>), ROWS_NW * 64,
+                  (rows_smem_bytes<128, NT_MAX, ROWS_NW>(state->B)));
+    else
+      ASPD_LAUNCH((attn_bf16_rows_kernel<64, NT_MAX, ROWS_NW>), ROWS_NW * 64,
+                  (rows_smem_bytes<64, NT_MAX, ROWS_NW>(state->B)));
+  } else if (kv->dtype == ASPD_BF16) {
 #define ASPD_BF16_CASE(DD, NN)                                                                            \
   do {                                                                                                    \
     if (stream_once)                                                                                      \
@@ -1230,8 +1511,11 @@ extern "C" size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ)
   int qpg = 0, nt = 0;
   const int rows_cap = rows_per_group(kv, 0, &qpg, &nt);  // the widest row group
   if (rows_cap == 0) return 0;
-  // two partial slots per workgroup of the largest grid any device would get
-  return COUNTER_BYTES + (size_t)2 * MAX_WG * rows_cap * (kv->head_dim + 4) * sizeof(float);
+  // two partial slots per workgroup of the largest grid any device would get, for whichever kernel
+  // needs more rows in total
+  size_t slot_rows = (size_t)2 * MAX_WG * rows_cap;
+  if (kv->dtype == ASPD_BF16) slot_rows = std::max(slot_rows, (size_t)2 * MAX_WG_ROWS * ROWS_NW * 16 * NT_MAX);
+  return COUNTER_BYTES + slot_rows * (kv->head_dim + 4) * sizeof(float);
 }
 
 namespace {
