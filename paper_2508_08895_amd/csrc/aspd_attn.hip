@@ -42,6 +42,11 @@ constexpr int NT_MAX = 3;             // 16-row MFMA tiles per row group (bf16 p
 constexpr int BF16_ROWS = 16 * NT_MAX;
 constexpr int F32_ROWS = 4;           // rows per row group (fp32 vector path)
 constexpr int MIN_PAGES_PER_WG = 16;  // do not split finer than this
+#ifndef ASPD_TUNE_PAD
+#define ASPD_TUNE_PAD 24
+#endif
+constexpr int PAD_STREAM = ASPD_TUNE_PAD;  // virtual units per item start, bandwidth-bound kernel at D = 128
+constexpr int PAD_COMPUTE = 8;             // the same for the compute-bound kernels
 constexpr int ROWS_NW = 8;            // waves per workgroup of the row-splitting (chunk) kernel
 constexpr int MAX_WG_ROWS = 256;      // its largest grid (its partial slots are ROWS_NW * 48 rows each)
 constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
@@ -78,6 +83,7 @@ struct AttnArgs {
   int            G;             // query heads per KV head
   int            qpg;           // queries per row group
   int            rows_cap;      // rows per row group the partial slots are sized for
+  int            pad;           // virtual units in front of every item (ragged batches): a segment's fixed cost in pages
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -91,12 +97,13 @@ struct Item {
 };
 
 // Per-sequence scalars, fetched once per workgroup into LDS so that walking from segment to segment
-// needs no further dependent global loads.
+// needs no further dependent global loads, and the table of share boundaries.
 struct Sched {
-  int* cu_units;  // [B+1] exclusive scan of pages * row groups * KV heads
+  int* cu_units;  // [B+1] exclusive scan of (pages + pad) * row groups * KV heads
   int* T;         // [B]   seq_len
   int* L;         // [B]   stage_base
   int* q0;        // [B+1] cu_seq_new
+  int* wgb;       // [MAX_WG+1] first unit of every workgroup's share (ragged regime only)
 };
 __device__ __forceinline__ Sched sched_at(int* base, int B) {
   Sched sc;
@@ -104,9 +111,10 @@ __device__ __forceinline__ Sched sched_at(int* base, int B) {
   sc.T = base + (B + 1);
   sc.L = sc.T + B;
   sc.q0 = sc.L + B;
+  sc.wgb = sc.q0 + (B + 1);
   return sc;
 }
-constexpr int sched_ints(int B) { return 4 * B + 2; }
+constexpr int sched_ints(int B) { return 4 * B + 2 + MAX_WG + 1; }
 
 __device__ __forceinline__ int pages_of(const AttnArgs& a, const Sched& sc, int s) {
   int np = (sc.T[s] + ASPD_BLOCK - 1) / ASPD_BLOCK;
@@ -117,20 +125,91 @@ __device__ __forceinline__ int groups_of(const AttnArgs& a, const Sched& sc, int
   return (nq + a.qpg - 1) / a.qpg;
 }
 
-// Fills the LDS tables.  Returns the total number of page units; *min_np gets the page count of the
-// shortest item.
+// Shares of the unit space, one per workgroup used.  A unit is a page of an item or, in the ragged
+// regime, one of `pad` virtual units in front of every item: they price the fixed cost a workgroup
+// pays for starting a segment (start-up, reduction, a partial to be merged), so that equal shares of
+// units are about equal shares of time.  Two regimes, chosen per launch:
+//
+// ALIGNED (every item at least two shares long: few long sequences; pad = 0).  Item i gets the
+// workgroups [rnd(U_i), rnd(U_i + np_i)) with U_i its first unit and rnd(x) = x * n / total rounded
+// to nearest, and is cut evenly among them.  Every workgroup then has exactly one segment, and
+// shares differ by a page or two.
+//
+// RAGGED.  Workgroup w nominally takes [w * total / n, (w + 1) * total / n); a boundary inside an
+// item's padding, or within `tol` units after it or before the item's end, is moved onto the item
+// boundary: a sliver of a neighbouring item would cost a whole extra segment for a few pages.  The
+// boundaries are tabulated in LDS (wgb), which also gives the owner of a unit by binary search.
+struct Shares {
+  int total, n, tol, pad;
+  bool aligned;
+  double per_page;  // n / total: workgroups per unit
+  double share;     // total / n: units per workgroup
+  // Any monotone map with rnd(0) = 0 and rnd(total) = n serves, as long as every caller uses this one;
+  // double arithmetic avoids 64-bit integer division.
+  __device__ __forceinline__ int rnd(int x) const { return min(n, (int)((double)x * per_page + 0.5)); }
+  __device__ __forceinline__ int nominal_begin(int w) const { return min(total, (int)((double)w * share)); }
+};
+
+// The item that holds unit `u`, and the unit's index within it (padding first, then the pages).
+__device__ Item locate(const AttnArgs& a, const Sched& sc, int pad, int u, int* vpage) {
+  int lo = 0, hi = a.B - 1;
+  while (lo < hi) {
+    int mid = (lo + hi + 1) >> 1;
+    if (sc.cu_units[mid] <= u) lo = mid; else hi = mid - 1;
+  }
+  Item it;
+  it.s = lo;
+  it.np = pages_of(a, sc, lo);
+  const int vl = it.np + pad;
+  const int rel = u - sc.cu_units[lo];
+  const int idx = rel / vl;
+  *vpage = rel - idx * vl;
+  const int ngroups = groups_of(a, sc, lo);
+  it.h = idx / ngroups;       // row groups of one KV head are neighbours: they read the same pages
+  it.rg = idx - it.h * ngroups;
+  it.first_unit = sc.cu_units[lo] + idx * vl;
+  const int qs = sc.q0[lo];
+  const int nq = sc.q0[lo + 1] - qs;
+  it.q0 = qs + it.rg * a.qpg;
+  it.nq = min(a.qpg, nq - it.rg * a.qpg);
+  return it;
+}
+
+__device__ int share_begin(const AttnArgs& a, const Sched& sc, const Shares& sh, int w) {
+  if (w <= 0) return 0;
+  if (w >= sh.n) return sh.total;
+  const int nominal = sh.nominal_begin(w);
+  int vpage;
+  Item it = locate(a, sc, sh.pad, nominal, &vpage);
+  if (sh.aligned) {
+    // rounding moves an item's first workgroup by half a share at most: the item that holds the
+    // nominal boundary, or its neighbour
+    if (w < sh.rnd(it.first_unit)) it = locate(a, sc, 0, it.first_unit - 1, &vpage);
+    else if (w >= sh.rnd(it.first_unit + it.np)) it = locate(a, sc, 0, it.first_unit + it.np, &vpage);
+    const int w0 = sh.rnd(it.first_unit);
+    const int k = sh.rnd(it.first_unit + it.np) - w0;
+    return it.first_unit + (int)((unsigned)(w - w0) * (unsigned)it.np / (unsigned)k);
+  }
+  const int vl = it.np + sh.pad;
+  if (vpage <= sh.pad + sh.tol) return it.first_unit;
+  if (vl - vpage <= sh.tol) return it.first_unit + vl;
+  return nominal;
+}
+
+// Fills the LDS tables and returns the shares.  All threads of the workgroup call it.
 template <int THREADS>
-__device__ int build_units(const AttnArgs& a, const Sched& sc, int* scratch /*THREADS + THREADS / 64 ints*/,
-                           int* min_np) {
+__device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratch /* 3 * THREADS / 64 ints */) {
   constexpr int PER = (ASPD_MAX_BATCH + THREADS - 1) / THREADS;  // sequences per thread
+  constexpr int NWV = THREADS / 64;
   const int tid = threadIdx.x;
-  int mine[PER];
-  int sum = 0;
+  int mine_p[PER], mine_i[PER];
+  int sum_p = 0, sum_i = 0;
   int shortest = 0x7fffffff;
 #pragma unroll
   for (int j = 0; j < PER; ++j) {
     const int s = tid * PER + j;
-    mine[j] = 0;
+    mine_p[j] = 0;
+    mine_i[j] = 0;
     if (s < a.B) {
       const int T = a.seq_len[s];
       const int q0 = a.cu_seq_new[s];
@@ -141,136 +220,119 @@ __device__ int build_units(const AttnArgs& a, const Sched& sc, int* scratch /*TH
       if (s == a.B - 1) sc.q0[a.B] = q1;
       const int np = min((T + ASPD_BLOCK - 1) / ASPD_BLOCK, a.kv.max_blocks_per_seq);
       const int ng = (q1 - q0 + a.qpg - 1) / a.qpg;
-      mine[j] = np * ng * a.kv.num_kv_heads;
-      if (mine[j] > 0) shortest = min(shortest, np);
+      if (np * ng > 0) {
+        mine_i[j] = ng * a.kv.num_kv_heads;
+        mine_p[j] = np * mine_i[j];
+        shortest = min(shortest, np);
+      }
     }
-    sum += mine[j];
+    sum_p += mine_p[j];
+    sum_i += mine_i[j];
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) shortest = min(shortest, __shfl_xor(shortest, off));
-  if ((tid & 63) == 0) scratch[THREADS + (tid >> 6)] = shortest;
-  // scan: inside the wave by shuffles, across the waves through LDS (one barrier)
-  int incl = sum;
+  // scans: inside the wave by shuffles, across the waves through LDS (one barrier)
+  int incl_p = sum_p, incl_i = sum_i;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
-    const int v = __shfl_up(incl, off);
-    if ((tid & 63) >= off) incl += v;
+    const int vp = __shfl_up(incl_p, off);
+    const int vi = __shfl_up(incl_i, off);
+    if ((tid & 63) >= off) {
+      incl_p += vp;
+      incl_i += vi;
+    }
   }
-  if ((tid & 63) == 63) scratch[tid >> 6] = incl;
+  if ((tid & 63) == 63) {
+    scratch[tid >> 6] = incl_p;
+    scratch[NWV + (tid >> 6)] = incl_i;
+    scratch[2 * NWV + (tid >> 6)] = shortest;
+  }
   __syncthreads();
-  int run = incl - sum;  // exclusive within the wave
-  int total = 0;
+  int run_p = incl_p - sum_p, run_i = incl_i - sum_i;  // exclusive within the wave
+  int pages = 0, items = 0;
   int mn = 0x7fffffff;
 #pragma unroll
-  for (int w = 0; w < THREADS / 64; ++w) {
-    const int t = scratch[w];
-    if (w < (tid >> 6)) run += t;
-    total += t;
-    mn = min(mn, scratch[THREADS + w]);
+  for (int w = 0; w < NWV; ++w) {
+    const int tp = scratch[w], ti = scratch[NWV + w];
+    if (w < (tid >> 6)) {
+      run_p += tp;
+      run_i += ti;
+    }
+    pages += tp;
+    items += ti;
+    mn = min(mn, scratch[2 * NWV + w]);
   }
+  Shares sh;
+  const int n0 = max(1, min(a.nwg, pages / MIN_PAGES_PER_WG));
+  sh.aligned = (double)mn * n0 >= 2.0 * pages;
+  sh.pad = sh.aligned ? 0 : a.pad;
+  sh.total = pages + sh.pad * items;
+  sh.n = max(1, min(a.nwg, sh.total / MIN_PAGES_PER_WG));
+  sh.tol = min((sh.total / sh.n) >> 3, a.pad);
+  sh.per_page = (double)sh.n / (double)max(sh.total, 1);
+  sh.share = (double)sh.total / (double)sh.n;
 #pragma unroll
   for (int j = 0; j < PER; ++j) {
     const int s = tid * PER + j;
-    if (s < a.B) sc.cu_units[s] = run;
-    run += mine[j];
+    if (s < a.B) sc.cu_units[s] = run_p + sh.pad * run_i;
+    run_p += mine_p[j];
+    run_i += mine_i[j];
   }
-  if (tid == 0) sc.cu_units[a.B] = total;
-  *min_np = mn;
+  if (tid == 0) sc.cu_units[a.B] = sh.total;
   __syncthreads();
-  return total;
-}
-
-// The item that holds flattened page `u`, and the page's index within it.
-__device__ Item locate(const AttnArgs& a, const Sched& sc, int u, int* page) {
-  int lo = 0, hi = a.B - 1;
-  while (lo < hi) {
-    int mid = (lo + hi + 1) >> 1;
-    if (sc.cu_units[mid] <= u) lo = mid; else hi = mid - 1;
+  if (!sh.aligned) {
+    for (int w = tid; w <= sh.n; w += THREADS) sc.wgb[w] = share_begin(a, sc, sh, w);
+    __syncthreads();
   }
-  Item it;
-  it.s = lo;
-  it.np = pages_of(a, sc, lo);
-  const int rel = u - sc.cu_units[lo];
-  const int idx = rel / it.np;
-  *page = rel - idx * it.np;
-  const int ngroups = groups_of(a, sc, lo);
-  it.h = idx / ngroups;       // row groups of one KV head are neighbours: they read the same pages
-  it.rg = idx - it.h * ngroups;
-  it.first_unit = sc.cu_units[lo] + idx * it.np;
-  const int qs = sc.q0[lo];
-  const int nq = sc.q0[lo + 1] - qs;
-  it.q0 = qs + it.rg * a.qpg;
-  it.nq = min(a.qpg, nq - it.rg * a.qpg);
-  return it;
-}
-
-// Shares of the page space, one per workgroup used.  Two regimes, chosen per launch:
-//
-// ALIGNED (every item at least two shares long: few long sequences).  Item i gets the workgroups
-// [rnd(U_i), rnd(U_i + np_i)) with U_i its first flattened page and rnd(x) = x * n / total rounded to
-// nearest, and is cut evenly among them.  Every workgroup then has exactly one segment, and shares
-// differ by a page or two.
-//
-// FLATTENED (ragged batches).  Workgroup w nominally takes [w * total / n, (w + 1) * total / n); a
-// boundary within an eighth of a share of an item boundary is moved onto it, because a sliver of a
-// neighbouring item would cost a whole extra segment (start-up, reduction, a partial to be merged)
-// for a few pages.
-struct Shares {
-  int total, n, tol;
-  bool aligned;
-  double per_page;  // n / total: workgroups per page
-  double share;     // total / n: pages per workgroup
-  // Any monotone map with rnd(0) = 0 and rnd(total) = n serves, as long as every caller uses this one;
-  // double arithmetic avoids 64-bit integer division.
-  __device__ __forceinline__ int rnd(int x) const { return min(n, (int)((double)x * per_page + 0.5)); }
-  __device__ __forceinline__ int nominal_begin(int w) const { return min(total, (int)((double)w * share)); }
-  __device__ __forceinline__ int nominal_owner(int u) const { return min(n - 1, (int)((double)u * per_page)); }
-};
-__device__ __forceinline__ Shares make_shares(int total, int nwg, int min_np) {
-  Shares sh;
-  sh.total = total;
-  sh.n = max(1, min(nwg, total / MIN_PAGES_PER_WG));
-  sh.tol = (total / sh.n) >> 3;
-  sh.aligned = (double)min_np * sh.n >= 2.0 * total;
-  sh.per_page = (double)sh.n / (double)max(total, 1);
-  sh.share = (double)total / (double)sh.n;
   return sh;
 }
-__device__ int share_begin(const AttnArgs& a, const Sched& sc, const Shares& sh, int w) {
-  if (w <= 0) return 0;
-  if (w >= sh.n) return sh.total;
-  const int nominal = sh.nominal_begin(w);
-  int page;
-  Item it = locate(a, sc, nominal, &page);
-  if (sh.aligned) {
-    // rounding moves an item's first workgroup by half a share at most: the item that holds the
-    // nominal boundary, or its neighbour
-    if (w < sh.rnd(it.first_unit)) it = locate(a, sc, it.first_unit - 1, &page);
-    else if (w >= sh.rnd(it.first_unit + it.np)) it = locate(a, sc, it.first_unit + it.np, &page);
-    const int w0 = sh.rnd(it.first_unit);
-    const int k = sh.rnd(it.first_unit + it.np) - w0;
-    return it.first_unit + (int)((unsigned)(w - w0) * (unsigned)it.np / (unsigned)k);
-  }
-  if (page <= sh.tol) return it.first_unit;
-  if (it.np - page <= sh.tol) return it.first_unit + it.np;
-  return nominal;
-}
-// The workgroup whose share holds flattened page u.
+
+// The workgroup whose share holds unit u.
 __device__ int share_owner(const AttnArgs& a, const Sched& sc, const Shares& sh, int u) {
   if (sh.aligned) {
     int page;
-    const Item it = locate(a, sc, u, &page);
+    const Item it = locate(a, sc, 0, u, &page);
     const int w0 = sh.rnd(it.first_unit);
     const int k = sh.rnd(it.first_unit + it.np) - w0;
     return w0 + (int)((((unsigned)page + 1u) * (unsigned)k - 1u) / (unsigned)it.np);
   }
-  // nominal owner, corrected against the actual boundaries (rounding and moved boundaries shift it
-  // by a workgroup or two at most)
-  int w = sh.nominal_owner(u);
-  while (w > 0 && u < share_begin(a, sc, sh, w)) --w;
-  while (w < sh.n - 1 && u >= share_begin(a, sc, sh, w + 1)) ++w;
-  return w;
+  int lo = 0, hi = sh.n - 1;  // last w with wgb[w] <= u
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (sc.wgb[mid] <= u) lo = mid; else hi = mid - 1;
+  }
+  return lo;
 }
+
+// One workgroup's walk over its share [*u, end): the next run of real pages, or false at the end.
+__device__ __forceinline__ void share_range(const AttnArgs& a, const Sched& sc, const Shares& sh, int* u, int* end) {
+  if (sh.aligned) {
+    *u = share_begin(a, sc, sh, blockIdx.x);
+    *end = share_begin(a, sc, sh, blockIdx.x + 1);
+  } else {
+    *u = sc.wgb[blockIdx.x];
+    *end = sc.wgb[blockIdx.x + 1];
+  }
+}
+__device__ __forceinline__ bool next_segment(const AttnArgs& a, const Sched& sc, const Shares& sh, int* u, int end,
+                                             Item* it, int* page0, int* page1) {
+  while (*u < end) {
+    int v0;
+    *it = locate(a, sc, sh.pad, *u, &v0);
+    const int v1 = min(it->np + sh.pad, v0 + (end - *u));
+    *u += v1 - v0;
+    *page0 = max(0, v0 - sh.pad);
+    *page1 = max(0, v1 - sh.pad);
+    if (*page1 > *page0) return true;
+  }
+  return false;
+}
+
+// Defined after the kernels (it needs the merge): called by every thread of a workgroup that has
+// written a partial of `it`, pages [page0, page1).
+template <int D, bool BF16, int THREADS>
+__device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh, int page0,
+                                 int page1, int* flag /* LDS */);
 
 __device__ __forceinline__ float* partial_slot(const AttnArgs& a, int wg, int starts_item, int D) {
   return a.partial + ((long)(2 * wg + starts_item)) * a.rows_cap * (D + 4);
@@ -801,21 +863,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
                           (BLK_WIN + 4) * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
   const Sched sc = sched_at(sched_base, a.B);
-  int min_np;
-  const int total = build_units<THREADS>(a, sc, scratch, &min_np);
-  const Shares sh = make_shares(total, a.nwg, min_np);
+  const Shares sh = build_schedule<THREADS>(a, sc, scratch);
   if ((int)blockIdx.x >= sh.n) return;
-  const int end = share_begin(a, sc, sh, blockIdx.x + 1);
-  int u = share_begin(a, sc, sh, blockIdx.x);
-  while (u < end) {
-    int page0;
-    const Item it = locate(a, sc, u, &page0);
-    const int page1 = min(it.np, page0 + (end - u));
+  int u, end, page0, page1;
+  share_range(a, sc, sh, &u, &end);
+  Item it;
+  while (next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
-    if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, &merge_flag);
-    u += page1 - page0;
+    if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, page0, page1, &merge_flag);
   }
 }
 
@@ -1042,21 +1099,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
                           (BLK_WIN + 4) * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
   const Sched sc = sched_at(sched_base, a.B);
-  int min_np;
-  const int total = build_units<THREADS>(a, sc, scratch, &min_np);
-  const Shares sh = make_shares(total, a.nwg, min_np);
+  const Shares sh = build_schedule<THREADS>(a, sc, scratch);
   if ((int)blockIdx.x >= sh.n) return;
-  const int end = share_begin(a, sc, sh, blockIdx.x + 1);
-  int u = share_begin(a, sc, sh, blockIdx.x);
-  while (u < end) {
-    int page0;
-    const Item it = locate(a, sc, u, &page0);
-    const int page1 = min(it.np, page0 + (end - u));
+  int u, end, page0, page1;
+  share_range(a, sc, sh, &u, &end);
+  Item it;
+  while (next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_rows<D, NT, NW>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
-    if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, &merge_flag);
-    u += page1 - page0;
+    if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, page0, page1, &merge_flag);
   }
 }
 
@@ -1204,21 +1256,16 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
                           (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4);
   int* scratch = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4);  // idle until the first segment ends
   const Sched sc = sched_at(sched_base, a.B);
-  int min_np;
-  const int total = build_units<THREADS>(a, sc, scratch, &min_np);
-  const Shares sh = make_shares(total, a.nwg, min_np);
+  const Shares sh = build_schedule<THREADS>(a, sc, scratch);
   if ((int)blockIdx.x >= sh.n) return;
-  const int end = share_begin(a, sc, sh, blockIdx.x + 1);
-  int u = share_begin(a, sc, sh, blockIdx.x);
-  while (u < end) {
-    int page0;
-    const Item it = locate(a, sc, u, &page0);
-    const int page1 = min(it.np, page0 + (end - u));
+  int u, end, page0, page1;
+  share_range(a, sc, sh, &u, &end);
+  Item it;
+  while (next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_f32<D>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
-    if (!complete) announce_partial<D, false, THREADS>(a, sc, it, sh, &merge_flag);
-    u += page1 - page0;
+    if (!complete) announce_partial<D, false, THREADS>(a, sc, it, sh, page0, page1, &merge_flag);
   }
 }
 
@@ -1312,13 +1359,14 @@ __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_l
 
 // Called by every thread of the workgroup after it has written a partial of `it`.
 template <int D, bool BF16, int THREADS>
-__device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh,
-                                 int* flag /* LDS */) {
+__device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh, int page0,
+                                 int page1, int* flag /* LDS */) {
   // the write-through stores of the partial have completed before the arrival is counted
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  const int owner = share_owner(a, sc, sh, it.first_unit);
-  const int w_last = share_owner(a, sc, sh, it.first_unit + it.np - 1);
+  // the workgroups that hold the item's first and last page
+  const int owner = page0 == 0 ? (int)blockIdx.x : share_owner(a, sc, sh, it.first_unit + sh.pad);
+  const int w_last = page1 == it.np ? (int)blockIdx.x : share_owner(a, sc, sh, it.first_unit + sh.pad + it.np - 1);
   if (threadIdx.x == 0) {
     const int old = atomicAdd(a.counters + owner, 1);
     const int last = (old == w_last - owner) ? 1 : 0;
@@ -1444,6 +1492,11 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   a.G = kv->num_q_heads / kv->num_kv_heads;
   a.qpg = qpg;
   a.rows_cap = rows_cap;
+  // A segment's fixed cost (start-up, reduction across waves, partial, merge) in units of the time one
+  // more page takes its workgroup: measured at about 10 us against 0.4 us per 8 KB page when streaming,
+  // and against 0.9 us per page in the compute-bound kernels.
+  if (by_rows || kv->dtype != ASPD_BF16) a.pad = PAD_COMPUTE;
+  else a.pad = PAD_STREAM * 128 / kv->head_dim;
 
   // Grid: as many workgroups as stay resident at once (one of 8 waves per compute unit for bf16, two of
   // 4 waves for fp32), never more than the pages can feed.
