@@ -28,16 +28,23 @@ namespace {
 
 constexpr int NW = 4;                 // waves per workgroup, fp32 kernel (two workgroups per compute unit)
 constexpr int THREADS = NW * 64;
-// bf16 kernel, one workgroup per compute unit.  Row groups of one 16-row tile: 8 waves (two per SIMD),
-// one page pair in flight per wave.  Wider row groups: 4 waves (one per SIMD, so 512 registers each),
-// three pairs in flight per wave: their longer compute per pair would otherwise leave the memory
-// pipeline idle, and their accumulators do not fit next to the loads in flight in 256 registers.
+// bf16 streaming kernel: one workgroup of 4 waves per compute unit (one wave per SIMD, so up to 512
+// registers each) and one pair of pages in flight per wave, 64 KB per compute unit.  Measured: deeper
+// prefetch (rings of 2 or 3 pairs per wave) and 8 waves both lower the read rate of the whole device
+// and make it uneven between the XCDs; the ring depth stays a template parameter.
 #ifndef ASPD_TUNE_NW1
-#define ASPD_TUNE_NW1 8
+#define ASPD_TUNE_NW1 4
 #define ASPD_TUNE_PF1 1
 #endif
-#define BF16_NW(NT_) ((NT_) == 1 ? ASPD_TUNE_NW1 : 4)
-#define BF16_PF(NT_) ((NT_) == 1 ? ASPD_TUNE_PF1 : ((NT_) == 2 ? 3 : 2))
+#ifndef ASPD_TUNE_NW2
+#define ASPD_TUNE_NW2 4
+#endif
+#define BF16_NW(NT_) ((NT_) == 1 ? ASPD_TUNE_NW1 : ((NT_) == 2 ? ASPD_TUNE_NW2 : 4))
+#ifndef ASPD_TUNE_PF2
+#define ASPD_TUNE_PF2 1
+#define ASPD_TUNE_PF3 1
+#endif
+#define BF16_PF(NT_) ((NT_) == 1 ? ASPD_TUNE_PF1 : ((NT_) == 2 ? ASPD_TUNE_PF2 : ASPD_TUNE_PF3))
 constexpr int NT_MAX = 3;             // 16-row MFMA tiles per row group (bf16 path)
 constexpr int BF16_ROWS = 16 * NT_MAX;
 constexpr int F32_ROWS = 4;           // rows per row group (fp32 vector path)
@@ -151,11 +158,21 @@ struct Shares {
 };
 
 // The item that holds unit `u`, and the unit's index within it (padding first, then the pages).
+// WAVE: every lane of the wave calls with the same u; batches of up to 64 sequences are then searched
+// in one step (lane s looks at sequence s) instead of a chain of dependent LDS reads.
+template <bool WAVE>
 __device__ Item locate(const AttnArgs& a, const Sched& sc, int pad, int u, int* vpage) {
-  int lo = 0, hi = a.B - 1;
-  while (lo < hi) {
-    int mid = (lo + hi + 1) >> 1;
-    if (sc.cu_units[mid] <= u) lo = mid; else hi = mid - 1;
+  int lo = 0;  // the last sequence that starts at or before u
+  if (WAVE && a.B <= 64) {
+    const int lane = threadIdx.x & 63;
+    const int start = lane < a.B ? sc.cu_units[lane] : 0x7fffffff;
+    lo = 63 - __clzll(__ballot(start <= u));  // cu_units[0] = 0 <= u: the mask is not empty
+  } else {
+    int hi = a.B - 1;
+    while (lo < hi) {
+      int mid = (lo + hi + 1) >> 1;
+      if (sc.cu_units[mid] <= u) lo = mid; else hi = mid - 1;
+    }
   }
   Item it;
   it.s = lo;
@@ -175,17 +192,18 @@ __device__ Item locate(const AttnArgs& a, const Sched& sc, int pad, int u, int* 
   return it;
 }
 
+template <bool WAVE>
 __device__ int share_begin(const AttnArgs& a, const Sched& sc, const Shares& sh, int w) {
   if (w <= 0) return 0;
   if (w >= sh.n) return sh.total;
   const int nominal = sh.nominal_begin(w);
   int vpage;
-  Item it = locate(a, sc, sh.pad, nominal, &vpage);
+  Item it = locate<WAVE>(a, sc, sh.pad, nominal, &vpage);
   if (sh.aligned) {
     // rounding moves an item's first workgroup by half a share at most: the item that holds the
     // nominal boundary, or its neighbour
-    if (w < sh.rnd(it.first_unit)) it = locate(a, sc, 0, it.first_unit - 1, &vpage);
-    else if (w >= sh.rnd(it.first_unit + it.np)) it = locate(a, sc, 0, it.first_unit + it.np, &vpage);
+    if (w < sh.rnd(it.first_unit)) it = locate<WAVE>(a, sc, 0, it.first_unit - 1, &vpage);
+    else if (w >= sh.rnd(it.first_unit + it.np)) it = locate<WAVE>(a, sc, 0, it.first_unit + it.np, &vpage);
     const int w0 = sh.rnd(it.first_unit);
     const int k = sh.rnd(it.first_unit + it.np) - w0;
     return it.first_unit + (int)((unsigned)(w - w0) * (unsigned)it.np / (unsigned)k);
@@ -281,7 +299,7 @@ __device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratc
   if (tid == 0) sc.cu_units[a.B] = sh.total;
   __syncthreads();
   if (!sh.aligned) {
-    for (int w = tid; w <= sh.n; w += THREADS) sc.wgb[w] = share_begin(a, sc, sh, w);
+    for (int w = tid; w <= sh.n; w += THREADS) sc.wgb[w] = share_begin<false>(a, sc, sh, w);  // w differs per lane
     __syncthreads();
   }
   return sh;
@@ -291,7 +309,7 @@ __device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratc
 __device__ int share_owner(const AttnArgs& a, const Sched& sc, const Shares& sh, int u) {
   if (sh.aligned) {
     int page;
-    const Item it = locate(a, sc, 0, u, &page);
+    const Item it = locate<true>(a, sc, 0, u, &page);
     const int w0 = sh.rnd(it.first_unit);
     const int k = sh.rnd(it.first_unit + it.np) - w0;
     return w0 + (int)((((unsigned)page + 1u) * (unsigned)k - 1u) / (unsigned)it.np);
@@ -307,8 +325,8 @@ __device__ int share_owner(const AttnArgs& a, const Sched& sc, const Shares& sh,
 // One workgroup's walk over its share [*u, end): the next run of real pages, or false at the end.
 __device__ __forceinline__ void share_range(const AttnArgs& a, const Sched& sc, const Shares& sh, int* u, int* end) {
   if (sh.aligned) {
-    *u = share_begin(a, sc, sh, blockIdx.x);
-    *end = share_begin(a, sc, sh, blockIdx.x + 1);
+    *u = share_begin<true>(a, sc, sh, blockIdx.x);
+    *end = share_begin<true>(a, sc, sh, blockIdx.x + 1);
   } else {
     *u = sc.wgb[blockIdx.x];
     *end = sc.wgb[blockIdx.x + 1];
@@ -318,7 +336,7 @@ __device__ __forceinline__ bool next_segment(const AttnArgs& a, const Sched& sc,
                                              Item* it, int* page0, int* page1) {
   while (*u < end) {
     int v0;
-    *it = locate(a, sc, sh.pad, *u, &v0);
+    *it = locate<true>(a, sc, sh.pad, *u, &v0);
     const int v1 = min(it->np + sh.pad, v0 + (end - *u));
     *u += v1 - v0;
     *page0 = max(0, v0 - sh.pad);
@@ -330,7 +348,7 @@ __device__ __forceinline__ bool next_segment(const AttnArgs& a, const Sched& sc,
 
 // Defined after the kernels (it needs the merge): called by every thread of a workgroup that has
 // written a partial of `it`, pages [page0, page1).
-template <int D, bool BF16, int THREADS>
+template <int D, bool BF16, int THREADS, int ELEMS>
 __device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh, int page0,
                                  int page1, int* flag /* LDS */);
 
@@ -392,6 +410,29 @@ struct PairRegs {
   u32x4 r[4][Bf16Cfg<D>::LPP];
   uint32_t own[2];  // owner tags of this lane's four keys in either page (pairs that need masking only)
 };
+
+// Owner tags through the scalar (constant) path, for the kernel whose waves fetch pages cooperatively:
+// the address is the same for the whole wave, and scalar loads are counted apart from the vector
+// loads, so waiting for the tags of a pair never means waiting for the pages of the next pair.
+typedef u32x4 __attribute__((aligned(4))) u32x4_a4;
+__device__ __forceinline__ u32x4 load_tags_uniform(const uint8_t* p /* same in all lanes, 4-byte aligned */) {
+  return *(const __attribute__((address_space(4))) u32x4_a4*)(uintptr_t)p;
+}
+// The lane's four keys (4g .. 4g + 3) out of a page's sixteen tags.
+__device__ __forceinline__ uint32_t lane_tags(const u32x4& t, int g) {
+  uint32_t r = t[0];
+  r = (g == 1) ? t[1] : r;
+  r = (g == 2) ? t[2] : r;
+  r = (g == 3) ? t[3] : r;
+  return r;
+}
+// A pointer every lane holds, as a value the compiler knows to be the same in all of them.
+__device__ __forceinline__ const uint8_t* uniform_ptr(const uint8_t* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const uint8_t*)(((uint64_t)hi << 32) | lo);
+}
 
 // STREAM: the pages are read once by this launch, so they are fetched with non-temporal loads, which
 // on this device sustain a visibly higher read rate than ordinary loads; launches that revisit pages
@@ -872,7 +913,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
-    if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, page0, page1, &merge_flag);
+    // the merging workgroup has 16 * NT rows of D / 4 chunks to combine: one pass of its 64 * NW threads
+    if (!complete) announce_partial<D, true, THREADS, (NT == 1 ? 2 : 3)>(a, sc, it, sh, page0, page1, &merge_flag);
   }
 }
 
@@ -918,7 +960,7 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
   int* blk_lds = rowtag + NW * ROWS;
 
   const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
-  const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
+  const uint8_t* owner_row = a.slot_owner ? uniform_ptr(a.slot_owner + (long)it.s * a.owner_stride) : nullptr;
 
   // ---- start-up: block ids of the first window, this wave's Q rows and row descriptors
   constexpr int BPT = BLK_WIN / THREADS;
@@ -1022,23 +1064,35 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
 #pragma unroll
       for (int k = 0; k < LPT; ++k) nxt[k] = src[lt + k * PER_PAGE];
     };
+    // owner tags of a pair that reaches into the branch region, fetched one pair ahead like the pages
+    auto tags_of = [&](int p, u32x4& t0, u32x4& t1) {
+      const int P = wbase + 2 * p;
+      if (owner_row && (P + 2) * ASPD_BLOCK > mask_from) {
+        t0 = load_tags_uniform(owner_row + P * ASPD_BLOCK);
+        t1 = load_tags_uniform(owner_row + min(P + 1, page1 - 1) * ASPD_BLOCK);  // stays inside the owner row
+      }
+    };
+    u32x4 tn0 = {0, 0, 0, 0}, tn1 = {0, 0, 0, 0};
     issue(0);
+    tags_of(0, tn0, tn1);
     for (int p = 0; p < npairs; ++p) {
       u32x4* stage = stage0 + (p & 1) * (C::STAGE_BYTES / 16);
 #pragma unroll
       for (int k = 0; k < LPT; ++k) stage[lpage * C::PAGE_U4 + lpos[k]] = nxt[k];
-      if (p + 1 < npairs) issue(p + 1);
+      const u32x4 tc0 = tn0, tc1 = tn1;
+      if (p + 1 < npairs) {
+        issue(p + 1);
+        tags_of(p + 1, tn0, tn1);
+      }
       __syncthreads();  // the pair is staged; everyone is done with the other buffer's previous pair
 
       const int P0 = wbase + 2 * p;
       const bool second_valid = (P0 + 1) < wend;
       if (!wave_active) continue;
-      const bool need_mask = (P0 + 2) * ASPD_BLOCK > mask_from || !second_valid;
       uint32_t own0 = 0, own1 = 0;
-      if (need_mask && owner_row) {
-        const int slot0 = P0 * ASPD_BLOCK + 4 * g;
-        own0 = *(const uint32_t*)(owner_row + slot0);
-        own1 = *(const uint32_t*)(owner_row + min(slot0 + ASPD_BLOCK, a.owner_stride - 4));
+      if (owner_row && (P0 + 2) * ASPD_BLOCK > mask_from) {
+        own0 = lane_tags(tc0, g);
+        own1 = lane_tags(tc1, g);
         // pairs wholly inside the branch region: skip if no key belongs to a branch of this wave's rows
         if (P0 * ASPD_BLOCK >= L && tag_lo > 0) {
           bool mine = false;
@@ -1108,7 +1162,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_rows<D, NT, NW>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
-    if (!complete) announce_partial<D, true, THREADS>(a, sc, it, sh, page0, page1, &merge_flag);
+    if (!complete) announce_partial<D, true, THREADS, 2>(a, sc, it, sh, page0, page1, &merge_flag);
   }
 }
 
@@ -1265,7 +1319,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_f32<D>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
-    if (!complete) announce_partial<D, false, THREADS>(a, sc, it, sh, page0, page1, &merge_flag);
+    if (!complete) announce_partial<D, false, THREADS, 2>(a, sc, it, sh, page0, page1, &merge_flag);
   }
 }
 
@@ -1276,11 +1330,11 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
 // another.  The partials are the "starts item" slot of the first workgroup and the "continues
 // item" slots of the following ones.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool BF16, int THREADS>
+template <int D, bool BF16, int THREADS, int ELEMS>
 __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_last) {
   constexpr int CPR = D / 4;  // float4 chunks per row
   constexpr int BATCH = 8;    // partials fetched at once, per element
-  constexpr int ELEMS = 2;    // (row, chunk) elements a thread combines concurrently
+  // ELEMS: (row, chunk) elements a thread combines concurrently
   const int R = it.nq * a.G;
   const long stride = (long)a.rows_cap * (D + 4);
   const int nparts = w_last - owner + 1;
@@ -1358,7 +1412,7 @@ __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_l
 }
 
 // Called by every thread of the workgroup after it has written a partial of `it`.
-template <int D, bool BF16, int THREADS>
+template <int D, bool BF16, int THREADS, int ELEMS>
 __device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh, int page0,
                                  int page1, int* flag /* LDS */) {
   // the write-through stores of the partial have completed before the arrival is counted
@@ -1382,7 +1436,7 @@ __device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item&
   // which all waves of the workgroup share.
   if (threadIdx.x < 64) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   __syncthreads();
-  merge_item<D, BF16, THREADS>(a, it, owner, w_last);
+  merge_item<D, BF16, THREADS, ELEMS>(a, it, owner, w_last);
 }
 
 // ---------------------------------------------------------------------------------------------
