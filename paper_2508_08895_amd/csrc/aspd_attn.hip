@@ -54,8 +54,19 @@ constexpr int MIN_PAGES_PER_WG = 16;  // do not split finer than this
 #endif
 constexpr int PAD_STREAM = ASPD_TUNE_PAD;  // virtual units per item start, bandwidth-bound kernel at D = 128
 constexpr int PAD_COMPUTE = 8;             // the same for the compute-bound kernels
-constexpr int ROWS_NW = 8;            // waves per workgroup of the row-splitting (chunk) kernel
-constexpr int MAX_WG_ROWS = 256;      // its largest grid (its partial slots are ROWS_NW * 48 rows each)
+#ifndef ASPD_TUNE_ROWS_NW
+#define ASPD_TUNE_ROWS_NW 8
+#endif
+constexpr int ROWS_NW = ASPD_TUNE_ROWS_NW;            // waves per workgroup of the row-splitting (chunk) kernel
+#ifndef ASPD_TUNE_ROWS_NT
+#define ASPD_TUNE_ROWS_NT 2
+#endif
+constexpr int ROWS_NT = ASPD_TUNE_ROWS_NT;            // 16-row tiles per wave there (Q operands and accumulators in 256 registers)
+#ifndef ASPD_TUNE_RD
+#define ASPD_TUNE_RD 1
+#endif
+constexpr int ROWS_PREFETCH = ASPD_TUNE_RD;  // pairs of pages that kernel keeps on their way per workgroup
+constexpr int MAX_WG_ROWS = 256;      // its largest grid (its partial slots are ROWS_NW * 16 * ROWS_NT rows each)
 constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
 constexpr int MAX_WG = 1024;          // upper bound of the grid (workspace is sized for it)
 constexpr float LOG2E = 1.4426950408889634f;
@@ -369,8 +380,11 @@ __device__ __forceinline__ float load_device_scope(const float* p) {
 }
 // The same write-through store, 16 or 8 bytes wide (4-byte write-through stores cost a partial-line
 // write each).  Callers order it like the 4-byte form: a later s_waitcnt vmcnt(0) covers it.
+// A store of more than 8 bytes reads its data registers a little after it issues, and the compiler, which
+// does not look inside inline assembly, may let the very next instruction overwrite them: the s_nop keeps
+// the wait states the compiler would have inserted for a store of its own.
 __device__ __forceinline__ void store_device_scope_x4(float* p, f32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void store_device_scope_x2(float* p, float a, float b) {
   typedef __attribute__((ext_vector_type(2))) float f32x2;
@@ -482,11 +496,12 @@ struct RowState {
 // `stage` holds K page 0, K page 1, V page 0, V page 1 (swizzled), `qtile` the rows' Q (swizzled).
 // kr_even / kr_odd / vu are the lane's LDS bases (see the caller).  KB k-steps of K and VB d-tiles of
 // V are fetched from LDS at a time: large batches hide the LDS latency, small ones save registers.
-template <int D, int NT, int KB, int VB>
+// QREG: the rows' Q operands come from registers (qr[n * KSTEPS + t]) instead of `qtile`.
+template <int D, int NT, int KB, int VB, bool QREG = false>
 __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qtile, RowState<D, NT>& ts,
                                              int kr_even, int kr_odd, const int (&vu)[4], int g, int L,
                                              int mask_from, int P0, bool second_valid, uint32_t own0,
-                                             uint32_t own1, float scale_log2) {
+                                             uint32_t own1, float scale_log2, const bf16x8* qr = nullptr) {
   using C = Bf16Cfg<D>;
     // ---- S^T = K Q^T for both pages.  LDS operands are fetched KB k-steps (VB d-tiles below) at a
     // time: large batches hide the LDS latency, small ones leave registers to wide row groups.
@@ -510,7 +525,7 @@ __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qt
 #pragma unroll
         for (int tt = 0; tt < KB; ++tt) {
           const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
-          const bf16x8 qb = *(const bf16x8*)&qtile[16 * n * C::CH + kr];
+          const bf16x8 qb = QREG ? qr[n * C::KSTEPS + t0 + tt] : *(const bf16x8*)&qtile[16 * n * C::CH + kr];
           st[0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[tt], qb, st[0][n], 0, 0, 0);
           st[1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[tt], qb, st[1][n], 0, 0, 0);
         }
@@ -921,18 +936,19 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
 // ---------------------------------------------------------------------------------------------
 // bf16, many rows per KV head (branch chunks): the waves of a workgroup split the ROWS instead of
 // the keys.  Every pair of pages is loaded once per workgroup, cooperatively, into a double-buffered
-// LDS stage that all waves read; each wave keeps its own 16*NT rows (Q tile, accumulators, softmax
-// state) for the whole segment, so there is no reduction across waves.  One barrier per pair.
-// With NW waves a row group holds NW * 16 * NT rows, and the pages of a KV head are fetched once per
-// that many rows.  The product per pair is compute-bound here (rows x 32 keys x D on the MFMA
-// units), which is why the waves share the loads rather than the keys.
+// LDS stage that all waves read; each wave keeps its own 16*NT rows (Q operands, accumulators,
+// softmax state, all in registers) for the whole segment, so there is no reduction across waves.
+// One barrier per pair.  With NW waves a row group holds NW * 16 * NT rows, and the pages of a KV head
+// are fetched once per that many rows.  The product per pair is compute-bound here (rows x 32 keys x
+// D on the MFMA units, the softmax on the vector ALU, the operands out of LDS), which is why the
+// waves share the loads rather than the keys.  Measured: 8 waves of 32 rows beat 8 of 48 (whose Q
+// operands no longer fit in registers) and 4 of 64 (one wave per SIMD overlaps nothing).
 // A wave skips the arithmetic for pairs that none of its rows can see (the chunks and earlier
 // tokens of other branches).
 // ---------------------------------------------------------------------------------------------
 template <int D, int NT, int NW>
 size_t rows_smem_bytes(int B) {
-  return 2 * Bf16Cfg<D>::STAGE_BYTES + (size_t)NW * 16 * NT * D * 2 + 2 * NW * 16 * NT * 4 + (BLK_WIN + 4) * 4 +
-         (size_t)sched_ints(B) * 4;
+  return 2 * Bf16Cfg<D>::STAGE_BYTES + (BLK_WIN + 4) * 4 + (size_t)sched_ints(B) * 4;
 }
 
 template <int D, int NT, int NW>
@@ -953,61 +969,33 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
   const int Rw = min(ROWS, R - wave * ROWS);       // rows this wave owns (<= 0: none)
   const bool wave_active = Rw > 0;
 
-  u32x4* stage0 = (u32x4*)smem;                                          // [2][K0 K1 V0 V1]
-  u32x4* qtile = (u32x4*)(smem + 2 * C::STAGE_BYTES) + wave * ROWS * C::CH;  // this wave's [ROWS][CH]
-  int* rowslot = (int*)(smem + 2 * C::STAGE_BYTES + (size_t)NW * ROWS * D * 2);
-  int* rowtag = rowslot + NW * ROWS;
-  int* blk_lds = rowtag + NW * ROWS;
+  u32x4* stage0 = (u32x4*)smem;                 // [2][K0 K1 V0 V1]
+  int* blk_lds = (int*)(smem + 2 * C::STAGE_BYTES);
 
   const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
   const uint8_t* owner_row = a.slot_owner ? uniform_ptr(a.slot_owner + (long)it.s * a.owner_stride) : nullptr;
 
-  // ---- start-up: block ids of the first window, this wave's Q rows and row descriptors
+  // ---- start-up: block ids of the first window; this wave's Q operands and row descriptors go
+  // straight to registers (lane (c, g) holds, of row c of every tile, the 16-byte pieces 4t + g)
   constexpr int BPT = BLK_WIN / THREADS;
   int blkreg[BPT];
 #pragma unroll
   for (int k = 0; k < BPT; ++k) blkreg[k] = bt[min(page0 + tid + k * THREADS, page1 - 1)];
-  constexpr int QL = ROWS * C::CH / 64;  // Q chunks per lane
-  u32x4 qreg[QL];
-#pragma unroll
-  for (int k = 0; k < QL; ++k) {
-    const int i = lane + k * 64;
-    const int r = i / C::CH, ch = i - r * C::CH;
-    const int rr = min(wave * ROWS + r, R - 1);  // padding rows (and idle waves) repeat the last row
-    const int q = it.q0 + rr / a.G;
-    const int head = it.h * a.G + rr % a.G;
-    qreg[k] = *((const u32x4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + ch);
-  }
-  int d_slot = 0, d_tag = 0;
-  if (lane < ROWS) {
-    const int rr = min(wave * ROWS + lane, R - 1);
-    const int q = it.q0 + rr / a.G;
-    d_slot = a.logical_slot[q];
-    const int qb = a.q_branch[q];
-    d_tag = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
-  }
-  __syncthreads();  // LDS of the previous segment is free
-#pragma unroll
-  for (int k = 0; k < BPT; ++k) blk_lds[tid + k * THREADS] = min(max(blkreg[k], 0), a.kv.num_blocks - 1);
-#pragma unroll
-  for (int k = 0; k < QL; ++k) {
-    const int i = lane + k * 64;
-    const int r = i / C::CH, ch = i - r * C::CH;
-    qtile[k_swz<D>(r, ch)] = qreg[k];
-  }
-  if (lane < ROWS) {
-    rowslot[wave * ROWS + lane] = d_slot;
-    rowtag[wave * ROWS + lane] = d_tag;
-  }
-  __syncthreads();
-
   RowState<D, NT> ts;
+  bf16x8 qr[NT * C::KSTEPS];
   int mask_from = L;
   int tag_lo = 0x7fffffff, tag_hi = 0;  // range of branch tags among this wave's rows
 #pragma unroll
   for (int n = 0; n < NT; ++n) {
-    ts.slot[n] = rowslot[wave * ROWS + 16 * n + c];
-    ts.tag[n] = rowtag[wave * ROWS + 16 * n + c];
+    const int rr = min(wave * ROWS + 16 * n + c, R - 1);  // padding rows (and idle waves) repeat the last row
+    const int q = it.q0 + rr / a.G;
+    const int head = it.h * a.G + rr % a.G;
+    const u32x4* qsrc = (const u32x4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + g;
+#pragma unroll
+    for (int t = 0; t < C::KSTEPS; ++t) qr[n * C::KSTEPS + t] = __builtin_bit_cast(bf16x8, qsrc[4 * t]);
+    ts.slot[n] = a.logical_slot[q];
+    const int qb = a.q_branch[q];
+    ts.tag[n] = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
     mask_from = min(mask_from, ts.slot[n]);
     tag_lo = min(tag_lo, ts.tag[n]);
     tag_hi = max(tag_hi, ts.tag[n]);
@@ -1016,8 +1004,12 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
 #pragma unroll
     for (int mt = 0; mt < C::MT; ++mt) ts.acc[n][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
+  __syncthreads();  // LDS of the previous segment is free
 #pragma unroll
-  for (int off = 1; off < 16; off <<= 1) {
+  for (int k = 0; k < BPT; ++k) blk_lds[tid + k * THREADS] = min(max(blkreg[k], 0), a.kv.num_blocks - 1);
+  __syncthreads();
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
     mask_from = min(mask_from, __shfl_xor(mask_from, off));
     tag_lo = min(tag_lo, __shfl_xor(tag_lo, off));
     tag_hi = max(tag_hi, __shfl_xor(tag_hi, off));
@@ -1045,7 +1037,8 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
     lpos[k] = (lpage < 2) ? k_swz<D>(row, ch) : v_swz<D>(row, ch);
   }
 
-  u32x4 nxt[LPT];
+  constexpr int RD = ROWS_PREFETCH;  // pairs on their way per workgroup (a ring of register sets)
+  u32x4 nxt[RD][LPT];
   for (int wbase = page0; wbase < page1; wbase += BLK_WIN) {  // windows of block ids; normally one
     const int wend = min(page1, wbase + BLK_WIN);
     const int wpages = wend - wbase;
@@ -1057,12 +1050,15 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
         blk_lds[tid + k * THREADS] = min(max(bt[min(wbase + tid + k * THREADS, page1 - 1)], 0), a.kv.num_blocks - 1);
       __syncthreads();
     }
-    auto issue = [&](int p) {  // this thread's slice of pair p
-      const int pg = min(2 * p + (lpage & 1), wpages - 1);
+    // This thread's slice of pair p.  Issued for every ring slot, also past the end of the window (the
+    // last pair again, which the caches hold): the number of loads younger than a slot is then fixed,
+    // so waiting for the oldest slot leaves the younger ones in flight.
+    auto issue = [&](u32x4 (&dst)[LPT], int p) {
+      const int pg = min(2 * min(p, npairs - 1) + (lpage & 1), wpages - 1);
       const int b = blk_lds[pg];
       const u32x4* src = (const u32x4*)(lpage < 2 ? a.kv.k : a.kv.v) + ((long)b * a.kv.num_kv_heads + it.h) * C::PAGE_U4;
 #pragma unroll
-      for (int k = 0; k < LPT; ++k) nxt[k] = src[lt + k * PER_PAGE];
+      for (int k = 0; k < LPT; ++k) dst[k] = src[lt + k * PER_PAGE];
     };
     // owner tags of a pair that reaches into the branch region, fetched one pair ahead like the pages
     auto tags_of = [&](int p, u32x4& t0, u32x4& t1) {
@@ -1073,17 +1069,20 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
       }
     };
     u32x4 tn0 = {0, 0, 0, 0}, tn1 = {0, 0, 0, 0};
-    issue(0);
+#pragma unroll
+    for (int d = 0; d < RD; ++d) issue(nxt[d], d);
     tags_of(0, tn0, tn1);
-    for (int p = 0; p < npairs; ++p) {
+    for (int pbase = 0; pbase < npairs; pbase += RD) {
+#pragma unroll
+    for (int d = 0; d < RD; ++d) {  // the ring is unrolled so that every slot has fixed registers
+      const int p = pbase + d;
+      if (p >= npairs) break;
       u32x4* stage = stage0 + (p & 1) * (C::STAGE_BYTES / 16);
 #pragma unroll
-      for (int k = 0; k < LPT; ++k) stage[lpage * C::PAGE_U4 + lpos[k]] = nxt[k];
+      for (int k = 0; k < LPT; ++k) stage[lpage * C::PAGE_U4 + lpos[k]] = nxt[d][k];
       const u32x4 tc0 = tn0, tc1 = tn1;
-      if (p + 1 < npairs) {
-        issue(p + 1);
-        tags_of(p + 1, tn0, tn1);
-      }
+      issue(nxt[d], p + RD);
+      if (p + 1 < npairs) tags_of(p + 1, tn0, tn1);
       __syncthreads();  // the pair is staged; everyone is done with the other buffer's previous pair
 
       const int P0 = wbase + 2 * p;
@@ -1104,10 +1103,11 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
           if (!__any(mine)) continue;
         }
       }
-      constexpr int KB = (NT == 1) ? C::KSTEPS : (NT == 2 ? 2 : 1);
-      constexpr int VB = (NT == 1) ? C::MT : (NT == 2 ? 4 : 2);
-      pair_compute<D, NT, KB, VB>(stage, qtile, ts, kr_even, kr_odd, vu, g, L, mask_from, P0, second_valid, own0,
-                                  own1, a.scale_log2);
+      constexpr int KB = 2;
+      constexpr int VB = 4;
+      pair_compute<D, NT, KB, VB, true>(stage, nullptr, ts, kr_even, kr_odd, vu, g, L, mask_from, P0, second_valid,
+                                        own0, own1, a.scale_log2, qr);
+    }
     }
   }
 
@@ -1149,8 +1149,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
   __shared__ int merge_flag;
   using C = Bf16Cfg<D>;
   constexpr int THREADS = NW * 64;
-  int* sched_base = (int*)(smem + 2 * C::STAGE_BYTES + (size_t)NW * 16 * NT * D * 2 + 2 * NW * 16 * NT * 4 +
-                          (BLK_WIN + 4) * 4);
+  int* sched_base = (int*)(smem + 2 * C::STAGE_BYTES + (BLK_WIN + 4) * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
   const Sched sc = sched_at(sched_base, a.B);
   const Shares sh = build_schedule<THREADS>(a, sc, scratch);
@@ -1513,12 +1512,12 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   int rows_cap = rows_per_group(kv, step->max_new_per_seq, &qpg, &nt);
   if (rows_cap == 0) return ASPD_ERR_UNSUPPORTED;
   // Branch chunks bring many rows per KV head: the waves then split the rows (one fetch of the pages per
-  // ROWS_NW * 48 rows) instead of the keys.
+  // ROWS_NW * 16 * ROWS_NT rows) instead of the keys.
   const int G_ = kv->num_q_heads / kv->num_kv_heads;
   const bool by_rows = mode == MODE_CHUNK && kv->dtype == ASPD_BF16 && G_ <= 16 * NT_MAX &&
                        (step->max_new_per_seq == 0 || step->max_new_per_seq * G_ > 16 * NT_MAX);
   if (by_rows) {
-    rows_cap = ROWS_NW * 16 * NT_MAX;
+    rows_cap = ROWS_NW * 16 * ROWS_NT;
     qpg = rows_cap / G_;
   }
   const size_t need = aspd_workspace_bytes(kv, state->B, step->NQ);
@@ -1576,11 +1575,11 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   } while (0)
   if (by_rows) {
     if (D == 128)
-      ASPD_LAUNCH((attn_bf16_rows_kernel<128, NT_MAX, ROWS_NW>), ROWS_NW * 64,
-                  (rows_smem_bytes<128, NT_MAX, ROWS_NW>(state->B)));
+      ASPD_LAUNCH((attn_bf16_rows_kernel<128, ROWS_NT, ROWS_NW>), ROWS_NW * 64,
+                  (rows_smem_bytes<128, ROWS_NT, ROWS_NW>(state->B)));
     else
-      ASPD_LAUNCH((attn_bf16_rows_kernel<64, NT_MAX, ROWS_NW>), ROWS_NW * 64,
-                  (rows_smem_bytes<64, NT_MAX, ROWS_NW>(state->B)));
+      ASPD_LAUNCH((attn_bf16_rows_kernel<64, ROWS_NT, ROWS_NW>), ROWS_NW * 64,
+                  (rows_smem_bytes<64, ROWS_NT, ROWS_NW>(state->B)));
   } else if (kv->dtype == ASPD_BF16) {
 #define ASPD_BF16_CASE(DD, NN)                                                                            \
   do {                                                                                                    \
@@ -1621,7 +1620,7 @@ extern "C" size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ)
   // two partial slots per workgroup of the largest grid any device would get, for whichever kernel
   // needs more rows in total
   size_t slot_rows = (size_t)2 * MAX_WG * rows_cap;
-  if (kv->dtype == ASPD_BF16) slot_rows = std::max(slot_rows, (size_t)2 * MAX_WG_ROWS * ROWS_NW * 16 * NT_MAX);
+  if (kv->dtype == ASPD_BF16) slot_rows = std::max(slot_rows, (size_t)2 * MAX_WG_ROWS * ROWS_NW * 16 * ROWS_NT);
   return COUNTER_BYTES + slot_rows * (kv->head_dim + 4) * sizeof(float);
 }
 
