@@ -129,6 +129,30 @@ def test_config5_chunk_then_decode(A, scale, batch):
                        label=f"cfg5 decode scale={scale}")
 
 
+# --------------------------------------------------------------------------------------------- many sequences
+def test_large_batch_decode_and_serial(A):
+    """More sequences than a wave has lanes (the schedule's search over sequences takes its other path)
+    and more units than workgroups: config 3's mix, 150 sequences, short prefixes."""
+    from gpu_drive import assert_state_equal
+    wl = W.config(3, scale=0.06, batch=150)
+    gb, tt = _grow_both(A, wl, np.minimum(wl.branch_len, 24) - 1, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label="batch150 parallel")
+    chunk = np.full(wl.NB, 3, dtype=np.int32)
+    meta = tt.append_parallel(chunk)
+    step = gb.parallel(chunk)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label="batch150 chunk")
+    tt.merge()
+    gb.merge()
+    one = np.ones(wl.B, dtype=np.int32)
+    meta = tt.append_serial(one)
+    step = gb.serial(one)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label="batch150 serial")
+    assert_state_equal(gb, tt)
+
+
 # --------------------------------------------------------------------------------------------- randomized small
 SMALL = [
     dict(seed=101, dtype="bf16", head_dim=128, num_q_heads=32, num_kv_heads=8),
