@@ -96,14 +96,18 @@ class TokenTable:
         return self._step_meta(rows, cu_new)
 
     def open_parallel(self, num_branches) -> None:
-        """Start a parallel stage with num_branches[s] branches (0 leaves the sequence serial)."""
+        """Start a parallel stage with num_branches[s] branches (0 leaves the sequence serial).
+        A sequence whose parallel stage is still running is named with the branch count it has and
+        stays as it is: sequences switch stages independently of one another (Sec. 3.3)."""
         num_branches = np.asarray(num_branches)
         assert num_branches.shape == (self.B,)
         for s in range(self.B):
+            if self.cur_parallel[s]:
+                assert int(num_branches[s]) == len(self.tokens_in_branch[s]), "a running stage keeps its branches"
+                continue
             if int(num_branches[s]) == 0:
                 self.tokens_in_branch[s] = []
                 continue
-            assert not self.cur_parallel[s]
             self.cur_stage[s] += 1
             self.cur_parallel[s] = True
             self.stage_first_slot[s] = len(self.pos[s])
@@ -129,9 +133,42 @@ class TokenTable:
         np.cumsum(new_len, out=cu_new[1:])
         return self._step_meta(rows, cu_new)
 
-    def merge(self) -> None:
-        """All branches done: back to one main branch.  Nothing in the cache moves."""
+    def append_mixed(self, new_len_branch, new_len_main) -> StepMeta:
+        """One append call over a batch in which some sequences are in a parallel stage and the others
+        serial: new_len_branch[b] tokens for every open branch b (global index), new_len_main[s]
+        main-branch tokens for every serial sequence s (0 for the others).  Rows are sequence-major."""
+        new_len_branch = np.asarray(new_len_branch)
+        new_len_main = np.asarray(new_len_main)
+        assert new_len_main.shape == (self.B,)
+        rows = []
+        starts = []
+        g = 0
         for s in range(self.B):
+            if self.cur_parallel[s]:
+                assert int(new_len_main[s]) == 0, "no main-branch token while branches are open"
+                for k in range(len(self.tokens_in_branch[s])):
+                    starts.append(len(rows))
+                    for _ in range(int(new_len_branch[g])):
+                        t = self.tokens_in_branch[s][k]
+                        slot = self._push(s, k + 1, t, self.stage_start_pos[s] + t)
+                        self.tokens_in_branch[s][k] = t + 1
+                        rows.append((s, g, slot))
+                    g += 1
+            else:
+                for _ in range(int(new_len_main[s])):
+                    slot = self._push(s, MAIN, self.main_count[s], len(self.pos[s]))
+                    self.main_count[s] += 1
+                    rows.append((s, -1, slot))
+        assert g == new_len_branch.shape[0]
+        cu_new = np.array(starts + [len(rows)], dtype=np.int32)   # first packed row of every branch, then NQ
+        return self._step_meta(rows, cu_new)
+
+    def merge(self, which=None) -> None:
+        """All branches done: back to one main branch.  Nothing in the cache moves.
+        `which` (bool per sequence) merges only some of the sequences; None merges all."""
+        for s in range(self.B):
+            if which is not None and not bool(which[s]):
+                continue
             if self.cur_parallel[s]:
                 self.cur_parallel[s] = False
                 self.cur_stage[s] += 1

@@ -69,6 +69,105 @@ def test_worked_examples(golden_dir, name):
         assert kv_len[slot] == len(vis)
 
 
+def test_mixed_batch_worked_example(golden_dir):
+    """Sequences of one batch switch stages independently: hand-derived rows and final tables."""
+    tt = TokenTable(np.arange(16, dtype=np.int32).reshape(2, 8), 16)
+    meta, rows, slots = None, [], []
+
+    def check_rows():
+        if meta is None:
+            return
+        got = list(zip(meta.q_seq.tolist(), meta.q_branch.tolist(), meta.logical_slot.tolist(),
+                       meta.position_ids.tolist(), meta.kv_len.tolist()))
+        assert got == rows, (got, rows)
+
+    for line in open(os.path.join(golden_dir, "mixed_batch_example.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        w = line.split()
+        if w[0] == "call":
+            check_rows()
+            meta, rows = None, []
+            if w[1] == "serial":
+                meta = tt.append_serial([int(x) for x in w[2:]])
+            elif w[1] == "open":
+                tt.open_parallel([int(x) for x in w[2:]])
+            elif w[1] == "merge":
+                tt.merge([int(x) for x in w[2:]])
+            elif w[1] == "mixed":
+                bar = w.index("|")
+                meta = tt.append_mixed([int(x) for x in w[2:bar]], [int(x) for x in w[bar + 1:]])
+        elif w[0] == "row":
+            rows.append(tuple(int(x) for x in w[1:]))
+        elif w[0] == "slot":
+            i = w.index(":")
+            slots.append(tuple(int(x) for x in w[1:i]) + ({int(x) for x in w[i + 1:]},))
+    check_rows()
+    assert [len(p) for p in tt.pos] == [6, 6]
+    for s, slot, branch, stage, pos, vis in slots:
+        assert (tt.branch[s][slot], tt.stage[s][slot], tt.pos[s][slot]) == (branch, stage, pos), (s, slot)
+        assert {j for j in range(len(tt.pos[s])) if tt.visible_pair(s, slot, j)} == vis, (s, slot)
+        assert set(np.nonzero(tt.dense_mask(s, [slot])[0])[0]) == vis
+    assert tt.stage_base().tolist() == [6, 2] and tt.branch_len().tolist() == [1, 1, 2]
+
+
+def test_mixed_batch_equals_sequences_alone():
+    """Sequences do not interact: a batch driven through mixed calls, with stages opening and ending
+    at different times, gives each sequence what it gets alone through the single-mode calls."""
+    rng = np.random.default_rng(11)
+    B = 5
+    batch = TokenTable(np.arange(B * 8, dtype=np.int32).reshape(B, 8), 16)
+    alone = [TokenTable(np.arange(8, dtype=np.int32)[None, :] + 8 * s, 16) for s in range(B)]
+    start = rng.integers(1, 4, size=B)
+    batch.append_serial(start)
+    for s in range(B):
+        alone[s].append_serial([start[s]])
+    K = [0] * B                        # open branches per sequence
+    for step in range(14):
+        # some serial sequences open a stage, some running stages end
+        opening = [K[s] == 0 and rng.random() < 0.4 for s in range(B)]
+        ending = [K[s] > 0 and rng.random() < 0.25 for s in range(B)]
+        if any(ending):
+            batch.merge(ending)
+            for s in range(B):
+                if ending[s]:
+                    alone[s].merge()
+                    K[s] = 0
+        if any(opening):
+            for s in range(B):
+                if opening[s]:
+                    K[s] = int(rng.integers(1, 4))
+                    alone[s].open_parallel([K[s]])
+            batch.open_parallel(K)
+        nb = [rng.integers(0, 3, size=K[s]) for s in range(B)]
+        nm = [int(rng.integers(0, 3)) if K[s] == 0 else 0 for s in range(B)]
+        meta = batch.append_mixed(np.concatenate(nb + [np.zeros(0, dtype=np.int64)]), nm)
+        row = 0
+        g0 = 0
+        for s in range(B):
+            m1 = alone[s].append_parallel(nb[s]) if K[s] else alone[s].append_serial([nm[s]])
+            n = m1.NQ
+            sl = slice(row, row + n)
+            assert meta.q_seq[sl].tolist() == [s] * n
+            assert meta.logical_slot[sl].tolist() == m1.logical_slot.tolist()
+            assert meta.position_ids[sl].tolist() == m1.position_ids.tolist()
+            assert meta.kv_len[sl].tolist() == m1.kv_len.tolist()
+            assert meta.slot_mapping[sl].tolist() == m1.slot_mapping.tolist()
+            want_branch = [b + g0 if b >= 0 else -1 for b in m1.q_branch.tolist()]
+            assert meta.q_branch[sl].tolist() == want_branch
+            assert meta.cu_seq_new[s] == row
+            row += n
+            g0 += K[s]
+        assert meta.NQ == row and meta.cu_new[-1] == row
+    for s in range(B):
+        assert batch.pos[s] == alone[s].pos[0] and batch.branch[s] == alone[s].branch[0]
+        assert batch.stage[s] == alone[s].stage[0]
+        T = len(batch.pos[s])
+        assert (batch.dense_mask(s, range(T)) == alone[s].dense_mask(0, range(T))).all()
+    assert batch.stage_base().tolist() == [int(a.stage_base()[0]) for a in alone]
+
+
 # ----------------------------------------------------------------------------- brute force
 def _visible_set_by_history(stages, slot_of):
     """Independent enumeration from the prose of Sec. 3.3: a parallel token attends the tokens of
