@@ -56,6 +56,7 @@ extern "C" {
 #define ASPD_STAGE_PARALLEL 0 /* append new_len[b] tokens to branch b of the running parallel stage */
 #define ASPD_STAGE_SERIAL   1 /* append new_len[s] main-branch tokens to sequence s                 */
 #define ASPD_STAGE_MERGE    2 /* the parallel stage ends; no token is appended, no KV is touched     */
+#define ASPD_STAGE_MIXED    3 /* PARALLEL for the sequences with open branches, SERIAL for the others */
 
 #define ASPD_POS_SAME_SEQ 0 /* Eq. 4 as adopted by the paper (Sec. 4.5.3, "Same-Sequential")     */
 
@@ -67,6 +68,8 @@ extern "C" {
 #define ASPD_FAULT_OWNER_ROW   2 /* a sequence outgrew owner_stride                                   */
 #define ASPD_FAULT_ROW_COUNT   4 /* the sum of new_len exceeded aspd_step.NQ                          */
 #define ASPD_FAULT_BRANCHES    8 /* a sequence has more than ASPD_MAX_BRANCHES_PER_SEQ branches        */
+#define ASPD_FAULT_STAGE      16 /* main-branch tokens for a sequence whose branches are open, or a
+                                    running stage whose branch count changes                           */
 
 /* The one reusable KV cache (paper: abstract, Sec. 2.3).  K and V each are
  * [num_blocks][num_kv_heads][block_size][head_dim] elements of `dtype`, so the rows one KV head
@@ -129,11 +132,27 @@ typedef struct aspd_step {
  *   be 0 (finished branch: its KV stays, it gets no query) or > 1 (chunk append).
  * SERIAL:   new_len_d[B]; main-branch token gets position = number of tokens already in the sequence
  *   (its flattened index); seq_len grows and stage_base follows it.  state->NB / branch arrays unused.
- * MERGE:    new_len_d and out may be NULL; stage_base[s] <- seq_len[s].  No KV is read or written.
+ * MERGE:    out may be NULL; stage_base[s] <- seq_len[s] for every sequence, or, when new_len_d is
+ *   given, for the sequences with new_len_d[s] != 0 ([B]; Sec. 3.3: every response switches modes on
+ *   its own).  No KV is read or written.
+ * MIXED:    new_len_d[NB + B]: first the tokens per open branch as in PARALLEL, then the main-branch
+ *   tokens per sequence as in SERIAL.  A sequence that owns branches (cu_branches) takes its branch
+ *   entries and must have main entry 0; a sequence that owns none takes its main entry.  Rows stay
+ *   sequence-major; out->cu_new_d [NB+1] holds the first row of every branch, then NQ.  The attention
+ *   call for such a step is aspd_attn_parallel_decode or aspd_attn_branch_chunk.
  * pos_mode must be ASPD_POS_SAME_SEQ.  out->NQ must equal the sum of new_len (known to the caller;
  * rows beyond it are dropped and ASPD_FAULT_ROW_COUNT is raised). */
 ASPD_API int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int32_t stage, int32_t pos_mode,
                            const int32_t* new_len_d, aspd_step* out, void* stream);
+
+/* Sequences open and end their parallel stages at different times (Sec. 3.3), which renumbers the
+ * batch's branches.  Given the new exclusive scan of branches per sequence, writes the new branch_len
+ * array [new NB]: the branches of a stage still running (stage_base < seq_len; their count must not
+ * change, else ASPD_FAULT_STAGE) keep the tokens they hold, every other entry starts at 0.  The new
+ * arrays must not be the ones in `state`; afterwards the caller points state->cu_branches_d,
+ * branch_len_d and NB at them.  Reads no KV. */
+ASPD_API int aspd_renumber_branches(const aspd_state* state, const int32_t* new_cu_branches_d,
+                                    int32_t* new_branch_len_d, void* stream);
 
 /* Bytes of device scratch the attention calls need for partial softmax results of split key
  * ranges (host-only computation, needs no GPU).  Returns 0 on invalid arguments. */

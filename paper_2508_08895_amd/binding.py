@@ -17,11 +17,11 @@ LIB_PATH = os.path.join(_HERE, "libaspd.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
-STAGE_PARALLEL, STAGE_SERIAL, STAGE_MERGE = 0, 1, 2
+STAGE_PARALLEL, STAGE_SERIAL, STAGE_MERGE, STAGE_MIXED = 0, 1, 2, 3
 POS_SAME_SEQ = 0
-FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES = 1, 2, 4, 8
+FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES, FAULT_STAGE = 1, 2, 4, 8, 16
 
-EXPORTS = ("aspd_build_branch_meta", "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
+EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
            "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_probe_read_bandwidth", "aspd_status_string")
 
 
@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
         L.aspd_build_branch_meta.restype = C.c_int
         L.aspd_build_branch_meta.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_state), C.c_int32, C.c_int32,
                                              C.c_void_p, C.POINTER(aspd_step), C.c_void_p]
+        L.aspd_renumber_branches.restype = C.c_int
+        L.aspd_renumber_branches.argtypes = [C.POINTER(aspd_state), C.c_void_p, C.c_void_p, C.c_void_p]
         L.aspd_workspace_bytes.restype = C.c_size_t
         L.aspd_workspace_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
         for name in ("aspd_attn_parallel_decode", "aspd_attn_branch_chunk", "aspd_attn_serial_decode"):
@@ -163,16 +165,17 @@ class Step:
 def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: torch.Tensor | None,
                            NQ: int = 0, step: Step | None = None, stream=None,
                            max_new_per_seq: int = 0) -> Step | None:
-    """See aspd.h.  `NQ` = sum of new_len, known to the caller.  Returns the Step (None for MERGE)."""
+    """See aspd.h.  `NQ` = sum of new_len, known to the caller.  Returns the Step (None for MERGE,
+    where new_len, if given, says per sequence whether its stage ends)."""
     kvs, sts = kv.struct(), state.struct()
     if stage == STAGE_MERGE:
-        rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, POS_SAME_SEQ, None, None,
+        rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, POS_SAME_SEQ, _ptr(new_len), None,
                                           _stream(stream))
         if rc != OK:
             raise AspdError(rc, "aspd_build_branch_meta")
         return None
     if step is None:
-        step = Step(NQ, state.NB if stage == STAGE_PARALLEL else state.B, state.B, state.device,
+        step = Step(NQ, state.B if stage == STAGE_SERIAL else state.NB, state.B, state.device,
                     max_new_per_seq)
     sps = step.struct()
     rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, POS_SAME_SEQ, _ptr(new_len),
@@ -180,6 +183,22 @@ def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: 
     if rc != OK:
         raise AspdError(rc, "aspd_build_branch_meta")
     return step
+
+
+def aspd_renumber_branches(state: BatchState, new_cu_branches: torch.Tensor, stream=None) -> None:
+    """See aspd.h: switches `state` to the branch numbering `new_cu_branches` ([B+1], any device);
+    branches of stages still running keep their lengths, the others start at zero."""
+    new_cu = new_cu_branches.to(device=state.device, dtype=torch.int32)
+    new_nb = int(new_cu_branches[-1])
+    new_len = torch.zeros(max(new_nb, 1), dtype=torch.int32, device=state.device)
+    if state.cu_branches is None:          # no branch has ever been open: nothing to carry over
+        state.cu_branches, state.branch_len, state.NB = new_cu, new_len, new_nb
+        return
+    sts = state.struct()
+    rc = lib().aspd_renumber_branches(C.byref(sts), _ptr(new_cu), _ptr(new_len), _stream(stream))
+    if rc != OK:
+        raise AspdError(rc, "aspd_renumber_branches")
+    state.cu_branches, state.branch_len, state.NB = new_cu, new_len, new_nb
 
 
 def aspd_workspace_bytes(kv: KVCache, B: int, NQ: int) -> int:

@@ -35,8 +35,12 @@ __device__ __forceinline__ void raise_fault(int32_t* fault, int bits) {
 
 // PARALLEL stage: new_len[NB].  Branch tokens take position stage_start + index-in-branch (Eq. 4,
 // second case) and are laid at the tail of the sequence ordered by (branch, token).
+// MIXED: main_len[B] as well.  Sequences switch between serial and parallel decoding independently
+// (Sec. 3.3), so one call may serve sequences with open branches (their branch entries of new_len)
+// and sequences without (their entry of main_len: main-branch tokens, Eq. 4 first case).
 __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, StateView st, StepView sp,
-                                                                     const int32_t* __restrict__ new_len) {
+                                                                     const int32_t* __restrict__ new_len,
+                                                                     const int32_t* __restrict__ main_len) {
   __shared__ int red[META_THREADS / 64];
   __shared__ int off[ASPD_MAX_BRANCHES_PER_SEQ + 2];  // exclusive scan of this sequence's new_len
   __shared__ int held[ASPD_MAX_BRANCHES_PER_SEQ + 1]; // tokens each branch already holds
@@ -55,7 +59,47 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
   // packed row of this sequence's first new token
   int part = 0;
   for (int i = tid; i < b0; i += META_THREADS) part += new_len[i];
+  if (main_len)
+    for (int i = tid; i < s; i += META_THREADS) part += main_len[i];
   const int base = block_sum(part, red);
+  const int c_main = main_len ? main_len[s] : 0;
+
+  if (K == 0) {
+    // no open branch: the sequence is serial and takes main-branch tokens (or none)
+    if (tid == 0) {
+      sp.cu_seq_new[s] = base;
+      if (s == st.B - 1) {
+        sp.cu_seq_new[st.B] = base + c_main;
+        sp.cu_new[b1] = base + c_main;
+      }
+    }
+    bool ok = true;
+    if ((long)T + c_main > (long)kv.max_blocks_per_seq * ASPD_BLOCK) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE); }
+    if (base + c_main > sp.NQ) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_ROW_COUNT); }
+    if (c_main > 0 && L != T) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_STAGE); }  // unmerged stage
+    if (!ok || c_main == 0) return;
+    for (int idx = tid; idx < c_main; idx += META_THREADS) {
+      const int row = base + idx;
+      const int slot = T + idx;
+      const int blk = kv.block_tables[(long)s * kv.max_blocks_per_seq + slot / ASPD_BLOCK];
+      if (blk < 0 || blk >= kv.num_blocks) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE);
+      sp.q_seq[row] = s;
+      sp.q_branch[row] = -1;
+      sp.position_ids[row] = slot;
+      sp.logical_slot[row] = slot;
+      sp.slot_mapping[row] = (int64_t)blk * ASPD_BLOCK + slot % ASPD_BLOCK;
+      sp.kv_len[row] = slot + 1;
+    }
+    if (tid == 0) {  // T and L were read before any barrier; nobody else touches this sequence
+      st.seq_len[s] = T + c_main;
+      st.stage_base[s] = T + c_main;
+    }
+    return;
+  }
+  if (c_main != 0) {  // main-branch tokens while branches are open: refuse the sequence
+    if (tid == 0) raise_fault(st.fault, ASPD_FAULT_STAGE);
+    return;
+  }
 
   // scan over the sequence's own branches (K <= 255: one branch per thread, serial scan by thread 0
   // would do, but a log-step scan keeps the launch short for wide stages)
@@ -168,9 +212,25 @@ __global__ __launch_bounds__(META_THREADS) void meta_serial_kernel(KvView kv, St
 
 // MERGE: the parallel stage ends.  Everything decoded so far becomes visible to all later queries;
 // the cache is reused as it is (Sec. 3.3: no re-prefill when switching back).
-__global__ void meta_merge_kernel(StateView st) {
+__global__ void meta_merge_kernel(StateView st, const int32_t* __restrict__ which /* null: every sequence */) {
   const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s < st.B) st.stage_base[s] = st.seq_len[s];
+  if (s < st.B && (!which || which[s] != 0)) st.stage_base[s] = st.seq_len[s];
+}
+
+// Branch numbering changes when sequences open or end stages at different times: the tokens held by
+// the branches of stages still running move to their branches' new indices, every other entry starts
+// at zero.  A stage is running while stage_base < seq_len (one that holds no token yet has only zeros).
+__global__ void meta_renumber_kernel(StateView st, const int32_t* __restrict__ new_cu,
+                                     int32_t* __restrict__ new_len_held) {
+  const int s = blockIdx.x;
+  const int o0 = st.cu_branches[s], k_old = st.cu_branches[s + 1] - o0;
+  const int n0 = new_cu[s], k_new = new_cu[s + 1] - n0;
+  const bool running = st.stage_base[s] < st.seq_len[s];
+  if (running && k_new != k_old) {
+    if (threadIdx.x == 0) raise_fault(st.fault, ASPD_FAULT_STAGE);
+    return;
+  }
+  for (int k = threadIdx.x; k < k_new; k += blockDim.x) new_len_held[n0 + k] = running ? st.branch_len[o0 + k] : 0;
 }
 
 }  // namespace
@@ -198,11 +258,12 @@ extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int3
   StateView sv = make_view(state);
 
   if (stage == ASPD_STAGE_MERGE) {
-    hipLaunchKernelGGL(meta_merge_kernel, dim3((state->B + 255) / 256), dim3(256), 0, hs, sv);
+    hipLaunchKernelGGL(meta_merge_kernel, dim3((state->B + 255) / 256), dim3(256), 0, hs, sv, new_len_d);
     ASPD_HIP_CHECK(hipGetLastError());
     return ASPD_OK;
   }
-  if (stage != ASPD_STAGE_PARALLEL && stage != ASPD_STAGE_SERIAL) return ASPD_ERR_INVALID_ARG;
+  if (stage != ASPD_STAGE_PARALLEL && stage != ASPD_STAGE_SERIAL && stage != ASPD_STAGE_MIXED)
+    return ASPD_ERR_INVALID_ARG;
   if (!new_len_d || !out || out->NQ < 0) return ASPD_ERR_INVALID_ARG;
   if (!out->cu_new_d || !out->cu_seq_new_d) return ASPD_ERR_INVALID_ARG;
   if (out->NQ > 0 && (!out->q_seq_d || !out->q_branch_d || !out->position_ids_d || !out->logical_slot_d ||
@@ -210,14 +271,30 @@ extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int3
     return ASPD_ERR_INVALID_ARG;
   KvView kvv = make_view(kv);
   StepView spv = make_view(out);
-  if (stage == ASPD_STAGE_PARALLEL) {
-    if (state->NB <= 0 || !state->cu_branches_d || !state->branch_len_d || !state->slot_owner_d ||
-        state->owner_stride <= 0)
+  if (stage == ASPD_STAGE_PARALLEL || stage == ASPD_STAGE_MIXED) {
+    if (state->NB < (stage == ASPD_STAGE_PARALLEL ? 1 : 0) || !state->cu_branches_d || !state->branch_len_d ||
+        !state->slot_owner_d || state->owner_stride <= 0)
       return ASPD_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(meta_parallel_kernel, dim3(state->B), dim3(META_THREADS), 0, hs, kvv, sv, spv, new_len_d);
+    const int32_t* main_len_d = stage == ASPD_STAGE_MIXED ? new_len_d + state->NB : nullptr;
+    hipLaunchKernelGGL(meta_parallel_kernel, dim3(state->B), dim3(META_THREADS), 0, hs, kvv, sv, spv, new_len_d,
+                       main_len_d);
   } else {
     hipLaunchKernelGGL(meta_serial_kernel, dim3(state->B), dim3(META_THREADS), 0, hs, kvv, sv, spv, new_len_d);
   }
+  ASPD_HIP_CHECK(hipGetLastError());
+  return ASPD_OK;
+}
+
+extern "C" int aspd_renumber_branches(const aspd_state* state, const int32_t* new_cu_branches_d,
+                                      int32_t* new_branch_len_d, void* stream) {
+  if (!state || state->B <= 0 || !state->stage_base_d || !state->seq_len_d || !state->cu_branches_d ||
+      !state->branch_len_d || !new_cu_branches_d || !new_branch_len_d)
+    return ASPD_ERR_INVALID_ARG;
+  if (state->B > ASPD_MAX_BATCH) return ASPD_ERR_UNSUPPORTED;
+  if (new_cu_branches_d == state->cu_branches_d || new_branch_len_d == state->branch_len_d)
+    return ASPD_ERR_INVALID_ARG;  // the old arrays are read while the new ones are written
+  hipLaunchKernelGGL(meta_renumber_kernel, dim3(state->B), dim3(64), 0, (hipStream_t)stream, make_view(state),
+                     new_cu_branches_d, new_branch_len_d);
   ASPD_HIP_CHECK(hipGetLastError());
   return ASPD_OK;
 }

@@ -39,8 +39,19 @@ class GpuBatch:
         return A.aspd_build_branch_meta(self.kv, self.state, A.STAGE_PARALLEL, self._dev_i32(new_len),
                                         NQ=int(np.sum(new_len)))
 
-    def merge(self):
-        A.aspd_build_branch_meta(self.kv, self.state, A.STAGE_MERGE, None)
+    def merge(self, which=None):
+        A.aspd_build_branch_meta(self.kv, self.state, A.STAGE_MERGE,
+                                 None if which is None else self._dev_i32(np.asarray(which, dtype=np.int32)))
+
+    def renumber(self, num_branches):
+        """Branch count per sequence after some stages opened / ended."""
+        cu = np.zeros(len(num_branches) + 1, dtype=np.int32)
+        np.cumsum(num_branches, out=cu[1:])
+        A.aspd_renumber_branches(self.state, torch.from_numpy(cu))
+
+    def mixed(self, new_len_branch, new_len_main):
+        both = np.concatenate([np.asarray(new_len_branch, dtype=np.int32), np.asarray(new_len_main, dtype=np.int32)])
+        return A.aspd_build_branch_meta(self.kv, self.state, A.STAGE_MIXED, self._dev_i32(both), NQ=int(both.sum()))
 
     def grow_to(self, branch_len):
         """Prefix, open the parallel stage, grow the branches one token per active branch per step."""

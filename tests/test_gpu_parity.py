@@ -129,6 +129,77 @@ def test_config5_chunk_then_decode(A, scale, batch):
                        label=f"cfg5 decode scale={scale}")
 
 
+# --------------------------------------------------------------------------------------------- mixed batches
+@pytest.mark.parametrize("seed,dtype", [(21, "bf16"), (22, "f32")])
+def test_mixed_batch_stages_switch_independently(A, seed, dtype):
+    """Sequences open and end their parallel stages at different times; every call serves serial and
+    parallel sequences together (MIXED append, per-sequence merge, branch renumbering).  Metadata
+    bit-exact, attention against the dense-mask oracle, state equal after every call."""
+    from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
+    rng = np.random.default_rng(seed)
+    kw = dict(dtype=dtype, head_dim=64 if dtype == "f32" else 128, num_q_heads=4 if dtype == "f32" else 16,
+              num_kv_heads=4, batch=6, prefix_range=(3, 90), branches_range=(4, 4), branch_len_range=(40, 40))
+    wl = W.random_small(seed=seed, **kw)        # sizes the pools and block tables: <= 4 branches x 40 tokens
+    gb = GpuBatch(wl)
+    tt = table_with_prefix(wl)
+    gb.serial(wl.prefix_len)
+    B = wl.B
+    K = [0] * B
+    budget = [4 * 40 - 8] * B                   # tokens a sequence may still take
+    for it in range(12):
+        ending = [K[s] > 0 and rng.random() < 0.3 for s in range(B)]
+        if any(ending):
+            tt.merge(ending)
+            gb.merge(ending)
+            for s in range(B):
+                if ending[s]:
+                    K[s] = 0
+        opening = [K[s] == 0 and rng.random() < 0.5 for s in range(B)]
+        if any(ending) or any(opening):
+            for s in range(B):
+                if opening[s]:
+                    K[s] = int(rng.integers(1, 5))
+            tt.open_parallel(K)
+            gb.renumber(K)
+        chunky = it % 4 == 3
+        nb, nm = [], []
+        for s in range(B):
+            if K[s]:
+                n = rng.integers(0, 4 if chunky else 2, size=K[s])
+                if n.sum() > budget[s]:
+                    n[:] = 0
+                nb.append(n)
+                nm.append(0)
+            else:
+                nb.append(np.zeros(0, dtype=np.int64))
+                nm.append(int(rng.integers(0, 3 if chunky else 2)) if budget[s] > 4 else 0)
+            budget[s] -= int(nb[-1].sum()) + nm[-1]
+        nbv = np.concatenate(nb)
+        if nbv.sum() + sum(nm) == 0:
+            continue
+        meta = tt.append_mixed(nbv, nm)
+        step = gb.mixed(nbv, nm)
+        assert_step_equal(step, meta)
+        fn = A.aspd_attn_branch_chunk if chunky else A.aspd_attn_parallel_decode
+        _compare_attention(A, gb, tt, wl, step, meta, fn, label=f"mixed seed={seed} call {it}")
+        assert_state_equal(gb, tt)
+
+
+def test_mixed_rejects_main_tokens_under_open_branches(A):
+    """A sequence with open branches cannot take a main-branch token: it is left as it was."""
+    from gpu_drive import GpuBatch
+    wl = W.random_small(seed=31, dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=4, batch=2,
+                        branches_range=(2, 2))
+    gb = GpuBatch(wl)
+    gb.serial(wl.prefix_len)
+    gb.renumber([2, 0])
+    before = gb.state.seq_len.cpu().numpy().copy()
+    gb.mixed([1, 1], [1, 1])                     # sequence 0 owns branches and still asks for a main token
+    after = gb.state.seq_len.cpu().numpy()
+    assert gb.fault() & A.FAULT_STAGE
+    assert after[0] == before[0] and after[1] == before[1] + 1
+
+
 # --------------------------------------------------------------------------------------------- many sequences
 def test_large_batch_decode_and_serial(A):
     """More sequences than a wave has lanes (the schedule's search over sequences takes its other path)
