@@ -154,6 +154,18 @@ ASPD_API int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int32_
 ASPD_API int aspd_renumber_branches(const aspd_state* state, const int32_t* new_cu_branches_d,
                                     int32_t* new_branch_len_d, void* stream);
 
+/* The step between aspd_build_branch_meta and the attention call: Eq. 4's position ids act on the
+ * scores through the rotary encoding of queries and keys (RoFormer's definition, rotate-half layout:
+ * pairs (i, i + head_dim/2), pair i turns by position * rope_theta^(-2i/head_dim); the layout of the
+ * base models of Sec. 4).  For every new token r of `step`:
+ *   q_d[r]      [num_q_heads][head_dim]  rotated in place by position_ids[r];
+ *   k_new_d[r]  [num_kv_heads][head_dim] rotated and written to the cache at slot_mapping[r];
+ *   v_new_d[r]  [num_kv_heads][head_dim] written to the cache at slot_mapping[r] as it is.
+ * All three are device arrays of kv->dtype, rows in the packed order of the step.  Arithmetic in
+ * fp32 with the angle formed in fp64; bf16 results are rounded to nearest even.  rope_theta > 1. */
+ASPD_API int aspd_rope_append(const aspd_kv* kv, const aspd_step* step, void* q_d, const void* k_new_d,
+                              const void* v_new_d, float rope_theta, void* stream);
+
 /* Bytes of device scratch the attention calls need for partial softmax results of split key
  * ranges (host-only computation, needs no GPU).  Returns 0 on invalid arguments. */
 ASPD_API size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ);

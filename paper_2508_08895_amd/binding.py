@@ -21,7 +21,7 @@ STAGE_PARALLEL, STAGE_SERIAL, STAGE_MERGE, STAGE_MIXED = 0, 1, 2, 3
 POS_SAME_SEQ = 0
 FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES, FAULT_STAGE = 1, 2, 4, 8, 16
 
-EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
+EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_rope_append", "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
            "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_probe_read_bandwidth", "aspd_status_string")
 
 
@@ -65,6 +65,9 @@ def lib() -> C.CDLL:
                                              C.c_void_p, C.POINTER(aspd_step), C.c_void_p]
         L.aspd_renumber_branches.restype = C.c_int
         L.aspd_renumber_branches.argtypes = [C.POINTER(aspd_state), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.aspd_rope_append.restype = C.c_int
+        L.aspd_rope_append.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_step), C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_float, C.c_void_p]
         L.aspd_workspace_bytes.restype = C.c_size_t
         L.aspd_workspace_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
         for name in ("aspd_attn_parallel_decode", "aspd_attn_branch_chunk", "aspd_attn_serial_decode"):
@@ -199,6 +202,17 @@ def aspd_renumber_branches(state: BatchState, new_cu_branches: torch.Tensor, str
     if rc != OK:
         raise AspdError(rc, "aspd_renumber_branches")
     state.cu_branches, state.branch_len, state.NB = new_cu, new_len, new_nb
+
+
+def aspd_rope_append(kv: KVCache, step: Step, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                     rope_theta: float, stream=None) -> torch.Tensor:
+    """See aspd.h: rotates q in place, writes rotated k_new and plain v_new into the cache.  Returns q."""
+    kvs, sps = kv.struct(), step.struct()
+    rc = lib().aspd_rope_append(C.byref(kvs), C.byref(sps), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                C.c_float(rope_theta), _stream(stream))
+    if rc != OK:
+        raise AspdError(rc, "aspd_rope_append")
+    return q
 
 
 def aspd_workspace_bytes(kv: KVCache, B: int, NQ: int) -> int:

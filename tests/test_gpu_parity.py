@@ -200,6 +200,58 @@ def test_mixed_rejects_main_tokens_under_open_branches(A):
     assert after[0] == before[0] and after[1] == before[1] + 1
 
 
+# --------------------------------------------------------------------------------------------- rotary append
+@pytest.mark.parametrize("seed,dtype,theta", [(41, "f32", 10000.0), (42, "bf16", 1e6), (43, "bf16", 10000.0)])
+def test_rope_append_then_attention(A, seed, dtype, theta):
+    """Metadata -> rotary encoding + cache append -> attention, against the oracle's chain of the same
+    three steps.  Checked: the rotated queries, every cache row written, that nothing else in the
+    pools changed, and the attention outputs computed from the cache the kernel wrote."""
+    from oracle import rope_append
+    kw = dict(dtype=dtype, head_dim=64 if dtype == "f32" else 128, num_q_heads=4 if dtype == "f32" else 16,
+              num_kv_heads=4 if dtype == "f32" else 8, batch=4, prefix_range=(20, 3000))
+    wl = W.random_small(seed=seed, **kw)
+    gb, tt = _grow_both(A, wl, wl.branch_len - 1, False)
+    tol = TOL[wl.dtype]
+    rng = np.random.default_rng(seed)
+    for new_len, fn in ((np.ones(wl.NB, dtype=np.int32), A.aspd_attn_parallel_decode),
+                        (rng.integers(0, 4, size=wl.NB).astype(np.int32), A.aspd_attn_branch_chunk)):
+        meta = tt.append_parallel(new_len)
+        step = gb.parallel(new_len)
+        NQ = meta.NQ
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        g = torch.Generator().manual_seed(seed + NQ)
+        q = (torch.randn(NQ, wl.num_q_heads, wl.head_dim, generator=g) * wl.sigma).to(tdt)
+        k_new = (torch.randn(NQ, wl.num_kv_heads, wl.head_dim, generator=g) * wl.sigma).to(tdt)
+        v_new = (torch.randn(NQ, wl.num_kv_heads, wl.head_dim, generator=g) * wl.sigma).to(tdt)
+        k_before, v_before = gb.kv.k.clone(), gb.kv.v.clone()
+        q_dev = A.aspd_rope_append(gb.kv, step, q.to(gb.dev), k_new.to(gb.dev), v_new.to(gb.dev), theta)
+        torch.cuda.synchronize()
+        # oracle chain, float64 throughout, on copies of the pools as they were before the call
+        k64 = k_before.double().cpu().numpy()
+        v64 = v_before.double().cpu().numpy()
+        q_ref = rope_append(q.double().numpy(), k_new.double().numpy(), v_new.double().numpy(), meta.position_ids,
+                            meta.slot_mapping, k64, v64, theta)
+        assert np.abs(q_dev.double().cpu().numpy() - q_ref).max() <= tol
+        k_got, v_got = gb.kv.k.double().cpu().numpy(), gb.kv.v.double().cpu().numpy()
+        written = np.zeros(k64.shape[0] * 16, dtype=bool)
+        written[meta.slot_mapping] = True
+        written = written.reshape(-1, 16)
+        kt, vt = k_got.transpose(0, 2, 1, 3), v_got.transpose(0, 2, 1, 3)      # [blocks][16][Hkv][D]
+        kr, vr = k64.transpose(0, 2, 1, 3), v64.transpose(0, 2, 1, 3)
+        assert np.abs(kt[written] - kr[written]).max() <= tol
+        assert np.array_equal(vt[written], vr[written])                        # values are copied, not computed
+        same = lambda a, b: np.array_equal(a, b, equal_nan=True)               # unmapped blocks hold NaN
+        assert same(kt[~written], kr[~written]) and same(vt[~written], vr[~written])
+        # attention on the cache the kernel wrote, against the oracle on the cache the oracle wrote
+        lse = torch.full((NQ, wl.num_q_heads), float("nan"), dtype=torch.float32, device=gb.dev)
+        out = fn(gb.kv, gb.state, step, q_dev, gb.workspace, lse=lse)
+        torch.cuda.synchronize()
+        ref, _ = attend(tt, meta, torch.from_numpy(q_ref), torch.from_numpy(k64), torch.from_numpy(v64))
+        err = np.abs(out.double().cpu().numpy() - ref).max()
+        print(f"[rope seed={seed} {fn.__name__}] rows={NQ} max|out-ref|={err:.3e}", flush=True)
+        assert err <= tol
+
+
 # --------------------------------------------------------------------------------------------- many sequences
 def test_large_batch_decode_and_serial(A):
     """More sequences than a wave has lanes (the schedule's search over sequences takes its other path)

@@ -126,3 +126,38 @@ def test_bad_state_and_step_are_rejected_before_launch():
     rc = L.aspd_attn_parallel_decode(C.byref(kv_wide), C.byref(st), C.byref(sp), 0x100, 0x200, None, 0.0, 0x300,
                                      1 << 30, None)
     assert rc == A.ERR_UNSUPPORTED
+
+
+def test_rope_append_and_renumber_reject_bad_arguments_before_launch():
+    L = A.lib()
+    kv = _kv()
+    sp = dict(NQ=1, max_new_per_seq=0, cu_new_d=0x10, cu_seq_new_d=0x10, q_seq_d=0x10, q_branch_d=0x10,
+              position_ids_d=0x10, logical_slot_d=0x10, slot_mapping_d=0x10, kv_len_d=0x10)
+
+    def rope(kv_=kv, sp_over=None, q=0x100, k=0x200, v=0x300, theta=10000.0):
+        s = A.aspd_step(**{**sp, **(sp_over or {})})
+        return L.aspd_rope_append(C.byref(kv_), C.byref(s), q, k, v, theta, None)
+
+    assert rope(kv_=_kv(head_dim=96)) == A.ERR_UNSUPPORTED
+    assert rope(q=None) == A.ERR_INVALID_ARG
+    assert rope(k=None) == A.ERR_INVALID_ARG
+    assert rope(v=None) == A.ERR_INVALID_ARG
+    assert rope(theta=1.0) == A.ERR_INVALID_ARG
+    assert rope(theta=float("nan")) == A.ERR_INVALID_ARG
+    assert rope(sp_over=dict(NQ=-2)) == A.ERR_INVALID_ARG
+    assert rope(sp_over=dict(slot_mapping_d=None)) == A.ERR_INVALID_ARG
+    assert rope(sp_over=dict(NQ=0), q=None) == A.OK            # nothing to do, nothing launched
+
+    st = dict(B=2, NB=1, stage_base_d=0x10, seq_len_d=0x20, cu_branches_d=0x30, branch_len_d=0x40,
+              slot_owner_d=0x50, owner_stride=64, fault_d=None)
+
+    def renumber(st_over=None, new_cu=0x400, new_len=0x500):
+        s = A.aspd_state(**{**st, **(st_over or {})})
+        return L.aspd_renumber_branches(C.byref(s), new_cu, new_len, None)
+
+    assert renumber(new_cu=None) == A.ERR_INVALID_ARG
+    assert renumber(new_len=None) == A.ERR_INVALID_ARG
+    assert renumber(new_cu=0x30) == A.ERR_INVALID_ARG          # must not be the array in use
+    assert renumber(new_len=0x40) == A.ERR_INVALID_ARG
+    assert renumber(st_over=dict(B=0)) == A.ERR_INVALID_ARG
+    assert renumber(st_over=dict(cu_branches_d=None)) == A.ERR_INVALID_ARG
