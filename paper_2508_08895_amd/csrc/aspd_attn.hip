@@ -110,6 +110,7 @@ struct AttnArgs {
 struct Item {
   int s, rg, h;     // sequence, row group, KV head
   int np;           // pages of the item
+  int lp;           // pages of it that lie wholly before stage_base (no owner tags, no masking)
   int q0, nq;       // first packed query row and number of queries of the row group
   int first_unit;   // flattened index of the item's page 0
 };
@@ -196,11 +197,27 @@ __device__ Item locate(const AttnArgs& a, const Sched& sc, int pad, int u, int* 
   it.h = idx / ngroups;       // row groups of one KV head are neighbours: they read the same pages
   it.rg = idx - it.h * ngroups;
   it.first_unit = sc.cu_units[lo] + idx * vl;
+  it.lp = a.slot_owner ? min(it.np, sc.L[lo] / ASPD_BLOCK) : it.np;
   const int qs = sc.q0[lo];
   const int nq = sc.q0[lo + 1] - qs;
   it.q0 = qs + it.rg * a.qpg;
   it.nq = min(a.qpg, nq - it.rg * a.qpg);
   return it;
+}
+
+// Cutting one item among its k workgroups (aligned regime).  A page of the branch region costs a wave
+// about one and a half times a page before it (owner tags, masking, the scores that are thrown away),
+// so the cut is even in cost(p) = 2p + max(0, p - lp) rather than in pages: piece j starts at the first
+// page p with cost(p) * k >= j * cost(np), and page p belongs to piece cost(p) * k / cost(np).
+__device__ __forceinline__ int item_cut(const Item& it, int j, int k) {
+  const int total = 2 * it.np + (it.np - it.lp);
+  const int t = (int)(((unsigned)j * (unsigned)total + (unsigned)k - 1u) / (unsigned)k);
+  return t <= 2 * it.lp ? (t + 1) >> 1 : it.lp + (t - 2 * it.lp + 2) / 3;
+}
+__device__ __forceinline__ int item_piece(const Item& it, int page, int k) {
+  const int total = 2 * it.np + (it.np - it.lp);
+  const int cost = 2 * page + max(0, page - it.lp);
+  return min(k - 1, (int)((unsigned)cost * (unsigned)k / (unsigned)total));
 }
 
 template <bool WAVE>
@@ -217,7 +234,7 @@ __device__ int share_begin(const AttnArgs& a, const Sched& sc, const Shares& sh,
     else if (w >= sh.rnd(it.first_unit + it.np)) it = locate<WAVE>(a, sc, 0, it.first_unit + it.np, &vpage);
     const int w0 = sh.rnd(it.first_unit);
     const int k = sh.rnd(it.first_unit + it.np) - w0;
-    return it.first_unit + (int)((unsigned)(w - w0) * (unsigned)it.np / (unsigned)k);
+    return it.first_unit + item_cut(it, w - w0, k);
   }
   const int vl = it.np + sh.pad;
   if (vpage <= sh.pad + sh.tol) return it.first_unit;
@@ -323,7 +340,7 @@ __device__ int share_owner(const AttnArgs& a, const Sched& sc, const Shares& sh,
     const Item it = locate<true>(a, sc, 0, u, &page);
     const int w0 = sh.rnd(it.first_unit);
     const int k = sh.rnd(it.first_unit + it.np) - w0;
-    return w0 + (int)((((unsigned)page + 1u) * (unsigned)k - 1u) / (unsigned)it.np);
+    return w0 + item_piece(it, page, k);
   }
   int lo = 0, hi = sh.n - 1;  // last w with wgb[w] <= u
   while (lo < hi) {
