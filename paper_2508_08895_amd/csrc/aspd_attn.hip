@@ -206,17 +206,18 @@ __device__ Item locate(const AttnArgs& a, const Sched& sc, int pad, int u, int* 
 }
 
 // Cutting one item among its k workgroups (aligned regime).  A page of the branch region costs a wave
-// about one and a half times a page before it (owner tags, masking, the scores that are thrown away),
-// so the cut is even in cost(p) = 2p + max(0, p - lp) rather than in pages: piece j starts at the first
-// page p with cost(p) * k >= j * cost(np), and page p belongs to piece cost(p) * k / cost(np).
+// more than a page before it (owner tags, masking, scores that are thrown away): measured between 1.1
+// and 1.5 times, taken as 1.25.  The cut is therefore even in cost(p) = 4p + max(0, p - lp) rather than
+// in pages: piece j starts at the first page p with cost(p) * k >= j * cost(np), and page p belongs to
+// piece cost(p) * k / cost(np).
 __device__ __forceinline__ int item_cut(const Item& it, int j, int k) {
-  const int total = 2 * it.np + (it.np - it.lp);
+  const int total = 4 * it.np + (it.np - it.lp);
   const int t = (int)(((unsigned)j * (unsigned)total + (unsigned)k - 1u) / (unsigned)k);
-  return t <= 2 * it.lp ? (t + 1) >> 1 : it.lp + (t - 2 * it.lp + 2) / 3;
+  return t <= 4 * it.lp ? (t + 3) >> 2 : it.lp + (t - 4 * it.lp + 4) / 5;
 }
 __device__ __forceinline__ int item_piece(const Item& it, int page, int k) {
-  const int total = 2 * it.np + (it.np - it.lp);
-  const int cost = 2 * page + max(0, page - it.lp);
+  const int total = 4 * it.np + (it.np - it.lp);
+  const int cost = 4 * page + max(0, page - it.lp);
   return min(k - 1, (int)((unsigned)cost * (unsigned)k / (unsigned)total));
 }
 
