@@ -1532,8 +1532,10 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   // Branch chunks bring many rows per KV head: the waves then split the rows (one fetch of the pages per
   // ROWS_NW * 16 * ROWS_NT rows) instead of the keys.
   const int G_ = kv->num_q_heads / kv->num_kv_heads;
-  const bool by_rows = mode == MODE_CHUNK && kv->dtype == ASPD_BF16 && G_ <= 16 * NT_MAX &&
-                       (step->max_new_per_seq == 0 || step->max_new_per_seq * G_ > 16 * NT_MAX);
+  // Calls that say so through the hint (a prefill through the serial call, say) take the same kernel.
+  const bool many_rows = step->max_new_per_seq * G_ > 16 * NT_MAX;
+  const bool by_rows = kv->dtype == ASPD_BF16 && G_ <= 16 * NT_MAX &&
+                       (many_rows || (mode == MODE_CHUNK && step->max_new_per_seq == 0));
   if (by_rows) {
     rows_cap = ROWS_NW * 16 * ROWS_NT;
     qpg = rows_cap / G_;

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import aspd_workloads as W
-from oracle import attend
+from oracle import attend, TokenTable
 from oracle_drive import table_with_prefix
 
 pytestmark = pytest.mark.gpu
@@ -198,6 +198,44 @@ def test_mixed_rejects_main_tokens_under_open_branches(A):
     after = gb.state.seq_len.cpu().numpy()
     assert gb.fault() & A.FAULT_STAGE
     assert after[0] == before[0] and after[1] == before[1] + 1
+
+
+# --------------------------------------------------------------------------------------------- whole sequences
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_prefill_and_teacher_forced_branches(A, dtype):
+    """Many tokens per call: a prompt prefilled through the serial call (causal among the new tokens, on
+    top of tokens already cached), then every branch appended whole in one chunk call (the
+    branch-sequential arrangement: a branch token sees the prefix and the earlier tokens of its own
+    branch only), then a multi-token main-branch append after the merge."""
+    from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
+    kw = dict(dtype=dtype, head_dim=64 if dtype == "f32" else 128, num_q_heads=4 if dtype == "f32" else 32,
+              num_kv_heads=4 if dtype == "f32" else 8, batch=3, prefix_range=(200, 700), branches_range=(2, 5),
+              branch_len_range=(30, 150), extra_tokens_per_seq=80)
+    wl = W.random_small(seed=51, **kw)
+    gb = GpuBatch(wl)
+    tt = TokenTable(wl.block_tables, wl.block_size)
+
+    def serial(new_len, label):
+        new_len = np.asarray(new_len, dtype=np.int32)
+        meta = tt.append_serial(new_len)
+        step = A.aspd_build_branch_meta(gb.kv, gb.state, A.STAGE_SERIAL, gb._dev_i32(new_len), NQ=int(new_len.sum()),
+                                        max_new_per_seq=int(new_len.max()))
+        assert_step_equal(step, meta)
+        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label=label)
+
+    first = wl.prefix_len // 3
+    serial(first, "prefill part 1")
+    serial(wl.prefix_len - first, "prefill part 2")
+    tt.open_parallel(wl.num_branches)
+    gb.open_parallel()
+    meta = tt.append_parallel(wl.branch_len)          # every branch whole, one call
+    step = gb.parallel(wl.branch_len)
+    assert_step_equal(step, meta)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label="teacher-forced branches")
+    tt.merge()
+    gb.merge()
+    serial(np.full(wl.B, 40), "main branch after merge, 40 tokens")
+    assert_state_equal(gb, tt)
 
 
 # --------------------------------------------------------------------------------------------- rotary append
