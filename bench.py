@@ -264,6 +264,36 @@ def main() -> int:
                           "algorithmic_MB": round(bts / 1e6, 3), "GBps": round(bts / avg / 1e9, 1),
                           "frac_of_8TBps": round(bts / avg / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # ---- the step before the attention call: rotary encoding of the new tokens fused with their cache append
+    # (aspd_rope_append), for the rows of the parallel-decode call; not part of the timed step above
+    if "parallel" in snaps:
+        _, c = snaps["parallel"]
+        step_p, q_p = c[3], c[4].clone()
+        k_new = (torch.randn(step_p.NQ, wl.num_kv_heads, wl.head_dim, device=dev) * wl.sigma).to(wl.torch_dtype)
+        v_new = (torch.randn(step_p.NQ, wl.num_kv_heads, wl.head_dim, device=dev) * wl.sigma).to(wl.torch_dtype)
+
+        def rope_body():
+            for _ in range(REP):
+                A.aspd_rope_append(kv, step_p, q_p, k_new, v_new, 1e6)
+
+        rope_body()
+        runner = rope_body
+        if not args.no_graph:
+            gk = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gk):
+                rope_body()
+            runner = gk.replay
+        runner()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        runner()
+        e1.record()
+        torch.cuda.synchronize()
+        per_call["rope_append"] = {"launches_per_step": 0, "avg_us": round(e0.elapsed_time(e1) * 1e3 / REP, 2),
+                                   "query_tokens_per_launch": int(step_p.NQ),
+                                   "note": "rows of the parallel-decode call; outside the timed step"}
+
     # ---- what a plain read-only stream reaches on this device (2 GiB, larger than any cache)
     probe_src = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
     probe_src.zero_()
