@@ -166,6 +166,12 @@ ASPD_API int aspd_renumber_branches(const aspd_state* state, const int32_t* new_
 ASPD_API int aspd_rope_append(const aspd_kv* kv, const aspd_step* step, void* q_d, const void* k_new_d,
                               const void* v_new_d, float rope_theta, void* stream);
 
+/* Caps the number of workgroups (one per compute unit for bf16, two for fp32) an attention launch may
+ * use, for callers that run other kernels next to the attention calls and want compute units left for
+ * them.  Process-wide, takes effect with the next attention call; 0 (the default) removes the cap.
+ * Results do not depend on it.  Returns the previous value. */
+ASPD_API int32_t aspd_set_max_workgroups(int32_t max_workgroups);
+
 /* Bytes of device scratch the attention calls need for partial softmax results of split key
  * ranges (host-only computation, needs no GPU).  Returns 0 on invalid arguments. */
 ASPD_API size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ);

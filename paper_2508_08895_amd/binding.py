@@ -21,7 +21,8 @@ STAGE_PARALLEL, STAGE_SERIAL, STAGE_MERGE, STAGE_MIXED = 0, 1, 2, 3
 POS_SAME_SEQ = 0
 FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES, FAULT_STAGE = 1, 2, 4, 8, 16
 
-EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_rope_append", "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
+EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_rope_append", "aspd_set_max_workgroups",
+           "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
            "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_probe_read_bandwidth", "aspd_status_string")
 
 
@@ -68,6 +69,8 @@ def lib() -> C.CDLL:
         L.aspd_rope_append.restype = C.c_int
         L.aspd_rope_append.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_step), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_float, C.c_void_p]
+        L.aspd_set_max_workgroups.restype = C.c_int32
+        L.aspd_set_max_workgroups.argtypes = [C.c_int32]
         L.aspd_workspace_bytes.restype = C.c_size_t
         L.aspd_workspace_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
         for name in ("aspd_attn_parallel_decode", "aspd_attn_branch_chunk", "aspd_attn_serial_decode"):
@@ -213,6 +216,11 @@ def aspd_rope_append(kv: KVCache, step: Step, q: torch.Tensor, k_new: torch.Tens
     if rc != OK:
         raise AspdError(rc, "aspd_rope_append")
     return q
+
+
+def aspd_set_max_workgroups(n: int) -> int:
+    """See aspd.h: process-wide cap of the attention grids (0 = none).  Returns the previous value."""
+    return int(lib().aspd_set_max_workgroups(int(n)))
 
 
 def aspd_workspace_bytes(kv: KVCache, B: int, NQ: int) -> int:

@@ -17,6 +17,7 @@
 // unnormalised partial (running max, sum, accumulator); the workgroup that delivers the last partial
 // of an item combines them, in the same launch.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <mutex>
 #include <set>
@@ -1489,6 +1490,9 @@ int device_cu_count() {
   return n;
 }
 
+// Process-wide cap of the attention grids (0: none), see aspd_set_max_workgroups.
+std::atomic<int> g_workgroup_cap{0};
+
 constexpr int LDS_BYTES = 160 * 1024;  // per compute unit on gfx950
 constexpr int STATIC_LDS_RESERVE = 256;  // room for the kernels' few static LDS variables
 
@@ -1580,6 +1584,8 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   // pages are read once when no sequence can have more than one row group
   const bool stream_once = step->max_new_per_seq > 0 && step->max_new_per_seq <= qpg;
   nwg = std::min(nwg, (units_max + MIN_PAGES_PER_WG - 1) / MIN_PAGES_PER_WG);
+  const int cap = g_workgroup_cap.load(std::memory_order_relaxed);
+  if (cap > 0) nwg = std::min(nwg, (long)cap);
   nwg = std::max(1L, std::min(nwg, (long)MAX_WG));
   a.nwg = (int)nwg;
 
@@ -1685,6 +1691,10 @@ extern "C" int aspd_probe_read_bandwidth(const void* src_d, size_t bytes, void* 
                      bytes / 16, (unsigned*)sink_d);
   ASPD_HIP_CHECK(hipGetLastError());
   return ASPD_OK;
+}
+
+extern "C" int32_t aspd_set_max_workgroups(int32_t max_workgroups) {
+  return g_workgroup_cap.exchange(max_workgroups > 0 ? max_workgroups : 0, std::memory_order_relaxed);
 }
 
 extern "C" int aspd_workspace_init(void* workspace_d, size_t workspace_bytes, void* stream) {

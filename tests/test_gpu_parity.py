@@ -200,6 +200,54 @@ def test_mixed_rejects_main_tokens_under_open_branches(A):
     assert after[0] == before[0] and after[1] == before[1] + 1
 
 
+# --------------------------------------------------------------------------------------------- limits
+def test_capped_grid_and_long_segments(A):
+    """With the grid capped to two workgroups a 70 000-token sequence gives each of them more pages
+    than the block-id window holds (2 048), so the kernels walk several windows; results must not
+    depend on the cap.  Also: the cap is honoured when lifted again."""
+    wl = W.random_small(seed=61, dtype="bf16", head_dim=64, num_q_heads=2, num_kv_heads=1, batch=1,
+                        prefix_range=(70000, 70000), branches_range=(3, 3), branch_len_range=(40, 40),
+                        extra_tokens_per_branch=8)
+    gb, tt = _grow_both(A, wl, np.minimum(wl.branch_len, 2) - 1, False)
+    prev = A.aspd_set_max_workgroups(2)
+    try:
+        ones = np.ones(wl.NB, dtype=np.int32)
+        meta = tt.append_parallel(ones)
+        step = gb.parallel(ones)
+        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label="cap 2 parallel")
+        chunk = np.full(wl.NB, 30, dtype=np.int32)           # 90 tokens x 2 heads: the row-splitting kernel
+        meta = tt.append_parallel(chunk)
+        step = gb.parallel(chunk)
+        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label="cap 2 chunk")
+        assert A.aspd_set_max_workgroups(0) == 2
+        tt.merge()
+        gb.merge()
+        one = np.ones(wl.B, dtype=np.int32)
+        meta = tt.append_serial(one)
+        step = gb.serial(one)
+        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label="uncapped serial")
+    finally:
+        A.aspd_set_max_workgroups(prev)
+
+
+def test_most_branches_one_sequence_can_have(A):
+    """255 branches (owner tags are one byte): decode step and a 2-token chunk."""
+    from gpu_drive import assert_state_equal
+    wl = W.random_small(seed=62, dtype="bf16", head_dim=128, num_q_heads=8, num_kv_heads=2, batch=2,
+                        prefix_range=(40, 300), branches_range=(255, 255), branch_len_range=(1, 4),
+                        extra_tokens_per_branch=4)
+    gb, tt = _grow_both(A, wl, wl.branch_len - 1, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label="255 branches decode")
+    two = np.full(wl.NB, 2, dtype=np.int32)
+    meta = tt.append_parallel(two)
+    step = gb.parallel(two)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label="255 branches chunk")
+    assert_state_equal(gb, tt)
+
+
 # --------------------------------------------------------------------------------------------- whole sequences
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_prefill_and_teacher_forced_branches(A, dtype):
