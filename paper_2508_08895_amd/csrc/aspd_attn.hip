@@ -66,7 +66,11 @@ constexpr int ROWS_NT = ASPD_TUNE_ROWS_NT;            // 16-row tiles per wave t
 #ifndef ASPD_TUNE_RD
 #define ASPD_TUNE_RD 1
 #endif
-constexpr int ROWS_PREFETCH = ASPD_TUNE_RD;  // pairs of pages that kernel keeps on their way per workgroup
+constexpr int ROWS_PREFETCH = ASPD_TUNE_RD;  // groups of pages that kernel keeps on their way per workgroup
+#ifndef ASPD_TUNE_PPS
+#define ASPD_TUNE_PPS 2
+#endif
+constexpr int ROWS_PPS = ASPD_TUNE_PPS;      // pairs of pages it stages (and computes) between two barriers
 constexpr int MAX_WG_ROWS = 256;      // its largest grid (its partial slots are ROWS_NW * 16 * ROWS_NT rows each)
 constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
 constexpr int MAX_WG = 1024;          // upper bound of the grid (workspace is sized for it)
@@ -967,7 +971,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
 // ---------------------------------------------------------------------------------------------
 template <int D, int NT, int NW>
 size_t rows_smem_bytes(int B) {
-  return 2 * Bf16Cfg<D>::STAGE_BYTES + (BLK_WIN + 4) * 4 + (size_t)sched_ints(B) * 4;
+  return 2 * ROWS_PPS * Bf16Cfg<D>::STAGE_BYTES + (BLK_WIN + 4) * 4 + (size_t)sched_ints(B) * 4;
 }
 
 template <int D, int NT, int NW>
@@ -976,8 +980,10 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
   using C = Bf16Cfg<D>;
   constexpr int ROWS = 16 * NT;        // rows per wave
   constexpr int THREADS = NW * 64;
-  constexpr int PER_PAGE = THREADS / 4;  // threads that share the load of one page
-  static_assert(C::PAGE_U4 % PER_PAGE == 0, "page not divisible among its loaders");
+  constexpr int PPS = ROWS_PPS;          // pairs per stage: all of them are staged, then computed, between two barriers
+  constexpr int ARR = 4 * PPS;           // page arrays of a stage: K0 K1 V0 V1 of every pair
+  constexpr int PER_PAGE = THREADS / ARR;  // threads that share the load of one page
+  static_assert(THREADS % ARR == 0 && C::PAGE_U4 % PER_PAGE == 0, "page not divisible among its loaders");
   constexpr int LPT = C::PAGE_U4 / PER_PAGE;  // 16-byte loads per thread and page
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -988,8 +994,8 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
   const int Rw = min(ROWS, R - wave * ROWS);       // rows this wave owns (<= 0: none)
   const bool wave_active = Rw > 0;
 
-  u32x4* stage0 = (u32x4*)smem;                 // [2][K0 K1 V0 V1]
-  int* blk_lds = (int*)(smem + 2 * C::STAGE_BYTES);
+  u32x4* stage0 = (u32x4*)smem;                 // [2][PPS][K0 K1 V0 V1]
+  int* blk_lds = (int*)(smem + 2 * PPS * C::STAGE_BYTES);
 
   const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
   const uint8_t* owner_row = a.slot_owner ? uniform_ptr(a.slot_owner + (long)it.s * a.owner_stride) : nullptr;
@@ -1044,24 +1050,25 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
   int vu[4];
 #pragma unroll
   for (int b = 0; b < 4; ++b) vu[b] = vkey * (D / 4) + (((b ^ (vkey & 3)) << 2) | (c & 3));
-  // cooperative load: thread t loads chunks [lt * LPT, lt * LPT + LPT) ... of page (t / PER_PAGE),
-  // consecutive threads consecutive 16 bytes
-  const int lpage = tid / PER_PAGE;          // 0: K0, 1: K1, 2: V0, 3: V1
+  // cooperative load: PER_PAGE threads share one page array, consecutive threads consecutive 16 bytes
+  const int lpage = tid / PER_PAGE;          // pair lpage / 4 of the group, array lpage % 4: K0, K1, V0, V1
   const int lt = tid - lpage * PER_PAGE;
+  const bool l_is_k = (lpage & 3) < 2;
   int lpos[LPT];                             // swizzled positions inside the page
 #pragma unroll
   for (int k = 0; k < LPT; ++k) {
     const int i = lt + k * PER_PAGE;         // chunk index inside the page
     const int row = i / C::CH, ch = i - row * C::CH;
-    lpos[k] = (lpage < 2) ? k_swz<D>(row, ch) : v_swz<D>(row, ch);
+    lpos[k] = l_is_k ? k_swz<D>(row, ch) : v_swz<D>(row, ch);
   }
 
-  constexpr int RD = ROWS_PREFETCH;  // pairs on their way per workgroup (a ring of register sets)
+  constexpr int RD = ROWS_PREFETCH;  // groups on their way per workgroup (a ring of register sets)
   u32x4 nxt[RD][LPT];
   for (int wbase = page0; wbase < page1; wbase += BLK_WIN) {  // windows of block ids; normally one
     const int wend = min(page1, wbase + BLK_WIN);
     const int wpages = wend - wbase;
     const int npairs = (wpages + 1) >> 1;
+    const int ngroups = (npairs + PPS - 1) / PPS;
     if (wbase != page0) {
       __syncthreads();
 #pragma unroll
@@ -1069,63 +1076,78 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
         blk_lds[tid + k * THREADS] = min(max(bt[min(wbase + tid + k * THREADS, page1 - 1)], 0), a.kv.num_blocks - 1);
       __syncthreads();
     }
-    // This thread's slice of pair p.  Issued for every ring slot, also past the end of the window (the
-    // last pair again, which the caches hold): the number of loads younger than a slot is then fixed,
+    // This thread's slice of group gi.  Issued for every ring slot, also past the end of the window (the
+    // last pages again, which the caches hold): the number of loads younger than a slot is then fixed,
     // so waiting for the oldest slot leaves the younger ones in flight.
-    auto issue = [&](u32x4 (&dst)[LPT], int p) {
-      const int pg = min(2 * min(p, npairs - 1) + (lpage & 1), wpages - 1);
+    auto issue = [&](u32x4 (&dst)[LPT], int gi) {
+      const int p = min(gi * PPS + (lpage >> 2), npairs - 1);
+      const int pg = min(2 * p + (lpage & 1), wpages - 1);
       const int b = blk_lds[pg];
-      const u32x4* src = (const u32x4*)(lpage < 2 ? a.kv.k : a.kv.v) + ((long)b * a.kv.num_kv_heads + it.h) * C::PAGE_U4;
+      const u32x4* src = (const u32x4*)(l_is_k ? a.kv.k : a.kv.v) + ((long)b * a.kv.num_kv_heads + it.h) * C::PAGE_U4;
 #pragma unroll
       for (int k = 0; k < LPT; ++k) dst[k] = src[lt + k * PER_PAGE];
     };
-    // owner tags of a pair that reaches into the branch region, fetched one pair ahead like the pages
-    auto tags_of = [&](int p, u32x4& t0, u32x4& t1) {
-      const int P = wbase + 2 * p;
-      if (owner_row && (P + 2) * ASPD_BLOCK > mask_from) {
-        t0 = load_tags_uniform(owner_row + P * ASPD_BLOCK);
-        t1 = load_tags_uniform(owner_row + min(P + 1, page1 - 1) * ASPD_BLOCK);  // stays inside the owner row
-      }
-    };
-    u32x4 tn0 = {0, 0, 0, 0}, tn1 = {0, 0, 0, 0};
+    // owner tags of the pairs that reach into the branch region, fetched one group ahead like the pages
+    auto tags_of = [&](int gi, u32x4 (&t)[PPS][2]) {
 #pragma unroll
-    for (int d = 0; d < RD; ++d) issue(nxt[d], d);
-    tags_of(0, tn0, tn1);
-    for (int pbase = 0; pbase < npairs; pbase += RD) {
-#pragma unroll
-    for (int d = 0; d < RD; ++d) {  // the ring is unrolled so that every slot has fixed registers
-      const int p = pbase + d;
-      if (p >= npairs) break;
-      u32x4* stage = stage0 + (p & 1) * (C::STAGE_BYTES / 16);
-#pragma unroll
-      for (int k = 0; k < LPT; ++k) stage[lpage * C::PAGE_U4 + lpos[k]] = nxt[d][k];
-      const u32x4 tc0 = tn0, tc1 = tn1;
-      issue(nxt[d], p + RD);
-      if (p + 1 < npairs) tags_of(p + 1, tn0, tn1);
-      __syncthreads();  // the pair is staged; everyone is done with the other buffer's previous pair
-
-      const int P0 = wbase + 2 * p;
-      const bool second_valid = (P0 + 1) < wend;
-      if (!wave_active) continue;
-      uint32_t own0 = 0, own1 = 0;
-      if (owner_row && (P0 + 2) * ASPD_BLOCK > mask_from) {
-        own0 = lane_tags(tc0, g);
-        own1 = lane_tags(tc1, g);
-        // pairs wholly inside the branch region: skip if no key belongs to a branch of this wave's rows
-        if (P0 * ASPD_BLOCK >= L && tag_lo > 0) {
-          bool mine = false;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int own = (int)(((e < 4 ? own0 : own1) >> (8 * (e & 3))) & 0xff);
-            mine |= (own >= tag_lo && own <= tag_hi);
-          }
-          if (!__any(mine)) continue;
+      for (int h = 0; h < PPS; ++h) {
+        const int P = wbase + 2 * (gi * PPS + h);
+        if (owner_row && P < wend && (P + 2) * ASPD_BLOCK > mask_from) {
+          t[h][0] = load_tags_uniform(owner_row + P * ASPD_BLOCK);
+          t[h][1] = load_tags_uniform(owner_row + min(P + 1, page1 - 1) * ASPD_BLOCK);  // stays inside the owner row
         }
       }
-      constexpr int KB = 2;
-      constexpr int VB = 4;
-      pair_compute<D, NT, KB, VB, true>(stage, nullptr, ts, kr_even, kr_odd, vu, g, L, mask_from, P0, second_valid,
-                                        own0, own1, a.scale_log2, qr);
+    };
+    u32x4 tn[PPS][2];
+#pragma unroll
+    for (int h = 0; h < PPS; ++h) tn[h][0] = tn[h][1] = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int d = 0; d < RD; ++d) issue(nxt[d], d);
+    tags_of(0, tn);
+    for (int gbase = 0; gbase < ngroups; gbase += RD) {
+#pragma unroll
+    for (int d = 0; d < RD; ++d) {  // the ring is unrolled so that every slot has fixed registers
+      const int gi = gbase + d;
+      if (gi >= ngroups) break;
+      u32x4* stage = stage0 + (gi & 1) * (PPS * C::STAGE_BYTES / 16);
+#pragma unroll
+      for (int k = 0; k < LPT; ++k) stage[lpage * C::PAGE_U4 + lpos[k]] = nxt[d][k];
+      u32x4 tc[PPS][2];
+#pragma unroll
+      for (int h = 0; h < PPS; ++h) {
+        tc[h][0] = tn[h][0];
+        tc[h][1] = tn[h][1];
+      }
+      issue(nxt[d], gi + RD);
+      if (gi + 1 < ngroups) tags_of(gi + 1, tn);
+      __syncthreads();  // the group is staged; everyone is done with the other buffer's previous group
+
+      if (!wave_active) continue;
+#pragma unroll
+      for (int h = 0; h < PPS; ++h) {
+        const int P0 = wbase + 2 * (gi * PPS + h);
+        if (P0 >= wend) break;
+        const bool second_valid = (P0 + 1) < wend;
+        uint32_t own0 = 0, own1 = 0;
+        if (owner_row && (P0 + 2) * ASPD_BLOCK > mask_from) {
+          own0 = lane_tags(tc[h][0], g);
+          own1 = lane_tags(tc[h][1], g);
+          // pairs wholly inside the branch region: skip if no key belongs to a branch of this wave's rows
+          if (P0 * ASPD_BLOCK >= L && tag_lo > 0) {
+            bool mine = false;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const int own = (int)(((e < 4 ? own0 : own1) >> (8 * (e & 3))) & 0xff);
+              mine |= (own >= tag_lo && own <= tag_hi);
+            }
+            if (!__any(mine)) continue;
+          }
+        }
+        constexpr int KB = 2;
+        constexpr int VB = 4;
+        pair_compute<D, NT, KB, VB, true>(stage + h * 4 * C::PAGE_U4, nullptr, ts, kr_even, kr_odd, vu, g, L, mask_from,
+                                          P0, second_valid, own0, own1, a.scale_log2, qr);
+      }
     }
     }
   }
@@ -1168,7 +1190,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
   __shared__ int merge_flag;
   using C = Bf16Cfg<D>;
   constexpr int THREADS = NW * 64;
-  int* sched_base = (int*)(smem + 2 * C::STAGE_BYTES + (BLK_WIN + 4) * 4);
+  int* sched_base = (int*)(smem + 2 * ROWS_PPS * C::STAGE_BYTES + (BLK_WIN + 4) * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
   const Sched sc = sched_at(sched_base, a.B);
   const Shares sh = build_schedule<THREADS>(a, sc, scratch);
