@@ -431,15 +431,18 @@ struct Bf16Cfg {
   static constexpr int RPL = 64 / CH;           // rows of a page one load covers
   static constexpr int KSTEPS = D / 32;
   static constexpr int MT = D / 16;
-  static constexpr int STAGE_BYTES = 4 * PAGE_U4 * 16;  // K0 K1 V0 V1
+  // In LDS a row (one key, or one query row) is followed by 32 bytes of padding.  Measured with all
+  // waves of a compute unit reading: the K / Q operand reads (16 rows x one 16-byte chunk per quarter
+  // wave) and the transposing V reads then run at the rate of linear reads, where the XOR swizzles
+  // tried before them (chunk ^ row) cost 1.6 times that; writes are not affected.
+  static constexpr int LROW = CH + 2;            // uint4 per row in LDS
+  static constexpr int LPAGE_U4 = 16 * LROW;     // uint4 per page in LDS
+  static constexpr int STAGE_BYTES = 4 * LPAGE_U4 * 16;  // K0 K1 V0 V1
 };
 
+// Position (in 16-byte units) of 16-byte chunk `chunk` of row `row` inside a page or Q tile in LDS.
 template <int D>
-__device__ __forceinline__ int k_swz(int row, int chunk) { return row * Bf16Cfg<D>::CH + (chunk ^ (row & 7)); }
-template <int D>
-__device__ __forceinline__ int v_swz(int row, int chunk) {
-  return row * Bf16Cfg<D>::CH + ((((chunk >> 1) ^ (row & 3)) << 1) | (chunk & 1));
-}
+__device__ __forceinline__ int lds_pos(int row, int chunk) { return row * Bf16Cfg<D>::LROW + chunk; }
 
 // One pair of pages in flight: K page 0, K page 1, V page 0, V page 1.
 template <int D>
@@ -516,7 +519,7 @@ struct RowState {
 };
 
 // One pair of pages (32 keys) against NT 16-row tiles: scores, mask, running softmax, accumulation.
-// `stage` holds K page 0, K page 1, V page 0, V page 1 (swizzled), `qtile` the rows' Q (swizzled).
+// `stage` holds K page 0, K page 1, V page 0, V page 1 (padded rows), `qtile` the rows' Q (padded rows).
 // kr_even / kr_odd / vu are the lane's LDS bases (see the caller).  KB k-steps of K and VB d-tiles of
 // V are fetched from LDS at a time: large batches hide the LDS latency, small ones save registers.
 // QREG: the rows' Q operands come from registers (qr[n * KSTEPS + t]) instead of `qtile`.
@@ -540,15 +543,15 @@ __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qt
 #pragma unroll
       for (int tt = 0; tt < KB; ++tt) {
         const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
-        ka[tt] = *(const bf16x8*)&stage[0 * C::PAGE_U4 + kr];
-        kb[tt] = *(const bf16x8*)&stage[1 * C::PAGE_U4 + kr];
+        ka[tt] = *(const bf16x8*)&stage[0 * C::LPAGE_U4 + kr];
+        kb[tt] = *(const bf16x8*)&stage[1 * C::LPAGE_U4 + kr];
       }
 #pragma unroll
       for (int n = 0; n < NT; ++n) {
 #pragma unroll
         for (int tt = 0; tt < KB; ++tt) {
           const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
-          const bf16x8 qb = QREG ? qr[n * C::KSTEPS + t0 + tt] : *(const bf16x8*)&qtile[16 * n * C::CH + kr];
+          const bf16x8 qb = QREG ? qr[n * C::KSTEPS + t0 + tt] : *(const bf16x8*)&qtile[16 * n * C::LROW + kr];
           st[0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[tt], qb, st[0][n], 0, 0, 0);
           st[1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[tt], qb, st[1][n], 0, 0, 0);
         }
@@ -557,8 +560,8 @@ __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qt
 
     // ---- V^T operands through the LDS transpose read; the first batch is issued ahead of the
     // softmax so that its latency is hidden
-    const s16x4* vs0 = (const s16x4*)(stage + 2 * C::PAGE_U4);
-    const s16x4* vs1 = (const s16x4*)(stage + 3 * C::PAGE_U4);
+    const s16x4* vs0 = (const s16x4*)(stage + 2 * C::LPAGE_U4);
+    const s16x4* vs1 = (const s16x4*)(stage + 3 * C::LPAGE_U4);
 #define ASPD_V_UNIT(mt) (vu[(mt) & 3] + 16 * ((mt) >> 2))
     s16x4 va[VB], vb[VB];
 #pragma unroll
@@ -663,8 +666,8 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   const int R = it.nq * a.G;
 
   u32x4* stage = (u32x4*)(smem + wave * C::STAGE_BYTES);                // this wave's K0 K1 V0 V1
-  u32x4* qtile = (u32x4*)(smem + NW * C::STAGE_BYTES);                  // [ROWS][CH] swizzled
-  int* rowslot = (int*)(smem + NW * C::STAGE_BYTES + ROWS * D * 2);
+  u32x4* qtile = (u32x4*)(smem + NW * C::STAGE_BYTES);                  // [ROWS][LROW]
+  int* rowslot = (int*)(smem + NW * C::STAGE_BYTES + ROWS * C::LROW * 16);
   int* rowtag = rowslot + ROWS;
   float* wm = (float*)(rowtag + ROWS);                                  // [NW][ROWS]
   float* wl = wm + NW * ROWS;
@@ -713,7 +716,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     const int i = tid + k * THREADS;
     if (i < ROWS * C::CH) {
       const int r = i / C::CH, ch = i - r * C::CH;
-      qtile[k_swz<D>(r, ch)] = qreg[k];
+      qtile[lds_pos<D>(r, ch)] = qreg[k];
     }
   }
   if (tid < ROWS) {
@@ -734,21 +737,19 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   for (int off = 1; off < 16; off <<= 1) mask_from = min(mask_from, __shfl_xor(mask_from, off));
   mask_from = __builtin_amdgcn_readfirstlane(mask_from);
 
-  // LDS addressing: every swizzled position used in the loop is one of a few lane-dependent bases
+  // LDS addressing: every position used in the loop is one of a few lane-dependent bases
   // plus a compile-time offset (which the LDS instructions carry as an immediate).
   //   stage writes: lane owns 16-byte chunk (lane % CH) of row (lane / CH) + i * RPL
   const int wrow = lane / C::CH, wch = lane % C::CH;
-  const int kw_lo = k_swz<D>(wrow, wch);                 // rows whose bit 2 equals wrow's
-  const int kw_hi = k_swz<D>(wrow ^ 4, wch) - 4 * C::CH;  // rows with bit 2 flipped, same row base
-  const int vw = v_swz<D>(wrow, wch);                    // V swizzle depends on row & 3 only
+  const int kw = lds_pos<D>(wrow, wch);
   //   K / Q operand reads: row c, chunk 4t + g; t even and t odd differ in bit 2 of the chunk
-  const int kr_even = k_swz<D>(c, g);
-  const int kr_odd = k_swz<D>(c, 4 + g);
-  //   V transpose reads in 8-byte units: key 4g + c/4, d-tile mt swizzled by (key & 3) in its low 2 bits
+  const int kr_even = lds_pos<D>(c, g);
+  const int kr_odd = lds_pos<D>(c, 4 + g);
+  //   V transpose reads in 8-byte units: key 4g + c/4, d-tile mt at units 4 mt .. 4 mt + 3 of the row
   const int vkey = 4 * g + (c >> 2);
   int vu[4];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) vu[b] = vkey * (D / 4) + (((b ^ (vkey & 3)) << 2) | (c & 3));
+  for (int b = 0; b < 4; ++b) vu[b] = vkey * (2 * C::LROW) + 4 * b + (c & 3);
 
 #pragma unroll
   for (int n = 0; n < NT; ++n) {
@@ -811,16 +812,15 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
           more = false;
           break;
         }
-      // ---- registers -> this wave's LDS stage (swizzled)
+      // ---- registers -> this wave's LDS stage
 #pragma unroll
       for (int i = 0; i < C::LPP; ++i) {
-        // load i of a page is rows i*RPL.. of it: the swizzled position is one of two lane-dependent
-        // bases plus a compile-time offset
-        const int kw = ((i * C::RPL) & 4) ? kw_hi : kw_lo;
-        stage[0 * C::PAGE_U4 + i * 64 + kw] = pr[sl].r[0][i];
-        stage[1 * C::PAGE_U4 + i * 64 + kw] = pr[sl].r[1][i];
-        stage[2 * C::PAGE_U4 + i * 64 + vw] = pr[sl].r[2][i];
-        stage[3 * C::PAGE_U4 + i * 64 + vw] = pr[sl].r[3][i];
+        // the position is a lane-dependent base plus a compile-time offset
+        constexpr int STEP = C::RPL * C::LROW;  // load i of a page is rows i * RPL .. of it
+        stage[0 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[0][i];
+        stage[1 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[1][i];
+        stage[2 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[2][i];
+        stage[3 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[3][i];
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -926,7 +926,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
 
 template <int D, int NT, int NW>
 size_t bf16_smem_bytes(int B) {
-  return NW * Bf16Cfg<D>::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
+  return NW * Bf16Cfg<D>::STAGE_BYTES + 16 * NT * Bf16Cfg<D>::LROW * 16 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
          (BLK_WIN + 4) * 4 + (size_t)sched_ints(B) * 4;
 }
 
@@ -938,7 +938,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
   using C = Bf16Cfg<D>;
   constexpr int THREADS = NW * 64;
   // after the stages, the Q tile, row descriptors and wave statistics: the unit scan
-  int* sched_base = (int*)(smem + NW * C::STAGE_BYTES + 16 * NT * D * 2 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
+  int* sched_base = (int*)(smem + NW * C::STAGE_BYTES + 16 * NT * C::LROW * 16 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
                           (BLK_WIN + 4) * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
   const Sched sc = sched_at(sched_base, a.B);
@@ -1043,23 +1043,23 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
   tag_lo = __builtin_amdgcn_readfirstlane(tag_lo);
   tag_hi = __builtin_amdgcn_readfirstlane(tag_hi);
 
-  // LDS bases of this lane (same swizzles as the streaming kernel)
-  const int kr_even = k_swz<D>(c, g);
-  const int kr_odd = k_swz<D>(c, 4 + g);
+  // LDS bases of this lane (same layout as the streaming kernel)
+  const int kr_even = lds_pos<D>(c, g);
+  const int kr_odd = lds_pos<D>(c, 4 + g);
   const int vkey = 4 * g + (c >> 2);
   int vu[4];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) vu[b] = vkey * (D / 4) + (((b ^ (vkey & 3)) << 2) | (c & 3));
+  for (int b = 0; b < 4; ++b) vu[b] = vkey * (2 * C::LROW) + 4 * b + (c & 3);
   // cooperative load: PER_PAGE threads share one page array, consecutive threads consecutive 16 bytes
   const int lpage = tid / PER_PAGE;          // pair lpage / 4 of the group, array lpage % 4: K0, K1, V0, V1
   const int lt = tid - lpage * PER_PAGE;
   const bool l_is_k = (lpage & 3) < 2;
-  int lpos[LPT];                             // swizzled positions inside the page
+  int lpos[LPT];                             // positions inside the page in LDS
 #pragma unroll
   for (int k = 0; k < LPT; ++k) {
     const int i = lt + k * PER_PAGE;         // chunk index inside the page
     const int row = i / C::CH, ch = i - row * C::CH;
-    lpos[k] = l_is_k ? k_swz<D>(row, ch) : v_swz<D>(row, ch);
+    lpos[k] = lds_pos<D>(row, ch);
   }
 
   constexpr int RD = ROWS_PREFETCH;  // groups on their way per workgroup (a ring of register sets)
@@ -1111,7 +1111,7 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
       if (gi >= ngroups) break;
       u32x4* stage = stage0 + (gi & 1) * (PPS * C::STAGE_BYTES / 16);
 #pragma unroll
-      for (int k = 0; k < LPT; ++k) stage[lpage * C::PAGE_U4 + lpos[k]] = nxt[d][k];
+      for (int k = 0; k < LPT; ++k) stage[lpage * C::LPAGE_U4 + lpos[k]] = nxt[d][k];
       u32x4 tc[PPS][2];
 #pragma unroll
       for (int h = 0; h < PPS; ++h) {
@@ -1145,7 +1145,7 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
         }
         constexpr int KB = 2;
         constexpr int VB = 4;
-        pair_compute<D, NT, KB, VB, true>(stage + h * 4 * C::PAGE_U4, nullptr, ts, kr_even, kr_odd, vu, g, L, mask_from,
+        pair_compute<D, NT, KB, VB, true>(stage + h * 4 * C::LPAGE_U4, nullptr, ts, kr_even, kr_odd, vu, g, L, mask_from,
                                           P0, second_valid, own0, own1, a.scale_log2, qr);
       }
     }
