@@ -53,10 +53,20 @@ class StepMeta:
 
 
 class TokenTable:
-    def __init__(self, block_tables: np.ndarray, block_size: int):
+    def __init__(self, block_tables: np.ndarray, block_size: int, pos_mode="same_seq"):
+        """pos_mode: the position-id paradigm (Sec. 4.5.3).  "same_seq" is the one the paper adopts
+        (Eq. 4: after a parallel stage the main branch continues at the number of tokens decoded so
+        far).  The two it compares against, as read here: "same_max" - branches share positions in the
+        same way, but the main branch continues right after the largest position any branch reached;
+        ("fix", N) - branch k of a stage owns the pre-allocated interval [stage_start + k N,
+        stage_start + (k+1) N) and the main branch continues after the last interval."""
         self.block_tables = np.asarray(block_tables)
         self.block_size = int(block_size)
         self.B = int(self.block_tables.shape[0])
+        self.pos_mode = pos_mode
+        self.fix_n = int(pos_mode[1]) if isinstance(pos_mode, tuple) else 0
+        assert pos_mode in ("same_seq", "same_max") or (isinstance(pos_mode, tuple) and pos_mode[0] == "fix")
+        self.next_main_pos = [0] * self.B        # position id the next main-branch token takes
         # per sequence, per logical slot
         self.stage = [[] for _ in range(self.B)]
         self.branch = [[] for _ in range(self.B)]
@@ -79,6 +89,23 @@ class TokenTable:
         self.pos[s].append(pos)
         return slot
 
+    def _push_main(self, s: int) -> int:
+        """One main-branch token.  Same-Seq: its position is the number of tokens decoded before it, all
+        branches included (Eq. 4, first case); the other paradigms continue from where the merge left
+        the position counter."""
+        pos = len(self.pos[s]) if self.pos_mode == "same_seq" else self.next_main_pos[s]
+        slot = self._push(s, MAIN, self.main_count[s], pos)
+        self.main_count[s] += 1
+        self.next_main_pos[s] = pos + 1
+        return slot
+
+    def _branch_pos(self, s: int, k: int, t: int) -> int:
+        """Token t (0-based) of branch k (0-based) of the running stage: Eq. 4, second case."""
+        if self.fix_n:
+            assert t < self.fix_n, "branch outgrew its pre-allocated interval"
+            return self.stage_start_pos[s] + k * self.fix_n + t
+        return self.stage_start_pos[s] + t
+
     def append_serial(self, new_len) -> StepMeta:
         """Main-branch tokens: new_len[s] of them for sequence s (Eq. 4 case 1)."""
         new_len = np.asarray(new_len)
@@ -87,9 +114,7 @@ class TokenTable:
         for s in range(self.B):
             assert not self.cur_parallel[s], "merge before appending main tokens"
             for _ in range(int(new_len[s])):
-                pos = len(self.pos[s])               # tokens decoded before this one, all branches included
-                slot = self._push(s, MAIN, self.main_count[s], pos)
-                self.main_count[s] += 1
+                slot = self._push_main(s)
                 rows.append((s, -1, slot))
         cu_new = np.zeros(self.B + 1, dtype=np.int32)
         np.cumsum(new_len, out=cu_new[1:])
@@ -111,7 +136,9 @@ class TokenTable:
             self.cur_stage[s] += 1
             self.cur_parallel[s] = True
             self.stage_first_slot[s] = len(self.pos[s])
-            self.stage_start_pos[s] = len(self.pos[s])   # number of tokens before the stage
+            # position the first token of every branch takes: the number of tokens before the stage
+            # (Same-Seq), or wherever the main branch's position counter stands
+            self.stage_start_pos[s] = len(self.pos[s]) if self.pos_mode == "same_seq" else self.next_main_pos[s]
             self.tokens_in_branch[s] = [0] * int(num_branches[s])
 
     def append_parallel(self, new_len) -> StepMeta:
@@ -123,8 +150,7 @@ class TokenTable:
             for k in range(len(self.tokens_in_branch[s])):       # branch index ascending
                 for _ in range(int(new_len[g])):                 # token index ascending
                     t = self.tokens_in_branch[s][k]
-                    pos = self.stage_start_pos[s] + t
-                    slot = self._push(s, k + 1, t, pos)
+                    slot = self._push(s, k + 1, t, self._branch_pos(s, k, t))
                     self.tokens_in_branch[s][k] = t + 1
                     rows.append((s, g, slot))
                 g += 1
@@ -150,15 +176,13 @@ class TokenTable:
                     starts.append(len(rows))
                     for _ in range(int(new_len_branch[g])):
                         t = self.tokens_in_branch[s][k]
-                        slot = self._push(s, k + 1, t, self.stage_start_pos[s] + t)
+                        slot = self._push(s, k + 1, t, self._branch_pos(s, k, t))
                         self.tokens_in_branch[s][k] = t + 1
                         rows.append((s, g, slot))
                     g += 1
             else:
                 for _ in range(int(new_len_main[s])):
-                    slot = self._push(s, MAIN, self.main_count[s], len(self.pos[s]))
-                    self.main_count[s] += 1
-                    rows.append((s, -1, slot))
+                    rows.append((s, -1, self._push_main(s)))
         assert g == new_len_branch.shape[0]
         cu_new = np.array(starts + [len(rows)], dtype=np.int32)   # first packed row of every branch, then NQ
         return self._step_meta(rows, cu_new)
@@ -170,6 +194,12 @@ class TokenTable:
             if which is not None and not bool(which[s]):
                 continue
             if self.cur_parallel[s]:
+                if self.pos_mode == "same_max":
+                    self.next_main_pos[s] = self.stage_start_pos[s] + max(self.tokens_in_branch[s])
+                elif self.fix_n:
+                    self.next_main_pos[s] = self.stage_start_pos[s] + len(self.tokens_in_branch[s]) * self.fix_n
+                else:
+                    self.next_main_pos[s] = len(self.pos[s])
                 self.cur_parallel[s] = False
                 self.cur_stage[s] += 1
                 self.tokens_in_branch[s] = []

@@ -168,6 +168,69 @@ def test_mixed_batch_equals_sequences_alone():
     assert batch.stage_base().tolist() == [int(a.stage_base()[0]) for a in alone]
 
 
+def _paradigm_history(tt):
+    tt.append_serial([2])
+    tt.open_parallel([2])
+    for step in ([1, 1], [1, 0], [1, 0]):
+        tt.append_parallel(step)
+    tt.merge()
+    tt.append_serial([2])
+    tt.open_parallel([2])
+    return tt.append_parallel([1, 1])
+
+
+def test_position_paradigms_worked_example(golden_dir):
+    seen = 0
+    for line in open(os.path.join(golden_dir, "position_paradigms.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        name, want = line.split("|")
+        w = name.split()
+        mode = (w[0], int(w[1])) if w[0] == "fix" else w[0]
+        tt = TokenTable(np.arange(8, dtype=np.int32)[None, :], 16, pos_mode=mode)
+        meta = _paradigm_history(tt)
+        assert tt.pos[0] == [int(x) for x in want.split()], (mode, tt.pos[0])
+        assert meta.position_ids.tolist() == tt.pos[0][8:10]
+        # what a token may see does not depend on the paradigm: the same sets as under Eq. 4
+        ref = TokenTable(np.arange(8, dtype=np.int32)[None, :], 16)
+        _paradigm_history(ref)
+        assert (tt.dense_mask(0, range(10)) == ref.dense_mask(0, range(10))).all()
+        seen += 1
+    assert seen == 3
+
+
+def test_position_paradigms_properties():
+    """Same-Max: one branch makes it Same-Seq; with equal branch lengths K the main branch continues
+    (K - 1) * len earlier than under Same-Seq.  Fix-N: positions of a branch are consecutive inside its
+    own interval and intervals of different branches never overlap."""
+    rng = np.random.default_rng(5)
+    for trial in range(20):
+        K = int(rng.integers(1, 5))
+        lens = rng.integers(1, 6, size=K)
+        pre = int(rng.integers(1, 7))
+        tabs = {m: TokenTable(np.arange(8, dtype=np.int32)[None, :], 16, pos_mode=m)
+                for m in ("same_seq", "same_max", ("fix", 8))}
+        for m, tt in tabs.items():
+            tt.append_serial([pre])
+            tt.open_parallel([K])
+            for new_len in W.interleaved_history(lens):
+                tt.append_parallel(new_len)
+            tt.merge()
+            tt.append_serial([1])
+        T = pre + int(lens.sum())
+        assert tabs["same_seq"].pos[0][-1] == T
+        assert tabs["same_max"].pos[0][-1] == pre + int(lens.max())
+        if K == 1:
+            assert tabs["same_max"].pos[0] == tabs["same_seq"].pos[0]
+        assert tabs[("fix", 8)].pos[0][-1] == pre + 8 * K
+        fx = tabs[("fix", 8)]
+        for k in range(K):
+            mine = [fx.pos[0][j] for j in range(pre, T) if fx.branch[0][j] == k + 1]
+            assert mine == list(range(pre + 8 * k, pre + 8 * k + int(lens[k])))
+        assert tabs["same_max"].pos[0][:T] == tabs["same_seq"].pos[0][:T]   # inside the stage they agree
+
+
 # ----------------------------------------------------------------------------- brute force
 def _visible_set_by_history(stages, slot_of):
     """Independent enumeration from the prose of Sec. 3.3: a parallel token attends the tokens of
