@@ -58,7 +58,14 @@ extern "C" {
 #define ASPD_STAGE_MERGE    2 /* the parallel stage ends; no token is appended, no KV is touched     */
 #define ASPD_STAGE_MIXED    3 /* PARALLEL for the sequences with open branches, SERIAL for the others */
 
-#define ASPD_POS_SAME_SEQ 0 /* Eq. 4 as adopted by the paper (Sec. 4.5.3, "Same-Sequential")     */
+/* Position-id paradigms (Sec. 4.5.3).  What a token may attend to is the same under all of them. */
+#define ASPD_POS_SAME_SEQ 0 /* Eq. 4 as adopted by the paper ("Same-Sequential"): after a parallel stage
+                               the main branch continues at the number of tokens decoded so far         */
+#define ASPD_POS_SAME_MAX 1 /* branches share positions as in Eq. 4; after the stage the main branch
+                               continues right after the largest position any branch reached           */
+#define ASPD_POS_FIX_N(n) (2 | ((n) << 8)) /* branch k of a stage owns the pre-allocated interval
+                               [stage_start + k n, stage_start + (k+1) n), 1 <= n < 2^22; the main branch
+                               continues after the last interval                                        */
 
 #define ASPD_MAX_BATCH             512  /* sequences per call                                      */
 #define ASPD_MAX_BRANCHES_PER_SEQ  255  /* owner tags are one byte                                 */
@@ -70,6 +77,7 @@ extern "C" {
 #define ASPD_FAULT_BRANCHES    8 /* a sequence has more than ASPD_MAX_BRANCHES_PER_SEQ branches        */
 #define ASPD_FAULT_STAGE      16 /* main-branch tokens for a sequence whose branches are open, or a
                                     running stage whose branch count changes                           */
+#define ASPD_FAULT_INTERVAL   32 /* ASPD_POS_FIX_N: a branch would outgrow its interval of n positions  */
 
 /* The one reusable KV cache (paper: abstract, Sec. 2.3).  K and V each are
  * [num_blocks][num_kv_heads][block_size][head_dim] elements of `dtype`, so the rows one KV head
@@ -106,6 +114,10 @@ typedef struct aspd_state {
   int32_t        owner_stride;
   int32_t*       fault_d;        /* nullable; ASPD_FAULT_* bits are OR-ed in, tokens that would not
                                     fit are dropped instead of written out of bounds               */
+  int32_t*       main_pos_d;     /* [B] position id the next main-branch token of each sequence takes.
+                                    Required (and kept up to date by aspd_build_branch_meta, from 0 for
+                                    an empty sequence) for ASPD_POS_SAME_MAX and ASPD_POS_FIX_N, where it
+                                    differs from seq_len; may be NULL for ASPD_POS_SAME_SEQ              */
 } aspd_state;
 
 /* What one aspd_build_branch_meta call produces for the NQ tokens it appends (caller-allocated).
@@ -140,7 +152,7 @@ typedef struct aspd_step {
  *   entries and must have main entry 0; a sequence that owns none takes its main entry.  Rows stay
  *   sequence-major; out->cu_new_d [NB+1] holds the first row of every branch, then NQ.  The attention
  *   call for such a step is aspd_attn_parallel_decode or aspd_attn_branch_chunk.
- * pos_mode must be ASPD_POS_SAME_SEQ.  out->NQ must equal the sum of new_len (known to the caller;
+ * pos_mode: one of ASPD_POS_*, the same in every call on a state.  out->NQ must equal the sum of new_len (known to the caller;
  * rows beyond it are dropped and ASPD_FAULT_ROW_COUNT is raised). */
 ASPD_API int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int32_t stage, int32_t pos_mode,
                            const int32_t* new_len_d, aspd_step* out, void* stream);

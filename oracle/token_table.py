@@ -196,8 +196,10 @@ class TokenTable:
             if self.cur_parallel[s]:
                 if self.pos_mode == "same_max":
                     self.next_main_pos[s] = self.stage_start_pos[s] + max(self.tokens_in_branch[s])
-                elif self.fix_n:
+                elif self.fix_n and max(self.tokens_in_branch[s]) > 0:   # a stage that never got a token leaves no trace
                     self.next_main_pos[s] = self.stage_start_pos[s] + len(self.tokens_in_branch[s]) * self.fix_n
+                elif self.fix_n:
+                    pass
                 else:
                     self.next_main_pos[s] = len(self.pos[s])
                 self.cur_parallel[s] = False

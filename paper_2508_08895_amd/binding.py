@@ -18,8 +18,13 @@ LIB_PATH = os.path.join(_HERE, "libaspd.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 F32, BF16 = 0, 1
 STAGE_PARALLEL, STAGE_SERIAL, STAGE_MERGE, STAGE_MIXED = 0, 1, 2, 3
-POS_SAME_SEQ = 0
-FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES, FAULT_STAGE = 1, 2, 4, 8, 16
+POS_SAME_SEQ, POS_SAME_MAX = 0, 1
+
+
+def POS_FIX_N(n: int) -> int:
+    return 2 | (int(n) << 8)
+
+FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES, FAULT_STAGE, FAULT_INTERVAL = 1, 2, 4, 8, 16, 32
 
 EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_rope_append", "aspd_set_max_workgroups",
            "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
@@ -36,7 +41,7 @@ class aspd_kv(C.Structure):
 class aspd_state(C.Structure):
     _fields_ = [("B", C.c_int32), ("NB", C.c_int32), ("stage_base_d", C.c_void_p), ("seq_len_d", C.c_void_p),
                 ("cu_branches_d", C.c_void_p), ("branch_len_d", C.c_void_p), ("slot_owner_d", C.c_void_p),
-                ("owner_stride", C.c_int32), ("fault_d", C.c_void_p)]
+                ("owner_stride", C.c_int32), ("fault_d", C.c_void_p), ("main_pos_d", C.c_void_p)]
 
 
 class aspd_step(C.Structure):
@@ -133,6 +138,8 @@ class BatchState:
         self.owner_stride = int(owner_stride)
         self.slot_owner = torch.zeros(B, self.owner_stride, dtype=torch.uint8, device=device)
         self.fault = torch.zeros(1, dtype=torch.int32, device=device)
+        self.main_pos = torch.zeros(B, dtype=torch.int32, device=device)
+        self.pos_mode = POS_SAME_SEQ   # the position paradigm every metadata call on this state uses
 
     def open_parallel(self, cu_branches: torch.Tensor) -> None:
         """New parallel stage: branch layout given by the caller, branch lengths start at zero."""
@@ -142,7 +149,8 @@ class BatchState:
 
     def struct(self) -> aspd_state:
         return aspd_state(self.B, self.NB, _ptr(self.stage_base), _ptr(self.seq_len), _ptr(self.cu_branches),
-                          _ptr(self.branch_len), _ptr(self.slot_owner), self.owner_stride, _ptr(self.fault))
+                          _ptr(self.branch_len), _ptr(self.slot_owner), self.owner_stride, _ptr(self.fault),
+                          _ptr(self.main_pos))
 
 
 class Step:
@@ -175,7 +183,7 @@ def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: 
     where new_len, if given, says per sequence whether its stage ends)."""
     kvs, sts = kv.struct(), state.struct()
     if stage == STAGE_MERGE:
-        rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, POS_SAME_SEQ, _ptr(new_len), None,
+        rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, state.pos_mode, _ptr(new_len), None,
                                           _stream(stream))
         if rc != OK:
             raise AspdError(rc, "aspd_build_branch_meta")
@@ -184,7 +192,7 @@ def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: 
         step = Step(NQ, state.B if stage == STAGE_SERIAL else state.NB, state.B, state.device,
                     max_new_per_seq)
     sps = step.struct()
-    rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, POS_SAME_SEQ, _ptr(new_len),
+    rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, state.pos_mode, _ptr(new_len),
                                       C.byref(sps), _stream(stream))
     if rc != OK:
         raise AspdError(rc, "aspd_build_branch_meta")

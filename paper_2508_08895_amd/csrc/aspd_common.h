@@ -31,6 +31,7 @@ struct StateView {
   uint8_t*       slot_owner;
   int32_t        owner_stride;
   int32_t*       fault;
+  int32_t*       main_pos;
 };
 
 struct StepView {
@@ -52,7 +53,7 @@ static inline KvView make_view(const aspd_kv* kv) {
 }
 static inline StateView make_view(const aspd_state* st) {
   return StateView{st->B, st->NB, st->stage_base_d, st->seq_len_d, st->cu_branches_d, st->branch_len_d,
-                   st->slot_owner_d, st->owner_stride, st->fault_d};
+                   st->slot_owner_d, st->owner_stride, st->fault_d, st->main_pos_d};
 }
 static inline StepView make_view(const aspd_step* sp) {
   return StepView{sp->NQ, sp->max_new_per_seq, sp->cu_new_d, sp->cu_seq_new_d, sp->q_seq_d, sp->q_branch_d, sp->position_ids_d,

@@ -38,9 +38,13 @@ __device__ __forceinline__ void raise_fault(int32_t* fault, int bits) {
 // MIXED: main_len[B] as well.  Sequences switch between serial and parallel decoding independently
 // (Sec. 3.3), so one call may serve sequences with open branches (their branch entries of new_len)
 // and sequences without (their entry of main_len: main-branch tokens, Eq. 4 first case).
+// Position paradigms (Sec. 4.5.3): under Same-Seq the main branch's position counter is the token count
+// and needs no storage; under Same-Max and fixed intervals it lives in st.main_pos.  `fix_n` > 0
+// selects fixed intervals of that many positions per branch.
 __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, StateView st, StepView sp,
                                                                      const int32_t* __restrict__ new_len,
-                                                                     const int32_t* __restrict__ main_len) {
+                                                                     const int32_t* __restrict__ main_len,
+                                                                     bool same_seq, int fix_n) {
   __shared__ int red[META_THREADS / 64];
   __shared__ int off[ASPD_MAX_BRANCHES_PER_SEQ + 2];  // exclusive scan of this sequence's new_len
   __shared__ int held[ASPD_MAX_BRANCHES_PER_SEQ + 1]; // tokens each branch already holds
@@ -50,6 +54,9 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
   const int b1 = st.cu_branches[s + 1];
   const int L = st.stage_base[s];  // state is read here, ahead of the barriers below, and
   const int T = st.seq_len[s];     // written only after the last of them
+  // position the next main-branch token takes = position of the first token of every branch of a
+  // stage that opens now (stage_start of Eq. 4); it does not move while the stage runs
+  const int P = same_seq ? L : st.main_pos[s];
   int K = b1 - b0;
   if (K > ASPD_MAX_BRANCHES_PER_SEQ) {
     if (tid == 0) raise_fault(st.fault, ASPD_FAULT_BRANCHES);
@@ -85,7 +92,7 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
       if (blk < 0 || blk >= kv.num_blocks) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE);
       sp.q_seq[row] = s;
       sp.q_branch[row] = -1;
-      sp.position_ids[row] = slot;
+      sp.position_ids[row] = (same_seq ? T : P) + idx;
       sp.logical_slot[row] = slot;
       sp.slot_mapping[row] = (int64_t)blk * ASPD_BLOCK + slot % ASPD_BLOCK;
       sp.kv_len[row] = slot + 1;
@@ -93,6 +100,7 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
     if (tid == 0) {  // T and L were read before any barrier; nobody else touches this sequence
       st.seq_len[s] = T + c_main;
       st.stage_base[s] = T + c_main;
+      if (st.main_pos) st.main_pos[s] = (same_seq ? T : P) + c_main;
     }
     return;
   }
@@ -138,6 +146,10 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
   if ((long)T + total > cap_slots) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE); }
   if ((long)T + total > st.owner_stride) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_OWNER_ROW); }
   if (base + total > sp.NQ) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_ROW_COUNT); }
+  if (fix_n > 0 && __syncthreads_or(tid < K && held[tid] + c_mine > fix_n)) {
+    ok = false;
+    if (tid == 0) raise_fault(st.fault, ASPD_FAULT_INTERVAL);
+  }
   if (!ok) return;  // the sequence is left as it was
 
   for (int idx = tid; idx < total; idx += META_THREADS) {
@@ -155,7 +167,7 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
     if (blk < 0 || blk >= kv.num_blocks) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE);
     sp.q_seq[row] = s;
     sp.q_branch[row] = b0 + k;
-    sp.position_ids[row] = L + t;
+    sp.position_ids[row] = P + k * fix_n + t;
     sp.logical_slot[row] = slot;
     sp.slot_mapping[row] = (int64_t)blk * ASPD_BLOCK + slot % ASPD_BLOCK;
     sp.kv_len[row] = L + t + 1;  // shared prefix + own branch up to and including itself
@@ -170,7 +182,7 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
 // SERIAL stage: new_len[B].  A main-branch token's position is the number of tokens decoded before
 // it, all branches of all earlier stages included (Eq. 4, first case): its flattened index.
 __global__ __launch_bounds__(META_THREADS) void meta_serial_kernel(KvView kv, StateView st, StepView sp,
-                                                                   const int32_t* __restrict__ new_len) {
+                                                                   const int32_t* __restrict__ new_len, bool same_seq) {
   __shared__ int red[META_THREADS / 64];
   const int s = blockIdx.x;
   const int tid = threadIdx.x;
@@ -179,6 +191,7 @@ __global__ __launch_bounds__(META_THREADS) void meta_serial_kernel(KvView kv, St
   const int base = block_sum(part, red);
   const int c = new_len[s];
   const int T = st.seq_len[s];
+  const int P = same_seq ? T : st.main_pos[s];
   if (tid == 0) {
     sp.cu_new[s] = base;
     sp.cu_seq_new[s] = base;
@@ -198,7 +211,7 @@ __global__ __launch_bounds__(META_THREADS) void meta_serial_kernel(KvView kv, St
     if (blk < 0 || blk >= kv.num_blocks) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE);
     sp.q_seq[row] = s;
     sp.q_branch[row] = -1;
-    sp.position_ids[row] = slot;
+    sp.position_ids[row] = P + idx;
     sp.logical_slot[row] = slot;
     sp.slot_mapping[row] = (int64_t)blk * ASPD_BLOCK + slot % ASPD_BLOCK;
     sp.kv_len[row] = slot + 1;
@@ -207,14 +220,29 @@ __global__ __launch_bounds__(META_THREADS) void meta_serial_kernel(KvView kv, St
   if (tid == 0) {
     st.seq_len[s] = T + c;
     st.stage_base[s] = T + c;  // a serial sequence has no branch region
+    if (st.main_pos) st.main_pos[s] = P + c;
   }
 }
 
 // MERGE: the parallel stage ends.  Everything decoded so far becomes visible to all later queries;
 // the cache is reused as it is (Sec. 3.3: no re-prefill when switching back).
-__global__ void meta_merge_kernel(StateView st, const int32_t* __restrict__ which /* null: every sequence */) {
+__global__ void meta_merge_kernel(StateView st, const int32_t* __restrict__ which /* null: every sequence */,
+                                  bool same_seq, int fix_n) {
   const int s = blockIdx.x * blockDim.x + threadIdx.x;
-  if (s < st.B && (!which || which[s] != 0)) st.stage_base[s] = st.seq_len[s];
+  if (s >= st.B || (which && which[s] == 0)) return;
+  const int T = st.seq_len[s];
+  const bool running = st.stage_base[s] < T;
+  st.stage_base[s] = T;
+  if (!st.main_pos) return;
+  // where the main branch continues (Sec. 4.5.3)
+  if (same_seq) {
+    st.main_pos[s] = T;
+  } else if (running && st.cu_branches) {
+    const int b0 = st.cu_branches[s], K = st.cu_branches[s + 1] - b0;
+    int longest = 0;
+    for (int k = 0; k < K; ++k) longest = max(longest, st.branch_len[b0 + k]);
+    st.main_pos[s] += fix_n > 0 ? K * fix_n : longest;
+  }
 }
 
 // Branch numbering changes when sequences open or end stages at different times: the tokens held by
@@ -253,12 +281,16 @@ extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int3
   if (rc != ASPD_OK) return rc;
   if (!state || state->B <= 0 || !state->stage_base_d || !state->seq_len_d) return ASPD_ERR_INVALID_ARG;
   if (state->B > ASPD_MAX_BATCH) return ASPD_ERR_UNSUPPORTED;
-  if (pos_mode != ASPD_POS_SAME_SEQ) return ASPD_ERR_UNSUPPORTED;
+  const bool same_seq = pos_mode == ASPD_POS_SAME_SEQ;
+  const int fix_n = (pos_mode & 0xff) == 2 ? (pos_mode >> 8) : 0;
+  if (!same_seq && pos_mode != ASPD_POS_SAME_MAX && fix_n <= 0) return ASPD_ERR_UNSUPPORTED;
+  if (!same_seq && !state->main_pos_d) return ASPD_ERR_INVALID_ARG;
   hipStream_t hs = (hipStream_t)stream;
   StateView sv = make_view(state);
 
   if (stage == ASPD_STAGE_MERGE) {
-    hipLaunchKernelGGL(meta_merge_kernel, dim3((state->B + 255) / 256), dim3(256), 0, hs, sv, new_len_d);
+    hipLaunchKernelGGL(meta_merge_kernel, dim3((state->B + 255) / 256), dim3(256), 0, hs, sv, new_len_d, same_seq,
+                       fix_n);
     ASPD_HIP_CHECK(hipGetLastError());
     return ASPD_OK;
   }
@@ -277,9 +309,10 @@ extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int3
       return ASPD_ERR_INVALID_ARG;
     const int32_t* main_len_d = stage == ASPD_STAGE_MIXED ? new_len_d + state->NB : nullptr;
     hipLaunchKernelGGL(meta_parallel_kernel, dim3(state->B), dim3(META_THREADS), 0, hs, kvv, sv, spv, new_len_d,
-                       main_len_d);
+                       main_len_d, same_seq, fix_n);
   } else {
-    hipLaunchKernelGGL(meta_serial_kernel, dim3(state->B), dim3(META_THREADS), 0, hs, kvv, sv, spv, new_len_d);
+    hipLaunchKernelGGL(meta_serial_kernel, dim3(state->B), dim3(META_THREADS), 0, hs, kvv, sv, spv, new_len_d,
+                       same_seq);
   }
   ASPD_HIP_CHECK(hipGetLastError());
   return ASPD_OK;

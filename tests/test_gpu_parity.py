@@ -338,6 +338,83 @@ def test_rope_append_then_attention(A, seed, dtype, theta):
         assert err <= tol
 
 
+# --------------------------------------------------------------------------------------------- position paradigms
+@pytest.mark.parametrize("mode", ["same_max", ("fix", 48)])
+def test_position_paradigms_of_the_ablation(A, mode):
+    """Same-Max and fixed-interval position ids (Sec. 4.5.3) through all metadata stages, over two
+    rounds of parallel decoding with sequences switching independently: position ids and every other
+    output bit-exact against the oracle run in the same paradigm; attention is the same as ever."""
+    from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
+    seed = 71
+    rng = np.random.default_rng(seed)
+    wl = W.random_small(seed=seed, dtype="bf16", head_dim=128, num_q_heads=8, num_kv_heads=4, batch=5,
+                        prefix_range=(5, 120), branches_range=(4, 4), branch_len_range=(40, 40))
+    gb = GpuBatch(wl)
+    gb.state.pos_mode = A.POS_SAME_MAX if mode == "same_max" else A.POS_FIX_N(mode[1])
+    tt = TokenTable(wl.block_tables, wl.block_size, pos_mode=mode)
+    meta = tt.append_serial(wl.prefix_len)
+    step = gb.serial(wl.prefix_len)
+    assert_step_equal(step, meta)
+    B = wl.B
+    K = [0] * B
+    held = [0] * B                                # tokens in the longest branch of the running stage
+    budget = [4 * 40 - 8] * B
+    for it in range(14):
+        ending = [K[s] > 0 and held[s] > 0 and rng.random() < 0.3 for s in range(B)]
+        if any(ending):
+            tt.merge(ending)
+            gb.merge(ending)
+            for s in range(B):
+                if ending[s]:
+                    K[s], held[s] = 0, 0
+        opening = [K[s] == 0 and rng.random() < 0.5 for s in range(B)]
+        if any(ending) or any(opening):
+            for s in range(B):
+                if opening[s]:
+                    K[s] = int(rng.integers(1, 5))
+            tt.open_parallel(K)
+            gb.renumber(K)
+        nb, nm = [], []
+        for s in range(B):
+            if K[s]:
+                n = rng.integers(0, 4, size=K[s])
+                if n.sum() > budget[s] or held[s] + 3 > 40:
+                    n[:] = 0
+                nb.append(n)
+                nm.append(0)
+                held[s] += int(n.max()) if n.size else 0
+            else:
+                nb.append(np.zeros(0, dtype=np.int64))
+                nm.append(int(rng.integers(0, 3)) if budget[s] > 4 else 0)
+            budget[s] -= int(nb[-1].sum()) + nm[-1]
+        nbv = np.concatenate(nb)
+        if nbv.sum() + sum(nm) == 0:
+            continue
+        meta = tt.append_mixed(nbv, nm)
+        step = gb.mixed(nbv, nm)
+        assert_step_equal(step, meta)
+        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label=f"{mode} call {it}")
+        assert_state_equal(gb, tt)
+        assert np.array_equal(gb.state.main_pos.cpu().numpy(), np.array(tt.next_main_pos, dtype=np.int32))
+    assert gb.fault() == 0
+
+
+def test_fixed_interval_overflow_is_refused(A):
+    from gpu_drive import GpuBatch
+    wl = W.random_small(seed=72, dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=4, batch=1,
+                        branches_range=(2, 2), branch_len_range=(20, 20))
+    gb = GpuBatch(wl)
+    gb.state.pos_mode = A.POS_FIX_N(4)
+    gb.serial(wl.prefix_len)
+    gb.renumber([2])
+    gb.parallel(np.array([3, 4], dtype=np.int32))
+    assert gb.fault() == 0
+    before = gb.state.seq_len.cpu().numpy().copy()
+    gb.parallel(np.array([2, 0], dtype=np.int32))          # branch 0 would hold 5 > 4 positions
+    assert gb.fault() & A.FAULT_INTERVAL
+    assert np.array_equal(gb.state.seq_len.cpu().numpy(), before)
+
+
 # --------------------------------------------------------------------------------------------- many sequences
 def test_large_batch_decode_and_serial(A):
     """More sequences than a wave has lanes (the schedule's search over sequences takes its other path)

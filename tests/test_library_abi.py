@@ -101,6 +101,9 @@ def test_bad_state_and_step_are_rejected_before_launch():
     assert meta(sp_over=dict(kv_len_d=None)) == A.ERR_INVALID_ARG
     assert meta(stage=9) == A.ERR_INVALID_ARG
     assert meta(pos=3) == A.ERR_UNSUPPORTED
+    assert meta(pos=A.POS_SAME_MAX) == A.ERR_INVALID_ARG                     # needs state.main_pos_d
+    assert meta(pos=A.POS_FIX_N(32), st_over=dict(main_pos_d=None)) == A.ERR_INVALID_ARG
+    assert meta(pos=2) == A.ERR_UNSUPPORTED                                  # fixed intervals of 0 positions
     assert meta(new_len=None) == A.ERR_INVALID_ARG
 
     def attn(st_over=None, sp_over=None, q=0x100, out=0x200, ws=0x300, ws_bytes=1 << 30, scale=0.0,
