@@ -51,7 +51,7 @@ constexpr int BF16_ROWS = 16 * NT_MAX;
 constexpr int F32_ROWS = 4;           // rows per row group (fp32 vector path)
 constexpr int MIN_PAGES_PER_WG = 16;  // do not split finer than this
 #ifndef ASPD_TUNE_PAD
-#define ASPD_TUNE_PAD 24
+#define ASPD_TUNE_PAD 32
 #endif
 constexpr int PAD_STREAM = ASPD_TUNE_PAD;  // virtual units per item start, bandwidth-bound kernel at D = 128
 constexpr int PAD_COMPUTE = 8;             // the same for the compute-bound kernels
@@ -1592,7 +1592,7 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   a.qpg = qpg;
   a.rows_cap = rows_cap;
   // A segment's fixed cost (start-up, reduction across waves, partial, merge) in units of the time one
-  // more page takes its workgroup: measured at about 10 us against 0.4 us per 8 KB page when streaming,
+  // more page takes its workgroup: measured at about 12 us against 0.4 us per 8 KB page when streaming,
   // and against 0.9 us per page in the compute-bound kernels.
   if (by_rows || kv->dtype != ASPD_BF16) a.pad = PAD_COMPUTE;
   else a.pad = PAD_STREAM * 128 / kv->head_dim;
