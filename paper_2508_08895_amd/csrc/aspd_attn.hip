@@ -1,7 +1,8 @@
 // Branch-isolated attention over a paged KV cache for gfx950 (ASPD Sec. 3.2 Eq. 1-3, Sec. 3.3).
 //
-// One streaming kernel serves the three attention entry points.  A query row q of sequence s sees
-// key slot j iff
+// The three attention entry points share one rule, one schedule and one way of combining partial
+// results; two bf16 kernels (one that streams keys past few rows, one that splits many rows among its
+// waves) and an fp32 kernel apply it.  A query row q of sequence s sees key slot j iff
 //     j <= slot(q)  and  ( j < stage_base[s]  or  tag(q) == 0  or  slot_owner[s][j] == tag(q) )
 // with tag(q) = 0 for a main-branch token and the 1-based branch number otherwise.  This is Eq. 2-3
 // in cache terms: slots below stage_base belong to earlier stages (visible to all), slots above it to
@@ -958,10 +959,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
 
 // ---------------------------------------------------------------------------------------------
 // bf16, many rows per KV head (branch chunks): the waves of a workgroup split the ROWS instead of
-// the keys.  Every pair of pages is loaded once per workgroup, cooperatively, into a double-buffered
-// LDS stage that all waves read; each wave keeps its own 16*NT rows (Q operands, accumulators,
-// softmax state, all in registers) for the whole segment, so there is no reduction across waves.
-// One barrier per pair.  With NW waves a row group holds NW * 16 * NT rows, and the pages of a KV head
+// the keys.  Every group of ROWS_PPS pairs of pages is loaded once per workgroup, cooperatively, into a
+// double-buffered LDS stage that all waves read; each wave keeps its own 16*NT rows (Q operands,
+// accumulators, softmax state, all in registers) for the whole segment, so there is no reduction
+// across waves.  One barrier per group.  With NW waves a row group holds NW * 16 * NT rows, and the pages of a KV head
 // are fetched once per that many rows.  The product per pair is compute-bound here (rows x 32 keys x
 // D on the MFMA units, the softmax on the vector ALU, the operands out of LDS), which is why the
 // waves share the loads rather than the keys.  Measured: 8 waves of 32 rows beat 8 of 48 (whose Q
