@@ -99,7 +99,7 @@ struct AttnArgs {
   const void*    q;
   void*          out;
   float*         lse;
-  float*         partial;       // [2 * nwg][rows_per_group][D + 4]: accumulator, running max, sum, pad
+  float*         partial;       // [2 * nwg] slots of {[rows_per_group][D] accumulators, [rows_per_group][4]: reference, sum, pad}
   int*           counters;      // [nwg] arrivals per split item, zero between calls
   float          scale_log2;    // sm_scale * log2(e)
   int            B;
@@ -390,6 +390,13 @@ __device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item&
 __device__ __forceinline__ float* partial_slot(const AttnArgs& a, int wg, int starts_item, int D) {
   return a.partial + ((long)(2 * wg + starts_item)) * a.rows_cap * (D + 4);
 }
+// Inside a slot the accumulator rows come first, D floats each and nothing between them, so that rows
+// start on 64-byte lines and the lanes of one store fill whole lines (a partly written line costs a
+// full line of write traffic); the softmax statistics of all rows follow, 16 bytes per row.
+__device__ __forceinline__ float* partial_acc(float* slot, int r, int D) { return slot + (long)r * D; }
+__device__ __forceinline__ float* partial_stat(const AttnArgs& a, float* slot, int r, int D) {
+  return slot + (long)a.rows_cap * D + 4 * r;
+}
 
 __device__ __forceinline__ float exp2_safe_ref(float m) { return (m == -INFINITY) ? 0.f : m; }
 
@@ -402,18 +409,13 @@ __device__ __forceinline__ void store_device_scope(float* p, float v) {
 __device__ __forceinline__ float load_device_scope(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// The same write-through store, 16 or 8 bytes wide (4-byte write-through stores cost a partial-line
+// The same write-through store, 16 bytes wide (narrow write-through stores cost a partial-line
 // write each).  Callers order it like the 4-byte form: a later s_waitcnt vmcnt(0) covers it.
 // A store of more than 8 bytes reads its data registers a little after it issues, and the compiler, which
 // does not look inside inline assembly, may let the very next instruction overwrite them: the s_nop keeps
 // the wait states the compiler would have inserted for a store of its own.
 __device__ __forceinline__ void store_device_scope_x4(float* p, f32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
-}
-__device__ __forceinline__ void store_device_scope_x2(float* p, float a, float b) {
-  typedef __attribute__((ext_vector_type(2))) float f32x2;
-  const f32x2 v = {a, b};
-  asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -879,46 +881,56 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     }
     __syncthreads();
     {
-      constexpr int PER = 16 * D / THREADS;  // consecutive floats per thread
-      const int row = tid / (D / PER);
-      const int d0 = (tid % (D / PER)) * PER;
-      const int r = 16 * n + row;
-      float mg = -INFINITY;
+      // Consecutive lanes take consecutive 16-byte chunks of the tile: every store fills whole lines.
+      constexpr int CPR = D / 4;  // chunks per row
+      constexpr int PASSES = (16 * CPR + THREADS - 1) / THREADS;
+      auto row_stats = [&](int r, float* mg_out, float* lg_out) {
+        float mg = -INFINITY;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) mg = fmaxf(mg, wm[w * ROWS + r]);
-      const float mref = exp2_safe_ref(mg);
-      float lg = 0.f;
+        for (int w = 0; w < NW; ++w) mg = fmaxf(mg, wm[w * ROWS + r]);
+        const float mref = exp2_safe_ref(mg);
+        float lg = 0.f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) lg += wl[w * ROWS + r] * __builtin_amdgcn_exp2f(wm[w * ROWS + r] - mref);
-      float o[PER];
+        for (int w = 0; w < NW; ++w) lg += wl[w * ROWS + r] * __builtin_amdgcn_exp2f(wm[w * ROWS + r] - mref);
+        *mg_out = mg;
+        *lg_out = lg;
+      };
+      // The index arithmetic below (divisions by G among it) depends on nothing the main loop produces;
+      // tying it to a value defined here keeps it, and the registers it needs, out of that loop.
+      int tid_here = tid;
+      asm volatile("" : "+v"(tid_here)::"memory");
 #pragma unroll
-      for (int e = 0; e < PER; ++e) {
-        o[e] = 0.f;
+      for (int k = 0; k < PASSES; ++k) {
+        const int ci = tid_here + k * THREADS;
+        if ((16 * CPR) % THREADS != 0 && ci >= 16 * CPR) break;
+        const int row = ci / CPR;
+        const int d0 = 4 * (ci % CPR);
+        const int r = 16 * n + row;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int w = 0; w < NW; ++w) o[e] += red[(w * 16 + row) * RS + d0 + e];
-      }
-      if (r < R) {
+        for (int w = 0; w < NW; ++w) o += *(const f32x4*)&red[(w * 16 + row) * RS + d0];
+        if (r >= R) continue;
         if (complete) {
+          float mg, lg;
+          row_stats(r, &mg, &lg);
           const int q = it.q0 + r / a.G;
           const int head = it.h * a.G + r % a.G;
           const float inv = 1.f / lg;
           __bf16* dst = (__bf16*)a.out + ((long)q * a.kv.num_q_heads + head) * D + d0;
-          typedef __attribute__((ext_vector_type(PER))) __bf16 out_vec;
+          typedef __attribute__((ext_vector_type(4))) __bf16 out_vec;
           out_vec ov;
 #pragma unroll
-          for (int e = 0; e < PER; ++e) ov[e] = (__bf16)(o[e] * inv);
+          for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(o[e] * inv);
           *(out_vec*)dst = ov;
           if (a.lse && d0 == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (mg + log2f(lg)) * LN2;
         } else {
-          float* dst = pslot + (long)r * (D + 4);
-          if constexpr (PER == 4) {
-            store_device_scope_x4(dst + d0, f32x4{o[0], o[1], o[2], o[3]});
-          } else {
-#pragma unroll
-            for (int e = 0; e < PER; e += 2) store_device_scope_x2(dst + d0 + e, o[e], o[e + 1]);
-          }
-          if (d0 == 0) store_device_scope_x2(dst + D, mg, lg);
+          store_device_scope_x4(partial_acc(pslot, r, D) + d0, o);
         }
+      }
+      if (!complete && tid_here < 16 && 16 * n + tid_here < R) {
+        float mg, lg;
+        row_stats(16 * n + tid_here, &mg, &lg);
+        store_device_scope_x4(partial_stat(a, pslot, 16 * n + tid_here, D), f32x4{mg, lg, 0.f, 0.f});
       }
     }
     __syncthreads();
@@ -1176,10 +1188,10 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
       }
       if (a.lse && g == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (ts.m_run[n] + log2f(ts.l_run[n])) * LN2;
     } else {
-      float* dst = pslot + (long)r * (D + 4);
+      float* dst = partial_acc(pslot, r, D);
 #pragma unroll
       for (int mt = 0; mt < C::MT; ++mt) store_device_scope_x4(dst + 16 * mt + 4 * g, ts.acc[n][mt]);
-      if (g == 0) store_device_scope_x2(dst + D, ts.m_run[n], ts.l_run[n]);
+      if (g == 0) store_device_scope_x4(partial_stat(a, pslot, r, D), f32x4{ts.m_run[n], ts.l_run[n], 0.f, 0.f});
     }
   }
 }
@@ -1259,6 +1271,9 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
   const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
 
   for (int P = page0 + wave; P < page1; P += NW) {
+    // The query rows are re-read from LDS for every page: kept in registers across the loop (4 rows x
+    // D / 4 values per lane) they would not fit beside the accumulators.
+    asm volatile("" ::: "memory");
     int blk = __builtin_amdgcn_readfirstlane(a.kv.block_tables[bt_base + P]);
     blk = min(max(blk, 0), a.kv.num_blocks - 1);
     const long off = (((long)blk * a.kv.num_kv_heads + it.h) * ASPD_BLOCK + k) * D + g * QD;
@@ -1281,15 +1296,17 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
       s += __shfl_xor(s, 32);
       s *= a.scale_log2;
       const bool vis = (j <= rowslot[r]) && (j < L || rowtag[r] == 0 || own == rowtag[r]);
-      if (vis) {  // lanes of one key agree on vis and on s, so their statistics stay identical
-        const float m_new = fmaxf(m_run[r], s);
-        const float alpha = exp2f(m_run[r] - m_new);
-        const float p = exp2f(s - m_new);
-        m_run[r] = m_new;
-        l_run[r] = l_run[r] * alpha + p;
+      // No branch on vis (an invisible key enters with weight zero): the lanes of one key agree on vis
+      // and on s, so their statistics stay identical, and the whole update runs with all lanes active.
+      const float sv = vis ? s : -INFINITY;
+      const float m_new = fmaxf(m_run[r], sv);
+      const float mref = exp2_safe_ref(m_new);
+      const float alpha = exp2f(m_run[r] - mref);
+      const float p = exp2f(sv - mref);
+      m_run[r] = m_new;
+      l_run[r] = l_run[r] * alpha + p;
 #pragma unroll
-        for (int e = 0; e < QD; ++e) acc[r][e] = fmaf(p, kv_v[e], acc[r][e] * alpha);
-      }
+      for (int e = 0; e < QD; ++e) acc[r][e] = fmaf(p, kv_v[e], acc[r][e] * alpha);
     }
   }
 
@@ -1327,11 +1344,11 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
         ((float*)a.out)[((long)q * a.kv.num_q_heads + head) * D + d] = o / lg;
         if (a.lse && d == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (mg + log2f(lg)) * LN2;
       } else {
-        float* dst = pslot + (long)r * (D + 4);
-        store_device_scope(dst + d, o);
+        store_device_scope(partial_acc(pslot, r, D) + d, o);
         if (d == 0) {
-          store_device_scope(dst + D, mg);
-          store_device_scope(dst + D + 1, lg);
+          float* stat = partial_stat(a, pslot, r, D);
+          store_device_scope(stat, mg);
+          store_device_scope(stat + 1, lg);
         }
       }
     }
@@ -1360,7 +1377,8 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_f32<D>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
-    if (!complete) announce_partial<D, false, THREADS, 2>(a, sc, it, sh, page0, page1, &merge_flag);
+    // F32_ROWS rows of D / 4 chunks never exceed the workgroup's threads: one element per thread
+    if (!complete) announce_partial<D, false, THREADS, 1>(a, sc, it, sh, page0, page1, &merge_flag);
   }
 }
 
@@ -1403,11 +1421,11 @@ __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_l
 #pragma unroll
         for (int k = 0; k < BATCH; ++k) {
           const int ww = owner + min(p0 + k, nparts - 1);
-          const float* p = a.partial + (long)(2 * ww + (ww == owner ? 1 : 0)) * stride + (long)r[x] * (D + 4);
-          const f32x4 ml = *(const f32x4*)(p + D);  // reference, sum, padding
+          const float* slot = a.partial + (long)(2 * ww + (ww == owner ? 1 : 0)) * stride;
+          const f32x4 ml = *(const f32x4*)(slot + (long)a.rows_cap * D + 4 * r[x]);  // reference, sum, padding
           pm[x][k] = ml[0];
           pl[x][k] = ml[1];
-          po[x][k] = *(const f32x4*)(p + 4 * cc[x]);
+          po[x][k] = *(const f32x4*)(slot + (long)r[x] * D + 4 * cc[x]);
         }
       }
 #pragma unroll
