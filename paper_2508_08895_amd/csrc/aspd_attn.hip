@@ -74,7 +74,11 @@ constexpr int ROWS_PREFETCH = ASPD_TUNE_RD;  // groups of pages that kernel keep
 constexpr int ROWS_PPS = ASPD_TUNE_PPS;      // pairs of pages it stages (and computes) between two barriers
 constexpr int MAX_WG_ROWS = 256;      // its largest grid (its partial slots are ROWS_NW * 16 * ROWS_NT rows each)
 constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
+constexpr int RECORD_INTS = 16;       // per workgroup: 16 bytes describing a segment, then two block ids per wave
+constexpr int RECORD_BYTES = 1024 * RECORD_INTS * 4;  // MAX_WG records after the counters
+constexpr int PARTIAL_OFFSET = COUNTER_BYTES + RECORD_BYTES;  // the partial slots follow
 constexpr int MAX_WG = 1024;          // upper bound of the grid (workspace is sized for it)
+static_assert(RECORD_BYTES == MAX_WG * RECORD_INTS * 4 && COUNTER_BYTES == MAX_WG * 4, "workspace head");
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float LAZY = 6.f;           // log2 slack of the running softmax reference (bf16 path)
@@ -101,6 +105,8 @@ struct AttnArgs {
   float*         lse;
   float*         partial;       // [2 * nwg] slots of {[rows_per_group][D] accumulators, [rows_per_group][4]: reference, sum, pad}
   int*           counters;      // [nwg] arrivals per split item, zero between calls
+  int*           records;       // [nwg][RECORD_INTS]: the first segment each workgroup had in the last call
+  int            NQ;            // rows of q / out
   float          scale_log2;    // sm_scale * log2(e)
   int            B;
   int            nwg;
@@ -249,10 +255,35 @@ __device__ int share_begin(const AttnArgs& a, const Sched& sc, const Shares& sh,
   return nominal;
 }
 
+// The per-sequence scalars of the thread's sequences, as loaded (the first memory round trip of a
+// launch; issuing it apart from its use lets a kernel put other loads in flight beside it).
+template <int THREADS>
+struct SeqLoads {
+  static constexpr int PER = (ASPD_MAX_BATCH + THREADS - 1) / THREADS;  // sequences per thread
+  int T[PER], q0[PER], q1[PER], L[PER];
+};
+template <int THREADS>
+__device__ __forceinline__ SeqLoads<THREADS> schedule_issue(const AttnArgs& a) {
+  SeqLoads<THREADS> ld;
+#pragma unroll
+  for (int j = 0; j < SeqLoads<THREADS>::PER; ++j) {
+    const int s = threadIdx.x * SeqLoads<THREADS>::PER + j;
+    ld.T[j] = ld.q0[j] = ld.q1[j] = ld.L[j] = 0;
+    if (s < a.B) {
+      ld.T[j] = a.seq_len[s];
+      ld.q0[j] = a.cu_seq_new[s];
+      ld.q1[j] = a.cu_seq_new[s + 1];
+      ld.L[j] = a.stage_base[s];
+    }
+  }
+  return ld;
+}
+
 // Fills the LDS tables and returns the shares.  All threads of the workgroup call it.
 template <int THREADS>
-__device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratch /* 3 * THREADS / 64 ints */) {
-  constexpr int PER = (ASPD_MAX_BATCH + THREADS - 1) / THREADS;  // sequences per thread
+__device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratch /* 3 * THREADS / 64 ints */,
+                                 const SeqLoads<THREADS>& ld) {
+  constexpr int PER = SeqLoads<THREADS>::PER;
   constexpr int NWV = THREADS / 64;
   const int tid = threadIdx.x;
   int mine_p[PER], mine_i[PER];
@@ -264,11 +295,11 @@ __device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratc
     mine_p[j] = 0;
     mine_i[j] = 0;
     if (s < a.B) {
-      const int T = a.seq_len[s];
-      const int q0 = a.cu_seq_new[s];
-      const int q1 = a.cu_seq_new[s + 1];
+      const int T = ld.T[j];
+      const int q0 = ld.q0[j];
+      const int q1 = ld.q1[j];
       sc.T[s] = T;
-      sc.L[s] = a.stage_base[s];
+      sc.L[s] = ld.L[j];
       sc.q0[s] = q0;
       if (s == a.B - 1) sc.q0[a.B] = q1;
       const int np = min((T + ASPD_BLOCK - 1) / ASPD_BLOCK, a.kv.max_blocks_per_seq);
@@ -339,6 +370,10 @@ __device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratc
   }
   return sh;
 }
+template <int THREADS>
+__device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratch) {
+  return build_schedule<THREADS>(a, sc, scratch, schedule_issue<THREADS>(a));
+}
 
 // The workgroup whose share holds unit u.
 __device__ int share_owner(const AttnArgs& a, const Sched& sc, const Shares& sh, int u) {
@@ -355,6 +390,22 @@ __device__ int share_owner(const AttnArgs& a, const Sched& sc, const Shares& sh,
     if (sc.wgb[mid] <= u) lo = mid; else hi = mid - 1;
   }
   return lo;
+}
+
+// Aligned regime: a workgroup's share is one run of pages of one item, found with one look-up (the
+// same item, and the same cuts, as share_begin gives for w and w + 1).
+__device__ __forceinline__ bool aligned_share(const AttnArgs& a, const Sched& sc, const Shares& sh, int w, Item* out,
+                                              int* page0, int* page1) {
+  int vpage;
+  Item it = locate<true>(a, sc, 0, sh.nominal_begin(w), &vpage);
+  if (w < sh.rnd(it.first_unit)) it = locate<true>(a, sc, 0, it.first_unit - 1, &vpage);
+  else if (w >= sh.rnd(it.first_unit + it.np)) it = locate<true>(a, sc, 0, it.first_unit + it.np, &vpage);
+  const int w0 = sh.rnd(it.first_unit);
+  const int k = sh.rnd(it.first_unit + it.np) - w0;
+  *page0 = item_cut(it, w - w0, k);
+  *page1 = item_cut(it, w + 1 - w0, k);
+  *out = it;
+  return *page1 > *page0;
 }
 
 // One workgroup's walk over its share [*u, end): the next run of real pages, or false at the end.
@@ -653,12 +704,108 @@ __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qt
 #undef ASPD_V_UNIT
 }
 
-constexpr int BLK_WIN = 2048;  // pages of a segment whose block ids are staged in LDS at once
+constexpr int BLK_WIN = 512;   // pages of a segment whose block ids are staged in LDS at once
 
+// What the start-up loads of a segment depend on.
+struct SegDesc {
+  int s, h;          // sequence, KV head
+  int q0, nq;        // first packed query row and number of queries of the row group
+  int page0, page1;  // the segment's pages
+};
+__device__ __forceinline__ bool same_segment(const SegDesc& x, const SegDesc& y) {
+  return x.s == y.s && x.h == y.h && x.q0 == y.q0 && x.nq == y.nq && x.page0 == y.page0 && x.page1 == y.page1;
+}
+
+// The start-up loads of a segment, in registers: block ids of the first window, the Q rows, the row
+// descriptors, and the first pair of pages of every wave (pair `wave` of the segment).
+template <int D, int NT, int NW>
+struct SegLoads {
+  static constexpr int THREADS = NW * 64;
+  static constexpr int BPT = BLK_WIN / THREADS;  // block ids per thread and window
+  static constexpr int QL = (16 * NT * Bf16Cfg<D>::CH + THREADS - 1) / THREADS;  // Q chunks per thread
+  int blkreg[BPT];
+  u32x4 qreg[QL];
+  int d_slot, d_branch, first_branch;  // of the thread's row: logical slot, global branch; the sequence's first branch
+  int b0, b1;                          // block ids of the wave's first pair, as loaded from the block table
+  int used0, used1;                    // the block ids `first` was fetched with
+  PairRegs<D> first;
+};
+
+// Segment start-up, part one: the loads.  Three dependent memory round trips are needed at least
+// (lengths -> block ids -> pages); the Q rows and row descriptors are fetched alongside the block ids,
+// and each wave fetches the two block ids of its first pair itself, so that the pages are on their way
+// before anything passes through LDS.  Touches no LDS; every address stays in bounds for any `d` with
+// 0 <= s < B, 0 <= h < KV heads, 0 <= q0, 1 <= nq, q0 + nq <= NQ, 0 <= page0 < page1 <= max blocks.
+template <int D, int NT, int NW>
+__device__ __forceinline__ void segment_issue_ids(const AttnArgs& a, const SegDesc& d, SegLoads<D, NT, NW>& ld) {
+  using C = Bf16Cfg<D>;
+  using LD = SegLoads<D, NT, NW>;
+  constexpr int ROWS = 16 * NT;
+  constexpr int THREADS = NW * 64;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 4;
+  const int R = d.nq * a.G;
+  const int* bt = a.kv.block_tables + (long)d.s * a.kv.max_blocks_per_seq;
+  const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)d.s * a.owner_stride : nullptr;
+  // The wave's own first pair: the same two addresses in every lane.  A wave past the end of a short
+  // segment fetches the last page again (and never uses it) rather than branch: with the same loads in
+  // flight on every path, the compiler's wait counts stay exact.
+  const int P0 = min(d.page0 + 2 * wave, d.page1 - 1);
+  ld.b0 = bt[P0];
+  ld.b1 = bt[min(P0 + 1, d.page1 - 1)];
+  // no load below depends on another, so that all of them are one round trip
+  ld.first_branch = a.cu_branches ? a.cu_branches[d.s] : 0;
+#pragma unroll
+  for (int k = 0; k < LD::BPT; ++k) {
+    const int P = min(d.page0 + tid + k * THREADS, d.page1 - 1);
+    ld.blkreg[k] = bt[P];
+  }
+#pragma unroll
+  for (int k = 0; k < LD::QL; ++k) {
+    const int i = tid + k * THREADS;
+    if (i < ROWS * C::CH) {
+      const int r = i / C::CH, ch = i - r * C::CH;
+      const int rr = min(r, R - 1);
+      const int q = d.q0 + rr / a.G;
+      const int head = d.h * a.G + rr % a.G;
+      ld.qreg[k] = *((const u32x4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + ch);
+    }
+  }
+  ld.d_slot = 0;
+  ld.d_branch = -1;
+  if (tid < ROWS) {
+    const int rr = min(tid, R - 1);
+    const int q = d.q0 + rr / a.G;
+    ld.d_slot = a.logical_slot[q];
+    ld.d_branch = a.q_branch[q];
+  }
+  // owner tags travel with the pair whenever the call has any (the rows that need them are not known yet)
+  ld.first.own[0] = ld.first.own[1] = 0;
+  if (owner_row) {
+    const uint8_t* own_p0 = owner_row + P0 * ASPD_BLOCK + 4 * g;
+    const int own_step = min(ASPD_BLOCK, a.owner_stride - 4 - (P0 * ASPD_BLOCK + 4 * g));  // stays inside the owner row
+    ld.first.own[0] = *(const uint32_t*)own_p0;
+    ld.first.own[1] = *(const uint32_t*)(own_p0 + own_step);
+  }
+}
+// ... and, once the two block ids have arrived, the pages of the wave's first pair.
+template <int D, int NT, int NW, bool STREAM>
+__device__ __forceinline__ void segment_issue_pair(const AttnArgs& a, const SegDesc& d, SegLoads<D, NT, NW>& ld) {
+  ld.used0 = min(max(__builtin_amdgcn_readfirstlane(ld.b0), 0), a.kv.num_blocks - 1);
+  ld.used1 = min(max(__builtin_amdgcn_readfirstlane(ld.b1), 0), a.kv.num_blocks - 1);
+  issue_pair<D, STREAM>(ld.first, a, d.h, ld.used0, ld.used1, threadIdx.x & 63, nullptr, 0);
+}
+
+// Segment start-up, part two, the stream and the epilogue.  `ld` holds the loads segment_issue made
+// for this very segment.
 template <int D, int NT, int NW, int PF, bool STREAM>
 __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
-                             bool complete, float* pslot) {
+                             bool complete, float* pslot, const SegLoads<D, NT, NW>& ld,
+                             int* rec_ids /* where to leave the first pairs' block ids, or null */) {
   using C = Bf16Cfg<D>;
+  using LD = SegLoads<D, NT, NW>;
   constexpr int ROWS = 16 * NT;
   constexpr int THREADS = NW * 64;
   const int tid = threadIdx.x;
@@ -677,54 +824,24 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   int* blk_lds = (int*)(wl + NW * ROWS);                                // [BLK_WIN] block ids of the window
   int* pair_counter = blk_lds + BLK_WIN;                                // next pair nobody has taken yet
 
-  // ---- segment start-up.  Three dependent memory round trips are needed at least (lengths ->
-  // block ids -> pages); the Q rows and row descriptors are fetched alongside the block ids.
   const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
   const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
-  constexpr int BPT = BLK_WIN / THREADS;  // block ids per thread and window
-  int blkreg[BPT];
-#pragma unroll
-  for (int k = 0; k < BPT; ++k) {
-    const int P = min(page0 + tid + k * THREADS, page1 - 1);
-    blkreg[k] = bt[P];
-  }
-  constexpr int QL = (ROWS * C::CH + THREADS - 1) / THREADS;  // Q chunks per thread (padding rows repeat the last row)
-  u32x4 qreg[QL];
-#pragma unroll
-  for (int k = 0; k < QL; ++k) {
-    const int i = tid + k * THREADS;
-    if (i < ROWS * C::CH) {
-      const int r = i / C::CH, ch = i - r * C::CH;
-      const int rr = min(r, R - 1);
-      const int q = it.q0 + rr / a.G;
-      const int head = it.h * a.G + rr % a.G;
-      qreg[k] = *((const u32x4*)a.q + ((long)q * a.kv.num_q_heads + head) * C::CH + ch);
-    }
-  }
-  int d_slot = 0, d_tag = 0;
-  if (tid < ROWS) {
-    const int rr = min(tid, R - 1);
-    const int q = it.q0 + rr / a.G;
-    d_slot = a.logical_slot[q];
-    const int qb = a.q_branch[q];
-    d_tag = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
-  }
 
   __syncthreads();  // LDS of the previous segment is free
 #pragma unroll
-  for (int k = 0; k < BPT; ++k) blk_lds[tid + k * THREADS] = min(max(blkreg[k], 0), a.kv.num_blocks - 1);
-  if (tid == 0) *pair_counter = 0;
+  for (int k = 0; k < LD::BPT; ++k) blk_lds[tid + k * THREADS] = min(max(ld.blkreg[k], 0), a.kv.num_blocks - 1);
+  if (tid == 0) *pair_counter = NW;  // pairs 0 .. NW - 1 of the first window are on their way already
 #pragma unroll
-  for (int k = 0; k < QL; ++k) {
+  for (int k = 0; k < LD::QL; ++k) {
     const int i = tid + k * THREADS;
     if (i < ROWS * C::CH) {
       const int r = i / C::CH, ch = i - r * C::CH;
-      qtile[lds_pos<D>(r, ch)] = qreg[k];
+      qtile[lds_pos<D>(r, ch)] = ld.qreg[k];
     }
   }
   if (tid < ROWS) {
-    rowslot[tid] = d_slot;
-    rowtag[tid] = d_tag;
+    rowslot[tid] = ld.d_slot;
+    rowtag[tid] = (ld.d_branch < 0 || !a.cu_branches) ? 0 : ld.d_branch - ld.first_branch + 1;
   }
   __syncthreads();
 
@@ -783,7 +900,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     if (wbase != page0) {
       __syncthreads();  // every wave is done with the previous window's ids and counter
 #pragma unroll
-      for (int k = 0; k < BPT; ++k) {
+      for (int k = 0; k < LD::BPT; ++k) {
         const int P = min(wbase + tid + k * THREADS, page1 - 1);
         blk_lds[tid + k * THREADS] = min(max(bt[P], 0), a.kv.num_blocks - 1);
       }
@@ -797,6 +914,20 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
     };
 #pragma unroll
     for (int sl = 0; sl < PF; ++sl) {
+      if (sl == 0 && wbase == page0) {  // fetched at start-up
+        idx[0] = wave;
+        pr[0] = ld.first;
+        // ... with block ids that may have come from the last launch's record: fetched again if the
+        // block table has changed since
+        const int a0 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * wave, wpages - 1)]);
+        const int a1 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * wave + 1, wpages - 1)]);
+        if (a0 != ld.used0 || a1 != ld.used1) issue_pair<D, STREAM>(pr[0], a, it.h, a0, a1, lane, nullptr, 0);
+        if (rec_ids && lane == 0) {
+          rec_ids[2 * wave] = a0;
+          rec_ids[2 * wave + 1] = a1;
+        }
+        continue;
+      }
       idx[sl] = take();
       if (idx[sl] < npairs) {
         const int b0 = __builtin_amdgcn_readfirstlane(blk_lds[2 * idx[sl]]);
@@ -955,15 +1086,79 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
                           (BLK_WIN + 4) * 4);
   int* scratch = (int*)smem;  // the stage area is idle until the first segment
   const Sched sc = sched_at(sched_base, a.B);
-  const Shares sh = build_schedule<THREADS>(a, sc, scratch);
+  const SeqLoads<THREADS> seq = schedule_issue<THREADS>(a);
+  asm volatile("" ::: "memory");  // these loads start here, not where the schedule first uses them
+  // A workgroup's first segment is, launch after launch of a decoding loop, mostly the one it had the
+  // last time (same batch, lengths one token longer).  Each workgroup therefore leaves a record of it
+  // in the workspace, and the next launch starts that segment's loads at once, beside the loads of the
+  // lengths, instead of after the schedule has been worked out from them: two of the three dependent
+  // round trips of a launch overlap.  The schedule is computed as always; loads made for a segment
+  // that turns out not to be the workgroup's first are dropped.  A record only chooses addresses to
+  // read early (checked against the call's bounds first); results never depend on it.
+  constexpr bool GUESS = (NT <= 2);  // three tiles leave no registers to hold the loads meanwhile
+  static_assert(4 + 2 * NW <= RECORD_INTS, "record holds two block ids per wave");
+  SegLoads<D, NT, NW> ld;
+  SegDesc guess = {0, 0, 0, 0, 0, 0};
+  bool guessed = false;
+  int* record = a.records + (long)blockIdx.x * RECORD_INTS;
+  if (GUESS) {
+    // one 16-byte load: sequence (12 bits), KV head (12), queries (8) | first row | first page | end page
+    u32x4 r0 = *(const u32x4*)record;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int rb0 = record[4 + 2 * wave], rb1 = record[5 + 2 * wave];  // block ids of the wave's first pair
+    asm volatile("" : "+v"(r0), "+v"(rb0), "+v"(rb1));  // both loads leave before either is waited for
+    const uint32_t w0 = __builtin_amdgcn_readfirstlane(r0[0]);
+    guess.s = (int)(w0 & 0xfffu);
+    guess.h = (int)((w0 >> 12) & 0xfffu);
+    guess.nq = (int)(w0 >> 24);
+    guess.q0 = (int)__builtin_amdgcn_readfirstlane(r0[1]);
+    guess.page0 = (int)__builtin_amdgcn_readfirstlane(r0[2]);
+    guess.page1 = (int)__builtin_amdgcn_readfirstlane(r0[3]);
+    guessed = guess.s >= 0 && guess.s < a.B && guess.h >= 0 && guess.h < a.kv.num_kv_heads && guess.q0 >= 0 &&
+              guess.nq >= 1 && guess.nq <= a.qpg && guess.q0 <= a.NQ - guess.nq && guess.page0 >= 0 &&
+              guess.page0 < guess.page1 && guess.page1 <= a.kv.max_blocks_per_seq;
+    // (a record that fails the checks is replaced by a segment every call has, so that the loads are
+    // the same on every path, see segment_issue)
+    if (!guessed) guess = SegDesc{0, 0, 0, 1, 0, 1};
+    segment_issue_ids<D, NT, NW>(a, guess, ld);
+    // the pages go with the block ids of the record (any two blocks of the pool are safe to read; the
+    // segment compares them with the block table before it uses the pages)
+    ld.used0 = min(max(__builtin_amdgcn_readfirstlane(rb0), 0), a.kv.num_blocks - 1);
+    ld.used1 = min(max(__builtin_amdgcn_readfirstlane(rb1), 0), a.kv.num_blocks - 1);
+    issue_pair<D, STREAM>(ld.first, a, guess.h, ld.used0, ld.used1, threadIdx.x & 63, nullptr, 0);
+    asm volatile("" ::: "memory");  // and all of these before the schedule is worked out
+  }
+  const Shares sh = build_schedule<THREADS>(a, sc, scratch, seq);
   if ((int)blockIdx.x >= sh.n) return;
-  int u, end, page0, page1;
-  share_range(a, sc, sh, &u, &end);
+  int u = 0, end = 0, page0, page1;
   Item it;
-  while (next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
+  bool pending;
+  if (sh.aligned) {
+    pending = aligned_share(a, sc, sh, blockIdx.x, &it, &page0, &page1);
+  } else {
+    share_range(a, sc, sh, &u, &end);
+    pending = next_segment(a, sc, sh, &u, end, &it, &page0, &page1);
+  }
+  bool first = true;
+  for (; pending; pending = !sh.aligned && next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
+    const SegDesc desc = {it.s, it.h, it.q0, it.nq, page0, page1};
+    const bool hit = GUESS && first && guessed && same_segment(desc, guess);
+    if (!hit) {
+      segment_issue_ids<D, NT, NW>(a, desc, ld);
+      segment_issue_pair<D, NT, NW, STREAM>(a, desc, ld);
+      if (GUESS && first && threadIdx.x == 0 && desc.s < 4096 && desc.h < 4096 && desc.nq < 256)
+        *(u32x4*)record = u32x4{(uint32_t)desc.s | ((uint32_t)desc.h << 12) | ((uint32_t)desc.nq << 24),
+                                (uint32_t)desc.q0, (uint32_t)desc.page0, (uint32_t)desc.page1};
+    }
+#ifdef ASPD_DEBUG_RECORDS
+    if (GUESS && first && threadIdx.x == 0) record[hit ? 6 : 7] += 1;
+#endif
+    const bool was_first = first;
+    first = false;
+    segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot, ld,
+                                        (GUESS && was_first) ? record + 4 : nullptr);
     // the merging workgroup has 16 * NT rows of D / 4 chunks to combine: one pass of its 64 * NW threads
     if (!complete) announce_partial<D, true, THREADS, (NT == 1 ? 2 : 3)>(a, sc, it, sh, page0, page1, &merge_flag);
   }
@@ -1208,10 +1403,16 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
   const Sched sc = sched_at(sched_base, a.B);
   const Shares sh = build_schedule<THREADS>(a, sc, scratch);
   if ((int)blockIdx.x >= sh.n) return;
-  int u, end, page0, page1;
-  share_range(a, sc, sh, &u, &end);
+  int u = 0, end = 0, page0, page1;
   Item it;
-  while (next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
+  bool pending;
+  if (sh.aligned) {
+    pending = aligned_share(a, sc, sh, blockIdx.x, &it, &page0, &page1);
+  } else {
+    share_range(a, sc, sh, &u, &end);
+    pending = next_segment(a, sc, sh, &u, end, &it, &page0, &page1);
+  }
+  for (; pending; pending = !sh.aligned && next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_rows<D, NT, NW>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
@@ -1370,10 +1571,16 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
   const Sched sc = sched_at(sched_base, a.B);
   const Shares sh = build_schedule<THREADS>(a, sc, scratch);
   if ((int)blockIdx.x >= sh.n) return;
-  int u, end, page0, page1;
-  share_range(a, sc, sh, &u, &end);
+  int u = 0, end = 0, page0, page1;
   Item it;
-  while (next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
+  bool pending;
+  if (sh.aligned) {
+    pending = aligned_share(a, sc, sh, blockIdx.x, &it, &page0, &page1);
+  } else {
+    share_range(a, sc, sh, &u, &end);
+    pending = next_segment(a, sc, sh, &u, end, &it, &page0, &page1);
+  }
+  for (; pending; pending = !sh.aligned && next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
     const bool complete = (page0 == 0) && (page1 == it.np);
     float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
     segment_f32<D>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
@@ -1604,7 +1811,9 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   a.out = out_d;
   a.lse = lse_d;
   a.counters = (int*)workspace_d;
-  a.partial = (float*)((char*)workspace_d + COUNTER_BYTES);
+  a.records = (int*)((char*)workspace_d + COUNTER_BYTES);
+  a.NQ = step->NQ;
+  a.partial = (float*)((char*)workspace_d + PARTIAL_OFFSET);
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)kv->head_dim) : sm_scale) * LOG2E;
   a.B = state->B;
   a.G = kv->num_q_heads / kv->num_kv_heads;
@@ -1688,13 +1897,14 @@ extern "C" size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ)
   // needs more rows in total
   size_t slot_rows = (size_t)2 * MAX_WG * rows_cap;
   if (kv->dtype == ASPD_BF16) slot_rows = std::max(slot_rows, (size_t)2 * MAX_WG_ROWS * ROWS_NW * 16 * ROWS_NT);
-  return COUNTER_BYTES + slot_rows * (kv->head_dim + 4) * sizeof(float);
+  return PARTIAL_OFFSET + slot_rows * (kv->head_dim + 4) * sizeof(float);
 }
 
 namespace {
-__global__ void zero_counters_kernel(int* counters) {
+// Counters at zero; records all zero, which no launch takes for a segment (it would have no rows).
+__global__ void zero_counters_kernel(int* head) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < MAX_WG) counters[i] = 0;
+  if (i < PARTIAL_OFFSET / 4) head[i] = 0;
 }
 }  // namespace
 
@@ -1740,8 +1950,8 @@ extern "C" int32_t aspd_set_max_workgroups(int32_t max_workgroups) {
 
 extern "C" int aspd_workspace_init(void* workspace_d, size_t workspace_bytes, void* stream) {
   if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
-  if (workspace_bytes < (size_t)COUNTER_BYTES) return ASPD_ERR_WORKSPACE;
-  hipLaunchKernelGGL(zero_counters_kernel, dim3(MAX_WG / 256), dim3(256), 0, (hipStream_t)stream,
+  if (workspace_bytes < (size_t)PARTIAL_OFFSET) return ASPD_ERR_WORKSPACE;
+  hipLaunchKernelGGL(zero_counters_kernel, dim3(PARTIAL_OFFSET / 4 / 256), dim3(256), 0, (hipStream_t)stream,
                      (int*)workspace_d);
   ASPD_HIP_CHECK(hipGetLastError());
   return ASPD_OK;

@@ -25,9 +25,10 @@ def A():
     return binding
 
 
-def _compare_attention(A, gb, tt, wl, step, meta, fn, rows=None, label=""):
+def _compare_attention(A, gb, tt, wl, step, meta, fn, rows=None, label="", check_step=True):
     from gpu_drive import assert_step_equal
-    assert_step_equal(step, meta)
+    if check_step:
+        assert_step_equal(step, meta)
     q = wl.draw_q(meta.NQ)
     lse = torch.full((meta.NQ, wl.num_q_heads), float("nan"), dtype=torch.float32, device=gb.dev)
     out = fn(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace, lse=lse)
@@ -203,7 +204,7 @@ def test_mixed_rejects_main_tokens_under_open_branches(A):
 # --------------------------------------------------------------------------------------------- limits
 def test_capped_grid_and_long_segments(A):
     """With the grid capped to two workgroups a 70 000-token sequence gives each of them more pages
-    than the block-id window holds (2 048), so the kernels walk several windows; results must not
+    than the block-id window holds (512), so the kernels walk several windows; results must not
     depend on the cap.  Also: the cap is honoured when lifted again."""
     wl = W.random_small(seed=61, dtype="bf16", head_dim=64, num_q_heads=2, num_kv_heads=1, batch=1,
                         prefix_range=(70000, 70000), branches_range=(3, 3), branch_len_range=(40, 40),
@@ -228,6 +229,58 @@ def test_capped_grid_and_long_segments(A):
         _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label="uncapped serial")
     finally:
         A.aspd_set_max_workgroups(prev)
+
+
+def test_decode_loop_on_one_workspace(A):
+    """Forty consecutive decode launches on ONE workspace, with the hints a decoding loop gives (so the
+    one- and two-tile kernels run, which start each launch from the record the last one left in the
+    workspace): parallel steps, merge, serial steps, crossing page boundaries on the way.  Every third
+    launch goes to a second cache that holds the same contents in other physical blocks, so a launch
+    also meets a record whose segment is right and whose block ids are not."""
+    import dataclasses
+    from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
+    wl = W.random_small(seed=71, dtype="bf16", head_dim=128, num_q_heads=8, num_kv_heads=2, batch=2,
+                        prefix_range=(6000, 9000), branches_range=(3, 3), branch_len_range=(2, 2),
+                        extra_tokens_per_branch=24, extra_tokens_per_seq=24)
+    rng = np.random.default_rng(71)
+    perm = rng.permutation(wl.num_blocks)
+    order = torch.from_numpy(np.argsort(perm))
+    bt = wl.block_tables
+    wl2 = dataclasses.replace(wl, block_tables=np.where(bt >= 0, perm[np.maximum(bt, 0)], bt).astype(bt.dtype),
+                              k_cache=wl.k_cache[order], v_cache=wl.v_cache[order])
+    gbs = [GpuBatch(wl), GpuBatch(wl2)]
+    gbs[1].workspace = gbs[0].workspace
+    tt = table_with_prefix(wl)
+    for gb in gbs:
+        gb.serial(wl.prefix_len)
+        gb.open_parallel()
+    tt.open_parallel(wl.num_branches)
+    for new_len in W.interleaved_history(wl.branch_len):
+        tt.append_parallel(new_len)
+        for gb in gbs:
+            gb.parallel(new_len)
+    launch = 0
+
+    def one(stage, new_len, hint, fn, label):
+        nonlocal launch
+        new_len = np.asarray(new_len, dtype=np.int32)
+        meta = tt.append_parallel(new_len) if stage == A.STAGE_PARALLEL else tt.append_serial(new_len)
+        steps = [A.aspd_build_branch_meta(gb.kv, gb.state, stage, gb._dev_i32(new_len), NQ=int(new_len.sum()),
+                                          max_new_per_seq=hint) for gb in gbs]
+        which = 1 if launch % 3 == 2 else 0
+        # (the second cache's physical slots differ from the oracle's by construction)
+        _compare_attention(A, gbs[which], tt, wl, steps[which], meta, fn, label=f"{label} {launch} cache {which}",
+                           check_step=(which == 0))
+        launch += 1
+
+    for _ in range(20):
+        one(A.STAGE_PARALLEL, np.ones(wl.NB), int(wl.num_branches.max()), A.aspd_attn_parallel_decode, "parallel")
+    tt.merge()
+    for gb in gbs:
+        gb.merge()
+    for _ in range(20):
+        one(A.STAGE_SERIAL, np.ones(wl.B), 1, A.aspd_attn_serial_decode, "serial")
+    assert_state_equal(gbs[0], tt)
 
 
 def test_most_branches_one_sequence_can_have(A):
