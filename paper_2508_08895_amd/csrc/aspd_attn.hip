@@ -74,7 +74,12 @@ constexpr int ROWS_PREFETCH = ASPD_TUNE_RD;  // groups of pages that kernel keep
 constexpr int ROWS_PPS = ASPD_TUNE_PPS;      // pairs of pages it stages (and computes) between two barriers
 constexpr int MAX_WG_ROWS = 256;      // its largest grid (its partial slots are ROWS_NW * 16 * ROWS_NT rows each)
 constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
-constexpr int RECORD_INTS = 16;       // per workgroup: 16 bytes describing a segment, then two block ids per wave
+constexpr int RECORD_INTS = 128;      // per workgroup, in ints:
+constexpr int REC_IDS = 4;            //   0: a segment (16 bytes);  4: two block ids per wave
+constexpr int REC_ITEM = 12;          //  12: first and last workgroup of the segment's item, its pages, its prefix pages
+constexpr int REC_SIG = 16;           //  16: the launch constants the schedule depends on (0: none recorded)
+constexpr int REC_SEQ = 32;           //  32: per sequence (FAST_B of them): pages, prefix pages, first row, end row
+constexpr int FAST_B = 16;            // batches up to this size can skip the schedule, see attn_bf16_kernel
 constexpr int RECORD_BYTES = 1024 * RECORD_INTS * 4;  // MAX_WG records after the counters
 constexpr int PARTIAL_OFFSET = COUNTER_BYTES + RECORD_BYTES;  // the partial slots follow
 constexpr int MAX_WG = 1024;          // upper bound of the grid (workspace is sized for it)
@@ -436,7 +441,10 @@ __device__ __forceinline__ bool next_segment(const AttnArgs& a, const Sched& sc,
 // written a partial of `it`, pages [page0, page1).
 template <int D, bool BF16, int THREADS, int ELEMS>
 __device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh, int page0,
-                                 int page1, int* flag /* LDS */);
+                                 int page1, int* flag /* LDS */, int* owner_out = nullptr, int* w_last_out = nullptr);
+// The same for a caller that knows the item's first and last workgroup.
+template <int D, bool BF16, int THREADS, int ELEMS>
+__device__ void announce_partial_to(const AttnArgs& a, const Item& it, int owner, int w_last, int* flag /* LDS */);
 
 __device__ __forceinline__ float* partial_slot(const AttnArgs& a, int wg, int starts_item, int D) {
   return a.partial + ((long)(2 * wg + starts_item)) * a.rows_cap * (D + 4);
@@ -1096,17 +1104,46 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
   // that turns out not to be the workgroup's first are dropped.  A record only chooses addresses to
   // read early (checked against the call's bounds first); results never depend on it.
   constexpr bool GUESS = (NT <= 2);  // three tiles leave no registers to hold the loads meanwhile
-  static_assert(4 + 2 * NW <= RECORD_INTS, "record holds two block ids per wave");
+  static_assert(REC_IDS + 2 * NW <= REC_ITEM, "record holds two block ids per wave");
   SegLoads<D, NT, NW> ld;
   SegDesc guess = {0, 0, 0, 0, 0, 0};
   bool guessed = false;
   int* record = a.records + (long)blockIdx.x * RECORD_INTS;
+  // Small batches go one step further.  The schedule is a function of a few launch constants and, per
+  // sequence, of its page count, its prefix page count and its rows; the record keeps those as well,
+  // every wave loads the current ones (lane s: sequence s), and when all of them are EQUAL the recorded
+  // segment is this launch's segment by construction: the schedule is then not worked out at all.
+  const int lane = threadIdx.x & 63;
+  const bool small = GUESS && a.B <= FAST_B;
+  const uint32_t sig0 = (uint32_t)a.nwg | ((uint32_t)a.qpg << 16);
+  const uint32_t sig1 = (uint32_t)a.pad | ((uint32_t)a.kv.num_kv_heads << 16);
+  const uint32_t sig2 = (uint32_t)a.B | (a.slot_owner ? 0x10000u : 0u) | 0x80000000u;
+  const uint32_t sig3 = (uint32_t)a.kv.max_blocks_per_seq;
+  int l_np = 0, l_lp = 0, l_q0 = 0, l_q1 = 0, l_L = 0;  // lane s: sequence s as this launch has it
+  bool fast = false;
+  Item it;
+  int page0 = 0, page1 = 0, owner_rec = 0, w_last_rec = 0;
   if (GUESS) {
     // one 16-byte load: sequence (12 bits), KV head (12), queries (8) | first row | first page | end page
     u32x4 r0 = *(const u32x4*)record;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int rb0 = record[4 + 2 * wave], rb1 = record[5 + 2 * wave];  // block ids of the wave's first pair
-    asm volatile("" : "+v"(r0), "+v"(rb0), "+v"(rb1));  // both loads leave before either is waited for
+    int rb0 = record[REC_IDS + 2 * wave], rb1 = record[REC_IDS + 2 * wave + 1];  // block ids of the wave's first pair
+    u32x4 ritem = {0u, 0u, 0u, 0u}, rsig = {0u, 0u, 0u, 0u}, rseq = {0u, 0u, 0u, 0u};
+    int l_T = 0, l_q0n = 0, l_q1n = 0;
+    if (small) {
+      ritem = *(const u32x4*)(record + REC_ITEM);
+      rsig = *(const u32x4*)(record + REC_SIG);
+      if (lane < a.B) {
+        rseq = *(const u32x4*)(record + REC_SEQ + 4 * lane);
+        l_T = a.seq_len[lane];
+        l_L = a.stage_base[lane];
+        l_q0n = a.cu_seq_new[lane];
+        l_q1n = a.cu_seq_new[lane + 1];
+      }
+    }
+    // all of these loads leave before any of them is waited for
+    asm volatile("" : "+v"(r0), "+v"(rb0), "+v"(rb1), "+v"(ritem), "+v"(rsig), "+v"(rseq), "+v"(l_T), "+v"(l_L),
+                 "+v"(l_q0n), "+v"(l_q1n));
     const uint32_t w0 = __builtin_amdgcn_readfirstlane(r0[0]);
     guess.s = (int)(w0 & 0xfffu);
     guess.h = (int)((w0 >> 12) & 0xfffu);
@@ -1117,27 +1154,63 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
     guessed = guess.s >= 0 && guess.s < a.B && guess.h >= 0 && guess.h < a.kv.num_kv_heads && guess.q0 >= 0 &&
               guess.nq >= 1 && guess.nq <= a.qpg && guess.q0 <= a.NQ - guess.nq && guess.page0 >= 0 &&
               guess.page0 < guess.page1 && guess.page1 <= a.kv.max_blocks_per_seq;
+    if (small) {
+      l_np = min((l_T + ASPD_BLOCK - 1) / ASPD_BLOCK, a.kv.max_blocks_per_seq);
+      l_lp = a.slot_owner ? min(l_np, l_L / ASPD_BLOCK) : l_np;
+      l_q0 = l_q0n;
+      l_q1 = l_q1n;
+      const bool same = lane >= a.B || ((int)rseq[0] == l_np && (int)rseq[1] == l_lp && (int)rseq[2] == l_q0 &&
+                                        (int)rseq[3] == l_q1);
+      const bool all_same = __all(same) != 0;
+      const bool sig_same = __builtin_amdgcn_readfirstlane(rsig[0]) == sig0 &&
+                            __builtin_amdgcn_readfirstlane(rsig[1]) == sig1 &&
+                            __builtin_amdgcn_readfirstlane(rsig[2]) == sig2 &&
+                            __builtin_amdgcn_readfirstlane(rsig[3]) == sig3;
+      owner_rec = (int)__builtin_amdgcn_readfirstlane(ritem[0]);
+      w_last_rec = (int)__builtin_amdgcn_readfirstlane(ritem[1]);
+      const int np_rec = (int)__builtin_amdgcn_readfirstlane(ritem[2]);
+      const int lp_rec = (int)__builtin_amdgcn_readfirstlane(ritem[3]);
+      // (the last line only guards against a workspace someone else has written to)
+      fast = guessed && all_same && sig_same && owner_rec >= 0 && owner_rec <= (int)blockIdx.x &&
+             (int)blockIdx.x <= w_last_rec && w_last_rec < a.nwg && guess.page1 <= np_rec && lp_rec <= np_rec &&
+             np_rec <= a.kv.max_blocks_per_seq;
+      if (fast) {
+        it.s = guess.s;
+        it.h = guess.h;
+        it.rg = 0;
+        it.np = np_rec;
+        it.lp = lp_rec;
+        it.q0 = guess.q0;
+        it.nq = guess.nq;
+        it.first_unit = 0;
+        page0 = guess.page0;
+        page1 = guess.page1;
+      }
+    }
     // (a record that fails the checks is replaced by a segment every call has, so that the loads are
-    // the same on every path, see segment_issue)
+    // the same on every path, see segment_issue_ids)
     if (!guessed) guess = SegDesc{0, 0, 0, 1, 0, 1};
     segment_issue_ids<D, NT, NW>(a, guess, ld);
     // the pages go with the block ids of the record (any two blocks of the pool are safe to read; the
     // segment compares them with the block table before it uses the pages)
     ld.used0 = min(max(__builtin_amdgcn_readfirstlane(rb0), 0), a.kv.num_blocks - 1);
     ld.used1 = min(max(__builtin_amdgcn_readfirstlane(rb1), 0), a.kv.num_blocks - 1);
-    issue_pair<D, STREAM>(ld.first, a, guess.h, ld.used0, ld.used1, threadIdx.x & 63, nullptr, 0);
+    issue_pair<D, STREAM>(ld.first, a, guess.h, ld.used0, ld.used1, lane, nullptr, 0);
     asm volatile("" ::: "memory");  // and all of these before the schedule is worked out
   }
-  const Shares sh = build_schedule<THREADS>(a, sc, scratch, seq);
-  if ((int)blockIdx.x >= sh.n) return;
-  int u = 0, end = 0, page0, page1;
-  Item it;
-  bool pending;
-  if (sh.aligned) {
-    pending = aligned_share(a, sc, sh, blockIdx.x, &it, &page0, &page1);
-  } else {
-    share_range(a, sc, sh, &u, &end);
-    pending = next_segment(a, sc, sh, &u, end, &it, &page0, &page1);
+  Shares sh;
+  sh.aligned = true;
+  int u = 0, end = 0;
+  bool pending = true;
+  if (!fast) {
+    sh = build_schedule<THREADS>(a, sc, scratch, seq);
+    if ((int)blockIdx.x >= sh.n) return;
+    if (sh.aligned) {
+      pending = aligned_share(a, sc, sh, blockIdx.x, &it, &page0, &page1);
+    } else {
+      share_range(a, sc, sh, &u, &end);
+      pending = next_segment(a, sc, sh, &u, end, &it, &page0, &page1);
+    }
   }
   bool first = true;
   for (; pending; pending = !sh.aligned && next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
@@ -1153,14 +1226,34 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
                                 (uint32_t)desc.q0, (uint32_t)desc.page0, (uint32_t)desc.page1};
     }
 #ifdef ASPD_DEBUG_RECORDS
-    if (GUESS && first && threadIdx.x == 0) record[hit ? 6 : 7] += 1;
+    if (GUESS && first && threadIdx.x == 0) record[fast ? 22 : (hit ? 20 : 21)] += 1;
 #endif
     const bool was_first = first;
     first = false;
-    segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot, ld,
-                                        (GUESS && was_first) ? record + 4 : nullptr);
+    // stage_base of the item's sequence
+    const int L = fast ? __builtin_amdgcn_readlane(l_L, __builtin_amdgcn_readfirstlane(it.s)) : sc.L[it.s];
+    segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, L, complete, pslot, ld,
+                                        (GUESS && was_first) ? record + REC_IDS : nullptr);
     // the merging workgroup has 16 * NT rows of D / 4 chunks to combine: one pass of its 64 * NW threads
-    if (!complete) announce_partial<D, true, THREADS, (NT == 1 ? 2 : 3)>(a, sc, it, sh, page0, page1, &merge_flag);
+    int owner = (int)blockIdx.x, w_last = (int)blockIdx.x;
+    if (!complete) {
+      if (fast)
+        announce_partial_to<D, true, THREADS, (NT == 1 ? 2 : 3)>(a, it, owner_rec, w_last_rec, &merge_flag);
+      else
+        announce_partial<D, true, THREADS, (NT == 1 ? 2 : 3)>(a, sc, it, sh, page0, page1, &merge_flag, &owner,
+                                                              &w_last);
+    }
+    // what a later launch with the same lengths needs in order to skip the schedule
+    if (GUESS && was_first && !fast) {
+      const bool keep = small && sh.aligned && desc.s < 4096 && desc.h < 4096 && desc.nq < 256;
+      if (threadIdx.x == 0) {
+        *(u32x4*)(record + REC_ITEM) = u32x4{(uint32_t)owner, (uint32_t)w_last, (uint32_t)it.np, (uint32_t)it.lp};
+        *(u32x4*)(record + REC_SIG) = keep ? u32x4{sig0, sig1, sig2, sig3} : u32x4{0u, 0u, 0u, 0u};
+      }
+      if (keep && (int)threadIdx.x < a.B)
+        *(u32x4*)(record + REC_SEQ + 4 * threadIdx.x) =
+            u32x4{(uint32_t)l_np, (uint32_t)l_lp, (uint32_t)l_q0, (uint32_t)l_q1};
+    }
   }
 }
 
@@ -1680,13 +1773,19 @@ __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_l
 // Called by every thread of the workgroup after it has written a partial of `it`.
 template <int D, bool BF16, int THREADS, int ELEMS>
 __device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh, int page0,
-                                 int page1, int* flag /* LDS */) {
-  // the write-through stores of the partial have completed before the arrival is counted
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+                                 int page1, int* flag /* LDS */, int* owner_out, int* w_last_out) {
   // the workgroups that hold the item's first and last page
   const int owner = page0 == 0 ? (int)blockIdx.x : share_owner(a, sc, sh, it.first_unit + sh.pad);
   const int w_last = page1 == it.np ? (int)blockIdx.x : share_owner(a, sc, sh, it.first_unit + sh.pad + it.np - 1);
+  if (owner_out) *owner_out = owner;
+  if (w_last_out) *w_last_out = w_last;
+  announce_partial_to<D, BF16, THREADS, ELEMS>(a, it, owner, w_last, flag);
+}
+template <int D, bool BF16, int THREADS, int ELEMS>
+__device__ void announce_partial_to(const AttnArgs& a, const Item& it, int owner, int w_last, int* flag /* LDS */) {
+  // the write-through stores of the partial have completed before the arrival is counted
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
   if (threadIdx.x == 0) {
     const int old = atomicAdd(a.counters + owner, 1);
     const int last = (old == w_last - owner) ? 1 : 0;
