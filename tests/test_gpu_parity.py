@@ -251,6 +251,12 @@ def test_decode_loop_on_one_workspace(A):
     gbs = [GpuBatch(wl), GpuBatch(wl2)]
     gbs[1].workspace = gbs[0].workspace
     tt = table_with_prefix(wl)
+    # a different batch of the same shape takes the same workspace now and then
+    wl3 = W.random_small(seed=72, dtype="bf16", head_dim=128, num_q_heads=8, num_kv_heads=2, batch=2,
+                         prefix_range=(6000, 9000), branches_range=(3, 3), branch_len_range=(2, 2),
+                         extra_tokens_per_branch=24, extra_tokens_per_seq=24)
+    gb3, tt3 = _grow_both(A, wl3, wl3.branch_len, False)
+    gb3.workspace = gbs[0].workspace
     for gb in gbs:
         gb.serial(wl.prefix_len)
         gb.open_parallel()
@@ -271,6 +277,11 @@ def test_decode_loop_on_one_workspace(A):
         # (the second cache's physical slots differ from the oracle's by construction)
         _compare_attention(A, gbs[which], tt, wl, steps[which], meta, fn, label=f"{label} {launch} cache {which}",
                            check_step=(which == 0))
+        if launch % 5 == 4 and stage == A.STAGE_PARALLEL:
+            meta3 = tt3.append_parallel(new_len)
+            step3 = A.aspd_build_branch_meta(gb3.kv, gb3.state, stage, gb3._dev_i32(new_len), NQ=int(new_len.sum()),
+                                             max_new_per_seq=hint)
+            _compare_attention(A, gb3, tt3, wl3, step3, meta3, fn, label=f"{label} {launch} other batch")
         launch += 1
 
     for _ in range(20):
