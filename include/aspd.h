@@ -184,15 +184,22 @@ ASPD_API int aspd_rope_append(const aspd_kv* kv, const aspd_step* step, void* q_
  * Results do not depend on it.  Returns the previous value. */
 ASPD_API int32_t aspd_set_max_workgroups(int32_t max_workgroups);
 
-/* Bytes of device scratch the attention calls need for partial softmax results of split key
- * ranges (host-only computation, needs no GPU).  Returns 0 on invalid arguments. */
+/* Bytes of device scratch the attention calls need: arrival counters, the per-workgroup records
+ * described with aspd_workspace_init, and the partial softmax results of split key ranges
+ * (host-only computation, needs no GPU).  Returns 0 on invalid arguments. */
 ASPD_API size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ);
 
 /* Prepares a freshly allocated workspace (256-byte aligned, at least aspd_workspace_bytes): enqueues
- * a small kernel that clears the arrival counters at its head.  Call once after allocation, on the
- * stream (or ordered before the stream) of the first attention call.  Attention calls leave the
- * counters cleared, so one workspace serves any number of calls, one at a time: two attention
- * calls that run concurrently must not share a workspace. */
+ * a small kernel that clears the arrival counters and the records at its head.  Call once after
+ * allocation, on the stream (or ordered before the stream) of the first attention call.  Attention
+ * calls leave the counters cleared, so one workspace serves any number of calls, one at a time: two
+ * attention calls that run concurrently must not share a workspace.
+ * Between calls the workspace belongs to the library: every workgroup of an attention launch leaves a
+ * record of the key range it had, and the next launch that finds the batch unchanged in everything
+ * its schedule depends on (typical of a decoding loop, layer after layer and step after step) starts
+ * from the record instead of working the schedule out again.  Calls with any other batch, shape or
+ * entry point may follow one another on the same workspace in any order; nothing but the library may
+ * write to it (or call aspd_workspace_init again after doing so). */
 ASPD_API int aspd_workspace_init(void* workspace_d, size_t workspace_bytes, void* stream);
 
 /* Sec. 3.2 Eq. 1-3, "The Parallel Branch's Perspective"; Sec. 3.3.  One new token per active branch
