@@ -231,7 +231,8 @@ def test_capped_grid_and_long_segments(A):
         A.aspd_set_max_workgroups(prev)
 
 
-def test_decode_loop_on_one_workspace(A):
+@pytest.mark.parametrize("branches", [3, 6], ids=["one_tile", "two_tiles"])
+def test_decode_loop_on_one_workspace(A, branches):
     """Forty consecutive decode launches on ONE workspace, with the hints a decoding loop gives (so the
     one- and two-tile kernels run, which start each launch from the record the last one left in the
     workspace): parallel steps, merge, serial steps, crossing page boundaries on the way.  Every third
@@ -240,7 +241,7 @@ def test_decode_loop_on_one_workspace(A):
     import dataclasses
     from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
     wl = W.random_small(seed=71, dtype="bf16", head_dim=128, num_q_heads=8, num_kv_heads=2, batch=2,
-                        prefix_range=(6000, 9000), branches_range=(3, 3), branch_len_range=(2, 2),
+                        prefix_range=(6000, 9000), branches_range=(branches, branches), branch_len_range=(2, 2),
                         extra_tokens_per_branch=24, extra_tokens_per_seq=24)
     rng = np.random.default_rng(71)
     perm = rng.permutation(wl.num_blocks)
@@ -253,7 +254,7 @@ def test_decode_loop_on_one_workspace(A):
     tt = table_with_prefix(wl)
     # a different batch of the same shape takes the same workspace now and then
     wl3 = W.random_small(seed=72, dtype="bf16", head_dim=128, num_q_heads=8, num_kv_heads=2, batch=2,
-                         prefix_range=(6000, 9000), branches_range=(3, 3), branch_len_range=(2, 2),
+                         prefix_range=(6000, 9000), branches_range=(branches, branches), branch_len_range=(2, 2),
                          extra_tokens_per_branch=24, extra_tokens_per_seq=24)
     gb3, tt3 = _grow_both(A, wl3, wl3.branch_len, False)
     gb3.workspace = gbs[0].workspace
