@@ -1225,9 +1225,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
         *(u32x4*)record = u32x4{(uint32_t)desc.s | ((uint32_t)desc.h << 12) | ((uint32_t)desc.nq << 24),
                                 (uint32_t)desc.q0, (uint32_t)desc.page0, (uint32_t)desc.page1};
     }
-#ifdef ASPD_DEBUG_RECORDS
-    if (GUESS && first && threadIdx.x == 0) record[fast ? 22 : (hit ? 20 : 21)] += 1;
-#endif
     const bool was_first = first;
     first = false;
     // stage_base of the item's sequence
