@@ -640,6 +640,53 @@ def test_hint_does_not_change_results(A):
         assert err <= TOL[wl.dtype], (hint, err)
 
 
+# --------------------------------------------------------------------------------------------- degenerate inputs
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_without_tokens_is_a_no_op(A, dtype):
+    """Every branch finished (new_len all zero): the metadata call leaves the state as it is and the
+    attention calls return without touching their output."""
+    from gpu_drive import assert_state_equal
+    kw = dict(dtype=dtype, head_dim=64, num_q_heads=4, num_kv_heads=4 if dtype == "f32" else 2, batch=3)
+    wl = W.random_small(151, **kw)
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    zeros = np.zeros(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(zeros)
+    step = gb.parallel(zeros)
+    assert step.NQ == 0 and meta.NQ == 0
+    assert gb.fault() == 0
+    assert_state_equal(gb, tt)
+    q = torch.zeros(1, wl.num_q_heads, wl.head_dim, dtype=wl.torch_dtype, device=gb.dev)
+    out = torch.full_like(q, 7.0)
+    for fn in (A.aspd_attn_parallel_decode, A.aspd_attn_branch_chunk):
+        fn(gb.kv, gb.state, step, q, gb.workspace, out=out)
+    torch.cuda.synchronize()
+    assert (out == 7.0).all()
+
+
+def test_single_branch_is_plain_causal_attention(A):
+    """K = 1: the branch sees the prefix and itself, which is ordinary causal attention; checked against
+    torch's own scaled-dot-product attention (a second reference besides the oracle)."""
+    wl = W.random_small(152, dtype="bf16", head_dim=128, num_q_heads=8, num_kv_heads=2, batch=2,
+                        prefix_range=(100, 900), branches_range=(1, 1), branch_len_range=(5, 40))
+    gb, tt = _grow_both(A, wl, wl.branch_len - 1, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label="single branch")
+    # the same through torch: the query of sequence s attends every token of s
+    q = wl.draw_q(meta.NQ)
+    out = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace).float().cpu()
+    G = wl.num_q_heads // wl.num_kv_heads
+    for s in range(wl.B):
+        phys = torch.from_numpy(np.asarray(tt.physical_slots(s), dtype=np.int64))
+        k = wl.k_cache[phys // 16, :, phys % 16].float()          # [T][Hkv][D]
+        v = wl.v_cache[phys // 16, :, phys % 16].float()
+        k = k.permute(1, 0, 2).repeat_interleave(G, dim=0)         # [Hq][T][D]
+        v = v.permute(1, 0, 2).repeat_interleave(G, dim=0)
+        ref = torch.nn.functional.scaled_dot_product_attention(q[s].float().unsqueeze(1), k, v)  # [Hq][1][D]
+        assert (out[s] - ref[:, 0]).abs().max().item() <= TOL["bf16"]
+
+
 # --------------------------------------------------------------------------------------------- faults (host-forced)
 def test_outgrowing_the_block_table_raises_a_fault_and_writes_nothing(A):
     from gpu_drive import GpuBatch
