@@ -16,6 +16,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -389,13 +390,13 @@ def main() -> int:
     dom_time = sum(dur[k] * len(bytes_of[k]) for k in dom)
     dom_bytes = sum(float(np.sum(bytes_of[k])) for k in dom)
     achieved = dom_bytes / dom_time / 1e9
+    # HBM bytes per launch as the counters saw them: the figure of the committed rocprofv3 summary of this
+    # workload (a line "traffic_bytes_per_decode_launch = N"), null when there is none
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", f"attn_bf16_{args.workload}_hbm_traffic.md")
     if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get("bytes_per_launch")
-        except Exception:
-            traffic = None
+        m = re.search(r"^traffic_bytes_per_decode_launch\s*=\s*(\d+)", open(tpath).read(), re.M)
+        traffic = int(m.group(1)) if m else None
     roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel (parallel + serial decode launches)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
