@@ -86,13 +86,18 @@ def test_config1_parallel_then_serial_fp32(A):
 
 
 # --------------------------------------------------------------------------------------------- configs 2-4
+@pytest.mark.parametrize("hinted", [False, True], ids=["no_hint", "hinted"])
 @pytest.mark.parametrize("index", [2, 3, 4])
-def test_config_parallel_decode_full_size(A, index):
+def test_config_parallel_decode_full_size(A, index, hinted):
+    """`hinted`: with the bound on new tokens per sequence a decoding loop knows and bench.py passes
+    (it selects the one- and two-tile kernels and their launch-to-launch records)."""
     wl = W.config(index)
     gb, tt = _grow_both(A, wl, wl.branch_len - 1, False)
     ones = np.ones(wl.NB, dtype=np.int32)
     meta = tt.append_parallel(ones)
     step = gb.parallel(ones)
+    if hinted:
+        step.max_new_per_seq = int(wl.num_branches.max())
     _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label=f"cfg{index} parallel")
     if index == 4:
         # merge, then serial steps over prefix + all branches (three of the 32 are checked here)
@@ -103,18 +108,23 @@ def test_config_parallel_decode_full_size(A, index):
         for i in range(3):
             meta = tt.append_serial(one)
             step = gb.serial(one)
+            if hinted:
+                step.max_new_per_seq = 1
             _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label=f"cfg4 serial {i}")
         assert_state_equal(gb, tt)
 
 
 # --------------------------------------------------------------------------------------------- config 5
+@pytest.mark.parametrize("hinted", [False, True], ids=["no_hint", "hinted"])
 @pytest.mark.parametrize("scale,batch", [(0.125, 8), (1.0, 64)])
-def test_config5_chunk_then_decode(A, scale, batch):
+def test_config5_chunk_then_decode(A, scale, batch, hinted):
     wl = W.config(5, scale=scale, batch=batch)
     gb, tt = _grow_both(A, wl, wl.branch_len, False)
     chunk = np.full(wl.NB, 16, dtype=np.int32)
     meta = tt.append_parallel(chunk)
     step = gb.parallel(chunk)
+    if hinted:
+        step.max_new_per_seq = 16 * int(wl.num_branches.max())
     rows = None
     if scale == 1.0:   # full size: a seeded sample of rows the oracle computes one by one
         rows = np.sort(np.random.default_rng(5).choice(meta.NQ, size=256, replace=False))
@@ -123,6 +133,8 @@ def test_config5_chunk_then_decode(A, scale, batch):
     ones = np.ones(wl.NB, dtype=np.int32)
     meta = tt.append_parallel(ones)
     step = gb.parallel(ones)
+    if hinted:
+        step.max_new_per_seq = int(wl.num_branches.max())
     rows = None
     if scale == 1.0:
         rows = np.sort(np.random.default_rng(6).choice(meta.NQ, size=96, replace=False))
