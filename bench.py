@@ -9,7 +9,11 @@ tables, queries) are resident in HBM before the timed region.  The decode state 
 snapshot at the start of every step (four small device copies, inside the timed region) so that
 every step does identical work.
 
-Prints ONE JSON line (see README for the fields).  One GPU only.
+Prints ONE JSON line.  Besides the throughput of the step (`value`, query tokens per second) it carries
+`per_call` (every call kind: average launch, algorithmic bytes, fraction of 8 TB/s, and the bound
+max(bytes / 8 TB/s, dispatch floor)), `roofline` (the streaming decode kernel against the HBM peak, with
+the counter-measured traffic, the rate of a plain read stream on the same device and the dispatch floor)
+and `cpu_baseline` (the CPU oracle on a bounded sample of the same workload).  One GPU only.
 """
 from __future__ import annotations
 
@@ -59,7 +63,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is one-GPU only (the path shards by sequence or KV head without "
-              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "exchange, nothing here uses a second GPU); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
