@@ -652,6 +652,58 @@ def test_hint_does_not_change_results(A):
         assert err <= TOL[wl.dtype], (hint, err)
 
 
+# --------------------------------------------------------------------------------------------- seeded sweep
+def test_seeded_sweep_on_a_shared_workspace(A):
+    """Forty seeded random shapes (dtype, head sizes, batch, prefix, branches), every call kind, each
+    launch three times in a row on ONE workspace shared by all shapes: a launch meets the records of
+    the launch before it, of another call kind and of another batch."""
+    from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
+    ws = torch.zeros(200 << 20, dtype=torch.uint8, device="cuda")
+    A.aspd_workspace_init(ws)
+    for seed in range(7001, 7041):
+        rng = np.random.default_rng(seed)
+        dtype = "bf16" if rng.random() < 0.75 else "f32"
+        D = int(rng.choice([64, 128]))
+        if dtype == "f32":
+            Hkv, G = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4]))
+        else:
+            Hkv, G = int(rng.choice([1, 2, 8])), int(rng.choice([1, 2, 4, 8, 16]))
+        B = int(rng.integers(1, 9))
+        pmax = int(rng.choice([10, 100, 700, 3000, 9000]))
+        kb = int(rng.choice([1, 3, 8, 20]))
+        wl = W.random_small(seed=seed, dtype=dtype, head_dim=D, num_q_heads=Hkv * G, num_kv_heads=Hkv, batch=B,
+                            prefix_range=(0, pmax), branches_range=(1, kb),
+                            branch_len_range=(1, int(rng.choice([3, 20, 70]))), extra_tokens_per_branch=24,
+                            extra_tokens_per_seq=12)
+        label = f"seed {seed} {dtype} D{D} Hkv{Hkv} G{G} B{B} pmax{pmax} K<={kb}"
+        gb, tt = _grow_both(A, wl, wl.branch_len - 1, False)
+        gb.workspace = ws
+
+        def check(meta, step, fn, what, hint):
+            assert_step_equal(step, meta)
+            q = wl.draw_q(meta.NQ)
+            step.max_new_per_seq = hint
+            ref, _ = attend(tt, meta, q, wl.k_cache, wl.v_cache)
+            for rep in range(3):
+                out = fn(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace)
+                err = np.abs(out.float().cpu().numpy().astype(np.float64) - ref).max()
+                assert np.isfinite(err) and err <= TOL[dtype], (label, what, rep, err)
+
+        ones = np.ones(wl.NB, dtype=np.int32)
+        check(tt.append_parallel(ones), gb.parallel(ones), A.aspd_attn_parallel_decode, "parallel",
+              int(rng.choice([0, int(wl.num_branches.max())])))
+        ch = rng.integers(0, int(rng.choice([3, 9, 21])), size=wl.NB).astype(np.int32)
+        if ch.sum():
+            check(tt.append_parallel(ch), gb.parallel(ch), A.aspd_attn_branch_chunk, "chunk", 0)
+        tt.merge()
+        gb.merge()
+        nm = rng.integers(0, int(rng.choice([2, 2, 30])), size=wl.B).astype(np.int32)
+        if nm.sum() and (nm <= 12).all():
+            check(tt.append_serial(nm), gb.serial(nm), A.aspd_attn_serial_decode, "serial",
+                  int(rng.choice([0, int(nm.max())])))
+        assert_state_equal(gb, tt)
+
+
 # --------------------------------------------------------------------------------------------- degenerate inputs
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_step_without_tokens_is_a_no_op(A, dtype):
