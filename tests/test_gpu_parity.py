@@ -624,6 +624,84 @@ def test_repeat_calls_agree(A):
     assert (a.float() - b.float()).abs().max().item() <= 4e-3
 
 
+def test_a_captured_step_replays_like_the_eager_one(A):
+    """No call reads device data on the host, so a whole decode step (state restored from a snapshot,
+    metadata, attention; then merge, metadata and attention of a serial step) can be captured in a HIP
+    graph.  Five replays, with eager launches on the same workspace and synchronisations between them,
+    each leave the step arrays, the state and the outputs the eager step left, and the oracle's."""
+    from gpu_drive import assert_step_equal, assert_state_equal
+    wl = W.config(3, scale=0.12, batch=6)
+    gb, tt = _grow_both(A, wl, wl.branch_len - 1, False)
+    st = gb.state
+    live = [st.stage_base, st.seq_len, st.branch_len, st.slot_owner, st.main_pos]
+    snap = [t.clone() for t in live]
+    ones = np.ones(wl.NB, dtype=np.int32)
+    one = np.ones(wl.B, dtype=np.int32)
+    d_ones, d_one = gb._dev_i32(ones), gb._dev_i32(one)
+    # eager step, checked against the oracle
+    meta_p = tt.append_parallel(ones)
+    step_p = gb.parallel(ones)
+    assert_step_equal(step_p, meta_p)
+    q_p = wl.draw_q(meta_p.NQ)
+    ref_p, _ = attend(tt, meta_p, q_p, wl.k_cache, wl.v_cache)
+    q_p = q_p.to(gb.dev)
+    eager_p = A.aspd_attn_parallel_decode(gb.kv, st, step_p, q_p, gb.workspace).clone()
+    tt.merge()
+    gb.merge()
+    meta_s = tt.append_serial(one)
+    step_s = gb.serial(one)
+    assert_step_equal(step_s, meta_s)
+    q_s = wl.draw_q(meta_s.NQ)
+    ref_s, _ = attend(tt, meta_s, q_s, wl.k_cache, wl.v_cache)
+    q_s = q_s.to(gb.dev)
+    eager_s = A.aspd_attn_serial_decode(gb.kv, st, step_s, q_s, gb.workspace).clone()
+    torch.cuda.synchronize()
+    assert np.abs(eager_p.float().cpu().numpy() - ref_p).max() <= TOL[wl.dtype]
+    assert np.abs(eager_s.float().cpu().numpy() - ref_s).max() <= TOL[wl.dtype]
+    assert_state_equal(gb, tt)
+    end_state = [t.clone() for t in live]
+    out_p, out_s = torch.empty_like(eager_p), torch.empty_like(eager_s)
+
+    def one_step():
+        for dst, src in zip(live, snap):
+            dst.copy_(src)
+        A.aspd_build_branch_meta(gb.kv, st, A.STAGE_PARALLEL, d_ones, step=step_p)
+        A.aspd_attn_parallel_decode(gb.kv, st, step_p, q_p, gb.workspace, out=out_p)
+        A.aspd_build_branch_meta(gb.kv, st, A.STAGE_MERGE, None)
+        A.aspd_build_branch_meta(gb.kv, st, A.STAGE_SERIAL, d_one, step=step_s)
+        A.aspd_attn_serial_decode(gb.kv, st, step_s, q_s, gb.workspace, out=out_s)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        one_step()
+    for i in range(5):
+        # eager work between the replays: scribble over what the graph has to produce, and use the
+        # workspace for another launch (a chunk call, another kernel) so that the replay meets its records
+        out_p.fill_(float("nan"))
+        out_s.fill_(float("nan"))
+        for t in (step_p.position_ids, step_p.logical_slot, step_s.position_ids, step_s.slot_mapping):
+            t.fill_(-7)
+        A.aspd_attn_branch_chunk(gb.kv, st, step_s, q_s, gb.workspace)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_step_equal(step_p, meta_p)
+        assert_step_equal(step_s, meta_s)
+        for t, e in zip(live, end_state):
+            assert torch.equal(t, e), i
+        # (pairs of pages are handed to waves dynamically: two runs agree to rounding, not bitwise)
+        assert (out_p.float() - eager_p.float()).abs().max().item() <= 4e-3, i
+        assert (out_s.float() - eager_s.float()).abs().max().item() <= 4e-3, i
+        assert np.abs(out_p.float().cpu().numpy() - ref_p).max() <= TOL[wl.dtype], i
+        assert np.abs(out_s.float().cpu().numpy() - ref_s).max() <= TOL[wl.dtype], i
+    assert gb.fault() == 0
+
+
 def test_fp32_repeat_calls_are_bit_identical(A):
     """The fp32 kernel assigns pages to waves statically: same inputs, same bits."""
     wl = W.random_small(132, dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=4, batch=3)
