@@ -2,6 +2,8 @@
 
 Metadata and slot mapping must match bit-exactly; attention outputs within max-abs 1e-5 for fp32
 inputs and 2e-2 for bf16 inputs (fp32 accumulation), the tolerances the benchmark spec states."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -712,6 +714,28 @@ def test_fp32_repeat_calls_are_bit_identical(A):
     a = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace).clone()
     b = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace)
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_softmax_scale_argument(A, dtype):
+    """sm_scale other than the default: scores scaled by c / sqrt(head_dim) with queries q are the scores
+    of the default scale with queries c q, which is what the oracle is given (c a power of two, so that
+    c q is exact in either dtype)."""
+    kw = dict(dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=2) if dtype == "f32" else {}
+    wl = W.random_small(141, batch=3, **kw)
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    q = wl.draw_q(meta.NQ)
+    for c in (0.25, 2.0):
+        ref, ref_lse = attend(tt, meta, q * c, wl.k_cache, wl.v_cache)
+        lse = torch.full((meta.NQ, wl.num_q_heads), float("nan"), dtype=torch.float32, device=gb.dev)
+        out = A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace, lse=lse,
+                                          sm_scale=c / math.sqrt(wl.head_dim))
+        torch.cuda.synchronize()
+        assert np.abs(out.float().cpu().numpy() - ref).max() <= TOL[wl.dtype], c
+        assert np.abs(lse.cpu().numpy() - ref_lse).max() <= LSE_TOL[wl.dtype], c
 
 
 def test_hint_does_not_change_results(A):
