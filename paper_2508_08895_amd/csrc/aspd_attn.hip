@@ -1689,8 +1689,10 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
 template <int D, bool BF16, int THREADS, int ELEMS>
 __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_last) {
   constexpr int CPR = D / 4;  // float4 chunks per row
-  constexpr int BATCH = 8;    // partials fetched at once, per element
-  // ELEMS: (row, chunk) elements a thread combines concurrently
+  // ELEMS: (row, chunk) elements a thread combines concurrently; BATCH: partials fetched at once, per
+  // element.  A second batch costs a second round trip to memory, so the batch is as large as the
+  // registers allow (sixteen in the one-tile streaming kernel, one wave per SIMD).
+  constexpr int BATCH = (BF16 && ELEMS == 2 && THREADS == 256) ? 16 : 8;
   const int R = it.nq * a.G;
   const long stride = (long)a.rows_cap * (D + 4);
   const int nparts = w_last - owner + 1;
