@@ -195,11 +195,12 @@ class TokenTable:
                 continue
             if self.cur_parallel[s]:
                 if self.pos_mode == "same_max":
+                    # right after the largest position a branch reached; a stage without a token reached none
                     self.next_main_pos[s] = self.stage_start_pos[s] + max(self.tokens_in_branch[s])
-                elif self.fix_n and max(self.tokens_in_branch[s]) > 0:   # a stage that never got a token leaves no trace
-                    self.next_main_pos[s] = self.stage_start_pos[s] + len(self.tokens_in_branch[s]) * self.fix_n
                 elif self.fix_n:
-                    pass
+                    # the K intervals were allotted when the stage opened ("pre-allocated", Sec. 4.5.3):
+                    # they are spent whether or not a branch ever produced a token
+                    self.next_main_pos[s] = self.stage_start_pos[s] + len(self.tokens_in_branch[s]) * self.fix_n
                 else:
                     self.next_main_pos[s] = len(self.pos[s])
                 self.cur_parallel[s] = False

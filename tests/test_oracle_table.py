@@ -26,6 +26,9 @@ def _parse_examples(path):
             examples[w[1]] = cur
         elif w[0] == "history":
             cur["history"].append((w[1], [int(x) for x in w[2:]]))
+        elif w[0] == "owners":    # owner tags of slots first .. as they stand after the history so far
+            i = w.index(":")
+            cur["history"].append(("owners", [int(w[1])] + [int(x) for x in w[i + 1:]]))
         elif w[0] == "slot":
             i = w.index(":")
             slot, branch, stage, pos = (int(x) for x in w[1:i])
@@ -45,6 +48,12 @@ def _replay(history, blocks=8):
             metas.append(tt.append_parallel(args))
         elif op == "merge":
             tt.merge()
+        elif op == "owners":
+            first, tags = args[0], args[1:]
+            row = tt.slot_owner(16 * blocks)[0]
+            assert row[first:first + len(tags)].tolist() == tags, (row[:first + len(tags)], tags)
+            assert not row[:first].any() and not row[first + len(tags):].any()
+            assert int(tt.stage_base()[0]) == (first if tags else len(tt.pos[0]))
     return tt, metas
 
 
@@ -179,6 +188,16 @@ def _paradigm_history(tt):
     return tt.append_parallel([1, 1])
 
 
+def _empty_stage_history(tt):
+    """A stage that ends before any branch produced a token, then a main token and a second stage."""
+    tt.append_serial([2])
+    tt.open_parallel([2])
+    tt.merge()
+    tt.append_serial([1])
+    tt.open_parallel([2])
+    return tt.append_parallel([1, 1])
+
+
 def test_position_paradigms_worked_example(golden_dir):
     seen = 0
     for line in open(os.path.join(golden_dir, "position_paradigms.txt")):
@@ -187,17 +206,21 @@ def test_position_paradigms_worked_example(golden_dir):
             continue
         name, want = line.split("|")
         w = name.split()
+        history = _paradigm_history
+        if w[0] == "empty":
+            history, w = _empty_stage_history, w[1:]
         mode = (w[0], int(w[1])) if w[0] == "fix" else w[0]
         tt = TokenTable(np.arange(8, dtype=np.int32)[None, :], 16, pos_mode=mode)
-        meta = _paradigm_history(tt)
+        meta = history(tt)
+        T = len(tt.pos[0])
         assert tt.pos[0] == [int(x) for x in want.split()], (mode, tt.pos[0])
-        assert meta.position_ids.tolist() == tt.pos[0][8:10]
+        assert meta.position_ids.tolist() == tt.pos[0][T - 2:T]
         # what a token may see does not depend on the paradigm: the same sets as under Eq. 4
         ref = TokenTable(np.arange(8, dtype=np.int32)[None, :], 16)
-        _paradigm_history(ref)
-        assert (tt.dense_mask(0, range(10)) == ref.dense_mask(0, range(10))).all()
+        history(ref)
+        assert (tt.dense_mask(0, range(T)) == ref.dense_mask(0, range(T))).all()
         seen += 1
-    assert seen == 3
+    assert seen == 6
 
 
 def test_position_paradigms_properties():
