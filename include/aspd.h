@@ -75,8 +75,8 @@ extern "C" {
 #define ASPD_FAULT_OWNER_ROW   2 /* a sequence outgrew owner_stride                                   */
 #define ASPD_FAULT_ROW_COUNT   4 /* the sum of new_len exceeded aspd_step.NQ                          */
 #define ASPD_FAULT_BRANCHES    8 /* a sequence has more than ASPD_MAX_BRANCHES_PER_SEQ branches        */
-#define ASPD_FAULT_STAGE      16 /* main-branch tokens for a sequence whose branches are open, or a
-                                    running stage whose branch count changes                           */
+#define ASPD_FAULT_STAGE      16 /* main-branch tokens for a sequence whose parallel stage has not been
+                                    merged, or a running stage whose branch count changes             */
 #define ASPD_FAULT_INTERVAL   32 /* ASPD_POS_FIX_N: a branch would outgrow its interval of n positions  */
 
 /* The one reusable KV cache (paper: abstract, Sec. 2.3).  K and V each are
@@ -118,6 +118,13 @@ typedef struct aspd_state {
                                     Required (and kept up to date by aspd_build_branch_meta, from 0 for
                                     an empty sequence) for ASPD_POS_SAME_MAX and ASPD_POS_FIX_N, where it
                                     differs from seq_len; may be NULL for ASPD_POS_SAME_SEQ              */
+  int32_t*       stage_open_d;   /* [B] 1 while the sequence is in a parallel stage, tokens or not; 0 otherwise.
+                                    Set by aspd_renumber_branches (sequences that are given branches) and by
+                                    PARALLEL / MIXED appends, cleared by MERGE; a caller that opens a stage by
+                                    writing cu_branches itself sets it too.  Required for ASPD_POS_FIX_N, whose
+                                    intervals are spent when the stage opens (a stage that ends without a
+                                    token cannot be told from no stage by stage_base and seq_len); may be
+                                    NULL otherwise                                                        */
 } aspd_state;
 
 /* What one aspd_build_branch_meta call produces for the NQ tokens it appends (caller-allocated).
@@ -144,6 +151,8 @@ typedef struct aspd_step {
  *   be 0 (finished branch: its KV stays, it gets no query) or > 1 (chunk append).
  * SERIAL:   new_len_d[B]; main-branch token gets position = number of tokens already in the sequence
  *   (its flattened index); seq_len grows and stage_base follows it.  state->NB / branch arrays unused.
+ *   A sequence whose parallel stage has not been merged (stage_base < seq_len, or stage_open set) takes
+ *   no main-branch token: it is left as it is and ASPD_FAULT_STAGE is raised.
  * MERGE:    out may be NULL; stage_base[s] <- seq_len[s] for every sequence, or, when new_len_d is
  *   given, for the sequences with new_len_d[s] != 0 ([B]; Sec. 3.3: every response switches modes on
  *   its own).  No KV is read or written.

@@ -41,7 +41,8 @@ class aspd_kv(C.Structure):
 class aspd_state(C.Structure):
     _fields_ = [("B", C.c_int32), ("NB", C.c_int32), ("stage_base_d", C.c_void_p), ("seq_len_d", C.c_void_p),
                 ("cu_branches_d", C.c_void_p), ("branch_len_d", C.c_void_p), ("slot_owner_d", C.c_void_p),
-                ("owner_stride", C.c_int32), ("fault_d", C.c_void_p), ("main_pos_d", C.c_void_p)]
+                ("owner_stride", C.c_int32), ("fault_d", C.c_void_p), ("main_pos_d", C.c_void_p),
+                ("stage_open_d", C.c_void_p)]
 
 
 class aspd_step(C.Structure):
@@ -139,6 +140,7 @@ class BatchState:
         self.slot_owner = torch.zeros(B, self.owner_stride, dtype=torch.uint8, device=device)
         self.fault = torch.zeros(1, dtype=torch.int32, device=device)
         self.main_pos = torch.zeros(B, dtype=torch.int32, device=device)
+        self.stage_open = torch.zeros(B, dtype=torch.int32, device=device)
         self.pos_mode = POS_SAME_SEQ   # the position paradigm every metadata call on this state uses
 
     def open_parallel(self, cu_branches: torch.Tensor) -> None:
@@ -146,11 +148,13 @@ class BatchState:
         self.cu_branches = cu_branches.to(device=self.device, dtype=torch.int32)
         self.NB = int(cu_branches[-1])
         self.branch_len = torch.zeros(max(self.NB, 1), dtype=torch.int32, device=self.device)
+        # the caller opens the stage, so the caller marks it (see aspd_state.stage_open_d)
+        self.stage_open.copy_((self.cu_branches[1:] > self.cu_branches[:-1]).to(torch.int32))
 
     def struct(self) -> aspd_state:
         return aspd_state(self.B, self.NB, _ptr(self.stage_base), _ptr(self.seq_len), _ptr(self.cu_branches),
                           _ptr(self.branch_len), _ptr(self.slot_owner), self.owner_stride, _ptr(self.fault),
-                          _ptr(self.main_pos))
+                          _ptr(self.main_pos), _ptr(self.stage_open))
 
 
 class Step:
@@ -207,6 +211,7 @@ def aspd_renumber_branches(state: BatchState, new_cu_branches: torch.Tensor, str
     new_len = torch.zeros(max(new_nb, 1), dtype=torch.int32, device=state.device)
     if state.cu_branches is None:          # no branch has ever been open: nothing to carry over
         state.cu_branches, state.branch_len, state.NB = new_cu, new_len, new_nb
+        state.stage_open.copy_((new_cu[1:] > new_cu[:-1]).to(torch.int32))
         return
     sts = state.struct()
     rc = lib().aspd_renumber_branches(C.byref(sts), _ptr(new_cu), _ptr(new_len), _stream(stream))

@@ -1826,14 +1826,28 @@ int rows_per_group(const aspd_kv* kv, int max_new_per_seq, int* qpg, int* nt) {
   return cap;
 }
 
+// Compute units of the current device (256 when there is none to ask, as on a build host).
+constexpr int MAX_DEVICES = 64;
 int device_cu_count() {
-  static int cached = 0;
-  if (cached > 0) return cached;
+  static std::atomic<int> cached[MAX_DEVICES];
   int dev = 0, n = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (dev >= 0 && dev < MAX_DEVICES && (n = cached[dev].load(std::memory_order_relaxed)) > 0) return n;
   if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
-  cached = n;
+  if (dev >= 0 && dev < MAX_DEVICES) cached[dev].store(n, std::memory_order_relaxed);
   return n;
+}
+
+// Workgroups of the largest grid an attention launch uses on the current device.
+long grid_limit(int dtype, bool by_rows) {
+  long nwg = (dtype == ASPD_BF16 ? 1L : 2L) * device_cu_count();
+  if (by_rows) nwg = std::min(nwg, (long)MAX_WG_ROWS);
+  return std::min(nwg, (long)MAX_WG);
+}
+// Scratch a launch of `nwg` workgroups with row groups of `rows_cap` rows needs: the head (counters,
+// records) and two partial slots per workgroup.
+size_t scratch_need(int head_dim, long nwg, int rows_cap) {
+  return PARTIAL_OFFSET + (size_t)2 * nwg * rows_cap * (head_dim + 4) * sizeof(float);
 }
 
 // Process-wide cap of the attention grids (0: none), see aspd_set_max_workgroups.
@@ -1884,16 +1898,16 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   const int G_ = kv->num_q_heads / kv->num_kv_heads;
   // Calls that say so through the hint (a prefill through the serial call, say) take the same kernel.
   const bool many_rows = step->max_new_per_seq * G_ > 16 * NT_MAX;
-  const bool by_rows = kv->dtype == ASPD_BF16 && G_ <= 16 * NT_MAX &&
+  const bool by_rows = kv->dtype == ASPD_BF16 && G_ <= 16 * NT_MAX && (long)step->NQ * G_ > 16 * NT_MAX &&
                        (many_rows || (mode == MODE_CHUNK && step->max_new_per_seq == 0));
   if (by_rows) {
     rows_cap = ROWS_NW * 16 * ROWS_NT;
     qpg = rows_cap / G_;
   }
-  const size_t need = aspd_workspace_bytes(kv, state->B, step->NQ);
-  if (need == 0) return ASPD_ERR_INVALID_ARG;
+  if (aspd_workspace_bytes(kv, state->B, step->NQ) == 0) return ASPD_ERR_INVALID_ARG;
   if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
-  if (workspace_bytes < need) return ASPD_ERR_WORKSPACE;
+  const long nwg_limit = grid_limit(kv->dtype, by_rows);
+  if (workspace_bytes < scratch_need(kv->head_dim, nwg_limit, rows_cap)) return ASPD_ERR_WORKSPACE;
 
   AttnArgs a;
   a.kv = make_view(kv);
@@ -1927,8 +1941,7 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   // 4 waves for fp32), never more than the pages can feed.
   const long groups_max = (long)state->B + step->NQ / qpg;
   const long units_max = groups_max * kv->num_kv_heads * kv->max_blocks_per_seq;
-  long nwg = (kv->dtype == ASPD_BF16 ? 1L : 2L) * device_cu_count();
-  if (by_rows) nwg = std::min(nwg, (long)MAX_WG_ROWS);
+  long nwg = nwg_limit;
   // pages are read once when no sequence can have more than one row group
   const bool stream_once = step->max_new_per_seq > 0 && step->max_new_per_seq <= qpg;
   nwg = std::min(nwg, (units_max + MIN_PAGES_PER_WG - 1) / MIN_PAGES_PER_WG);
@@ -1989,13 +2002,15 @@ extern "C" size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ)
   if (kv->head_dim != 64 && kv->head_dim != 128) return 0;
   if (kv->dtype != ASPD_F32 && kv->dtype != ASPD_BF16) return 0;
   int qpg = 0, nt = 0;
-  const int rows_cap = rows_per_group(kv, 0, &qpg, &nt);  // the widest row group
+  const int rows_cap = rows_per_group(kv, 0, &qpg, &nt);  // the widest row group of the streaming kernels
   if (rows_cap == 0) return 0;
-  // two partial slots per workgroup of the largest grid any device would get, for whichever kernel
-  // needs more rows in total
-  size_t slot_rows = (size_t)2 * MAX_WG * rows_cap;
-  if (kv->dtype == ASPD_BF16) slot_rows = std::max(slot_rows, (size_t)2 * MAX_WG_ROWS * ROWS_NW * 16 * ROWS_NT);
-  return PARTIAL_OFFSET + slot_rows * (kv->head_dim + 4) * sizeof(float);
+  // two partial slots per workgroup of the largest grid of the current device (of a device with 256
+  // compute units when there is none), for whichever kernel the NQ rows may be given to
+  size_t need = scratch_need(kv->head_dim, grid_limit(kv->dtype, false), rows_cap);
+  const long G = kv->num_q_heads / kv->num_kv_heads;
+  if (kv->dtype == ASPD_BF16 && (long)NQ * G > 16 * NT_MAX && G <= 16 * NT_MAX)  // rows enough for the row-splitting kernel
+    need = std::max(need, scratch_need(kv->head_dim, grid_limit(kv->dtype, true), ROWS_NW * 16 * ROWS_NT));
+  return need;
 }
 
 namespace {

@@ -32,6 +32,7 @@ struct StateView {
   int32_t        owner_stride;
   int32_t*       fault;
   int32_t*       main_pos;
+  int32_t*       stage_open;
 };
 
 struct StepView {
@@ -53,7 +54,7 @@ static inline KvView make_view(const aspd_kv* kv) {
 }
 static inline StateView make_view(const aspd_state* st) {
   return StateView{st->B, st->NB, st->stage_base_d, st->seq_len_d, st->cu_branches_d, st->branch_len_d,
-                   st->slot_owner_d, st->owner_stride, st->fault_d, st->main_pos_d};
+                   st->slot_owner_d, st->owner_stride, st->fault_d, st->main_pos_d, st->stage_open_d};
 }
 static inline StepView make_view(const aspd_step* sp) {
   return StepView{sp->NQ, sp->max_new_per_seq, sp->cu_new_d, sp->cu_seq_new_d, sp->q_seq_d, sp->q_branch_d, sp->position_ids_d,

@@ -83,7 +83,10 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
     bool ok = true;
     if ((long)T + c_main > (long)kv.max_blocks_per_seq * ASPD_BLOCK) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE); }
     if (base + c_main > sp.NQ) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_ROW_COUNT); }
-    if (c_main > 0 && L != T) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_STAGE); }  // unmerged stage
+    if (c_main > 0 && (L != T || (st.stage_open && st.stage_open[s]))) {  // unmerged stage
+      ok = false;
+      if (tid == 0) raise_fault(st.fault, ASPD_FAULT_STAGE);
+    }
     if (!ok || c_main == 0) return;
     for (int idx = tid; idx < c_main; idx += META_THREADS) {
       const int row = base + idx;
@@ -108,6 +111,7 @@ __global__ __launch_bounds__(META_THREADS) void meta_parallel_kernel(KvView kv, 
     if (tid == 0) raise_fault(st.fault, ASPD_FAULT_STAGE);
     return;
   }
+  if (tid == 0 && st.stage_open) st.stage_open[s] = 1;  // named with branches: in a parallel stage, tokens or not
 
   // scan over the sequence's own branches (K <= 255: one branch per thread, serial scan by thread 0
   // would do, but a log-step scan keeps the launch short for wide stages)
@@ -191,7 +195,9 @@ __global__ __launch_bounds__(META_THREADS) void meta_serial_kernel(KvView kv, St
   const int base = block_sum(part, red);
   const int c = new_len[s];
   const int T = st.seq_len[s];
+  const int L = st.stage_base[s];
   const int P = same_seq ? T : st.main_pos[s];
+  const bool open = st.stage_open && st.stage_open[s];
   if (tid == 0) {
     sp.cu_new[s] = base;
     sp.cu_seq_new[s] = base;
@@ -203,6 +209,9 @@ __global__ __launch_bounds__(META_THREADS) void meta_serial_kernel(KvView kv, St
   bool ok = true;
   if ((long)T + c > (long)kv.max_blocks_per_seq * ASPD_BLOCK) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_BLOCK_TABLE); }
   if (base + c > sp.NQ) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_ROW_COUNT); }
+  // A main-branch token under a parallel stage that has not been merged would take a position inside the
+  // branches' range (Eq. 4 case 1 counts the tokens of finished stages only): refuse the sequence.
+  if (c > 0 && (L != T || open)) { ok = false; if (tid == 0) raise_fault(st.fault, ASPD_FAULT_STAGE); }
   if (!ok) return;
   for (int idx = tid; idx < c; idx += META_THREADS) {
     const int row = base + idx;
@@ -232,22 +241,30 @@ __global__ void meta_merge_kernel(StateView st, const int32_t* __restrict__ whic
   if (s >= st.B || (which && which[s] == 0)) return;
   const int T = st.seq_len[s];
   const bool running = st.stage_base[s] < T;
+  const bool open = st.stage_open ? st.stage_open[s] != 0 : running;
   st.stage_base[s] = T;
+  if (st.stage_open) st.stage_open[s] = 0;
   if (!st.main_pos) return;
   // where the main branch continues (Sec. 4.5.3)
   if (same_seq) {
     st.main_pos[s] = T;
-  } else if (running && st.cu_branches) {
+  } else if (st.cu_branches) {
     const int b0 = st.cu_branches[s], K = st.cu_branches[s + 1] - b0;
-    int longest = 0;
-    for (int k = 0; k < K; ++k) longest = max(longest, st.branch_len[b0 + k]);
-    st.main_pos[s] += fix_n > 0 ? K * fix_n : longest;
+    if (fix_n > 0) {
+      // the K intervals were allotted when the stage opened and are spent, tokens or not
+      if (open) st.main_pos[s] += K * fix_n;
+    } else if (running) {
+      int longest = 0;
+      for (int k = 0; k < K; ++k) longest = max(longest, st.branch_len[b0 + k]);
+      st.main_pos[s] += longest;  // right after the largest position a branch reached
+    }
   }
 }
 
 // Branch numbering changes when sequences open or end stages at different times: the tokens held by
 // the branches of stages still running move to their branches' new indices, every other entry starts
 // at zero.  A stage is running while stage_base < seq_len (one that holds no token yet has only zeros).
+// Every sequence that is given branches is in a parallel stage from here on (stage_open).
 __global__ void meta_renumber_kernel(StateView st, const int32_t* __restrict__ new_cu,
                                      int32_t* __restrict__ new_len_held) {
   const int s = blockIdx.x;
@@ -259,6 +276,7 @@ __global__ void meta_renumber_kernel(StateView st, const int32_t* __restrict__ n
     return;
   }
   for (int k = threadIdx.x; k < k_new; k += blockDim.x) new_len_held[n0 + k] = running ? st.branch_len[o0 + k] : 0;
+  if (threadIdx.x == 0 && st.stage_open) st.stage_open[s] = k_new > 0 ? 1 : 0;
 }
 
 }  // namespace
@@ -285,6 +303,7 @@ extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int3
   const int fix_n = (pos_mode & 0xff) == 2 ? (pos_mode >> 8) : 0;
   if (!same_seq && pos_mode != ASPD_POS_SAME_MAX && fix_n <= 0) return ASPD_ERR_UNSUPPORTED;
   if (!same_seq && !state->main_pos_d) return ASPD_ERR_INVALID_ARG;
+  if (fix_n > 0 && !state->stage_open_d) return ASPD_ERR_INVALID_ARG;
   hipStream_t hs = (hipStream_t)stream;
   StateView sv = make_view(state);
 

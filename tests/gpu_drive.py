@@ -23,7 +23,7 @@ class GpuBatch:
         self.kv = A.KVCache(k.to(self.dev), v.to(self.dev),
                             torch.from_numpy(wl.block_tables).to(self.dev), wl.num_q_heads)
         self.state = A.BatchState(wl.B, wl.max_blocks_per_seq * wl.block_size, self.dev)
-        self.workspace = A.new_workspace(self.kv, wl.B, 1)
+        self.workspace = A.new_workspace(self.kv, wl.B, 1 << 20)   # any number of rows, chunk calls included
 
     def _dev_i32(self, x):
         return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(self.dev)
@@ -95,4 +95,5 @@ def assert_state_equal(gb, tt):
     own_o = tt.slot_owner(st.owner_stride)
     for s in range(gb.wl.B):
         assert np.array_equal(own_g[s, L[s]:T[s]], own_o[s, L[s]:T[s]]), s
+    assert st.stage_open.cpu().numpy().astype(bool).tolist() == [bool(x) for x in tt.cur_parallel]
     assert gb.fault() == 0

@@ -439,7 +439,7 @@ def test_position_paradigms_of_the_ablation(A, mode):
     held = [0] * B                                # tokens in the longest branch of the running stage
     budget = [4 * 40 - 8] * B
     for it in range(14):
-        ending = [K[s] > 0 and held[s] > 0 and rng.random() < 0.3 for s in range(B)]
+        ending = [K[s] > 0 and rng.random() < 0.3 for s in range(B)]   # also stages that hold no token yet
         if any(ending):
             tt.merge(ending)
             gb.merge(ending)
@@ -476,6 +476,61 @@ def test_position_paradigms_of_the_ablation(A, mode):
         assert_state_equal(gb, tt)
         assert np.array_equal(gb.state.main_pos.cpu().numpy(), np.array(tt.next_main_pos, dtype=np.int32))
     assert gb.fault() == 0
+
+
+@pytest.mark.parametrize("mode,want", [("same_seq", [0, 1, 2, 3, 3]), ("same_max", [0, 1, 2, 3, 3]),
+                                       (("fix", 4), [0, 1, 10, 11, 15])])
+def test_stage_that_ends_without_a_token(A, mode, want):
+    """The hand-derived lines "empty ..." of tests/golden/position_paradigms.txt, replayed on the GPU: a
+    stage is opened and merged before any branch produced a token; fixed intervals stay spent
+    (Sec. 4.5.3, "pre-allocated"), the other paradigms continue where the main branch stood."""
+    from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
+    wl = W.random_small(seed=73, dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=4, batch=1,
+                        prefix_range=(2, 2), branches_range=(2, 2), branch_len_range=(4, 4))
+    gb = GpuBatch(wl)
+    gb.state.pos_mode = {"same_seq": A.POS_SAME_SEQ, "same_max": A.POS_SAME_MAX}.get(mode) if isinstance(mode, str) \
+        else A.POS_FIX_N(mode[1])
+    tt = TokenTable(wl.block_tables, wl.block_size, pos_mode=mode)
+    got = []
+    for op, arg in (("serial", [2]), ("open", [2]), ("merge", None), ("serial", [1]), ("open", [2]), ("step", [1, 1])):
+        if op == "serial":
+            meta, step = tt.append_serial(arg), gb.serial(arg)
+        elif op == "open":
+            tt.open_parallel(arg)
+            gb.renumber(arg)
+            continue
+        elif op == "merge":
+            tt.merge()
+            gb.merge()
+            assert_state_equal(gb, tt)
+            continue
+        else:
+            meta, step = tt.append_parallel(arg), gb.parallel(arg)
+        assert_step_equal(step, meta)
+        got += step.position_ids.cpu().numpy()[:meta.NQ].tolist()
+    assert got == want
+    assert_state_equal(gb, tt)
+    assert np.array_equal(gb.state.main_pos.cpu().numpy(), np.array(tt.next_main_pos, dtype=np.int32))
+
+
+def test_serial_rejects_main_tokens_under_an_unmerged_stage(A):
+    """Main-branch tokens through the SERIAL stage for a sequence whose branches hold tokens that have not
+    been merged: the sequence is left as it was (its position would fall into the branches' range)."""
+    from gpu_drive import GpuBatch
+    wl = W.random_small(seed=32, dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=4, batch=2,
+                        branches_range=(2, 2))
+    gb = GpuBatch(wl)
+    gb.serial(wl.prefix_len)
+    gb.renumber([2, 0])
+    gb.mixed([1, 1], [0, 0])
+    assert gb.fault() == 0
+    before = gb.state.seq_len.cpu().numpy().copy()
+    base = gb.state.stage_base.cpu().numpy().copy()
+    gb.serial(np.array([1, 1], dtype=np.int32))   # sequence 0 is still in its parallel stage
+    after = gb.state.seq_len.cpu().numpy()
+    assert gb.fault() & A.FAULT_STAGE
+    assert after[0] == before[0] and after[1] == before[1] + 1
+    assert gb.state.stage_base.cpu().numpy()[0] == base[0]
 
 
 def test_fixed_interval_overflow_is_refused(A):
