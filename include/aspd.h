@@ -49,6 +49,8 @@ extern "C" {
 #define ASPD_ERR_UNSUPPORTED (-2) /* dtype / head_dim / block_size / head ratio / batch limits */
 #define ASPD_ERR_WORKSPACE   (-3) /* workspace_bytes below aspd_workspace_bytes(...)           */
 #define ASPD_ERR_HIP         (-4) /* a HIP call or launch failed                               */
+#define ASPD_ERR_SCRATCH_LIMIT (-5) /* aspd_attn_parallel_decode_static: the call needs more scratch
+                                       than ASPD_STATIC_SCRATCH_BYTES                             */
 
 #define ASPD_F32  0 /* fp32 in, fp32 accumulate, fp32 out                                 */
 #define ASPD_BF16 1 /* bf16 in, fp32 accumulate, bf16 out (round to nearest even)         */
@@ -236,6 +238,20 @@ ASPD_API int aspd_attn_branch_chunk(const aspd_kv* kv, const aspd_state* state, 
 ASPD_API int aspd_attn_serial_decode(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
                             const void* q_d, void* out_d, float* lse_d, float sm_scale,
                             void* workspace_d, size_t workspace_bytes, void* stream);
+
+/* aspd_attn_parallel_decode for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace,
+ * same results.  The scratch is an array inside the library's code object, ASPD_STATIC_SCRATCH_BYTES per
+ * device, held from the first use on that device until the process ends; the call allocates and frees
+ * nothing.  A call whose grid and row groups need more (ASPD_ERR_SCRATCH_LIMIT; on a device of 256 compute
+ * units every step with up to 48 query rows per sequence and KV head fits, as does any fp32 step) has to
+ * go through aspd_attn_parallel_decode with a workspace.  All calls on one device share the one array:
+ * two of them must not run concurrently (they would mix their partial results), and the first call on a
+ * device looks the array's address up, so make it outside graph capture. */
+#define ASPD_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+ASPD_API int aspd_attn_parallel_decode_static(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
+                                              const void* q_d, void* out_d, float* lse_d, float sm_scale,
+                                              void* stream);
 
 /* Measurement aid, not part of the method: enqueues one plain, fully coalesced read of
  * bytes / 16 * 16 bytes from src_d (16-byte aligned) and writes one 32-bit word per workgroup to

@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libaspd.so")
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_SCRATCH_LIMIT = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
 STAGE_PARALLEL, STAGE_SERIAL, STAGE_MERGE, STAGE_MIXED = 0, 1, 2, 3
 POS_SAME_SEQ, POS_SAME_MAX = 0, 1
@@ -28,7 +28,8 @@ FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES, FAULT_STAGE
 
 EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_rope_append", "aspd_set_max_workgroups",
            "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
-           "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_probe_read_bandwidth", "aspd_status_string")
+           "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_attn_parallel_decode_static",
+           "aspd_probe_read_bandwidth", "aspd_status_string")
 
 
 class aspd_kv(C.Structure):
@@ -84,6 +85,9 @@ def lib() -> C.CDLL:
             fn.restype = C.c_int
             fn.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_state), C.POINTER(aspd_step), C.c_void_p,
                            C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.aspd_attn_parallel_decode_static.restype = C.c_int
+        L.aspd_attn_parallel_decode_static.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_state), C.POINTER(aspd_step),
+                                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
         L.aspd_workspace_init.restype = C.c_int
         L.aspd_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.aspd_probe_read_bandwidth.restype = C.c_int
@@ -263,6 +267,17 @@ def aspd_attn_branch_chunk(kv, state, step, q, workspace, out=None, lse=None, sm
 
 def aspd_attn_serial_decode(kv, state, step, q, workspace, out=None, lse=None, sm_scale=0.0, stream=None):
     return _attn("aspd_attn_serial_decode", kv, state, step, q, out, lse, sm_scale, workspace, stream)
+
+
+def aspd_attn_parallel_decode_static(kv, state, step, q, out, lse=None, sm_scale=0.0, stream=None):
+    """See aspd.h: parallel decode on the library's own static scratch.  `out` is the caller's (nothing is
+    allocated here either)."""
+    kvs, sts, sps = kv.struct(), state.struct(), step.struct()
+    rc = lib().aspd_attn_parallel_decode_static(C.byref(kvs), C.byref(sts), C.byref(sps), _ptr(q), _ptr(out), _ptr(lse),
+                                                C.c_float(sm_scale), _stream(stream))
+    if rc != OK:
+        raise AspdError(rc, "aspd_attn_parallel_decode_static")
+    return out
 
 
 def aspd_workspace_init(workspace: torch.Tensor, stream=None) -> None:

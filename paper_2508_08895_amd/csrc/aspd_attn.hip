@@ -2090,3 +2090,40 @@ extern "C" int aspd_attn_serial_decode(const aspd_kv* kv, const aspd_state* stat
   return attn_launch(MODE_SERIAL, kv, state, step, q_d, out_d, lse_d, sm_scale, workspace_d, workspace_bytes,
                      stream);
 }
+
+// ---------------------------------------------------------------------------------------------
+// Parallel decode for callers that cannot allocate: the scratch is an array of the code object itself,
+// one copy per device, alive until the process ends.  It starts zeroed (which is what a prepared
+// workspace looks like) and every attention launch leaves its counters at zero again.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[ASPD_STATIC_SCRATCH_BYTES];
+
+namespace {
+// Device address of `scratch` on the current device (the array's name is only a host-side handle).
+int static_scratch(void** out) {
+  static std::mutex mu;
+  static void* ptrs[MAX_DEVICES];
+  int dev = 0;
+  ASPD_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return ASPD_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    void* p = nullptr;
+    ASPD_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255)) return ASPD_ERR_HIP;
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return ASPD_OK;
+}
+}  // namespace
+
+extern "C" int aspd_attn_parallel_decode_static(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
+                                                const void* q_d, void* out_d, float* lse_d, float sm_scale,
+                                                void* stream) {
+  void* ws = nullptr;
+  int rc = static_scratch(&ws);
+  if (rc != ASPD_OK) return rc;
+  rc = attn_launch(MODE_PARALLEL, kv, state, step, q_d, out_d, lse_d, sm_scale, ws, ASPD_STATIC_SCRATCH_BYTES, stream);
+  return rc == ASPD_ERR_WORKSPACE ? ASPD_ERR_SCRATCH_LIMIT : rc;
+}

@@ -358,6 +358,7 @@ extern "C" const char* aspd_status_string(int status) {
     case ASPD_ERR_UNSUPPORTED: return "unsupported configuration";
     case ASPD_ERR_WORKSPACE: return "workspace too small";
     case ASPD_ERR_HIP: return "HIP call failed";
+    case ASPD_ERR_SCRATCH_LIMIT: return "call needs more scratch than the library's static array holds";
     default: return "unknown status";
   }
 }
