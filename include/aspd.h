@@ -137,6 +137,9 @@ typedef struct aspd_step {
   int32_t  max_new_per_seq; /* host: upper bound of the tokens this step appends to any ONE sequence,
                                0 = unknown.  A tuning hint for the attention calls only (it sizes the
                                row tile); results do not depend on it, even when it is wrong.        */
+  int32_t  max_workgroups;  /* host: most workgroups an attention launch of this step may use, for callers
+                               that run other kernels next to attention and want compute units left for
+                               them; 0 = one per compute unit (two for fp32).  Results do not depend on it. */
   int32_t* cu_new_d;        /* [NB+1] (PARALLEL) or [B+1] (SERIAL): first row of each branch / sequence */
   int32_t* cu_seq_new_d;    /* [B+1] first row of each sequence                                    */
   int32_t* q_seq_d;         /* [NQ] sequence of the token                                          */
@@ -145,6 +148,16 @@ typedef struct aspd_step {
   int32_t* logical_slot_d;  /* [NQ]                                                                */
   int64_t* slot_mapping_d;  /* [NQ] physical slot: where the caller writes the token's K and V      */
   int32_t* kv_len_d;        /* [NQ] number of keys the token attends to, itself included           */
+  int32_t* plan_d;          /* nullable, 256-byte aligned, plan_bytes >= aspd_plan_bytes(kv, B, NQ): the plan of
+                               the step's attention launches (which workgroup reads which pages for which
+                               rows), written by aspd_build_branch_meta and read by every attention call of
+                               the step, i.e. by all layers.  Without it each attention call works the plan
+                               out itself (one more small kernel per call)                              */
+  size_t   plan_bytes;
+  uint64_t plan_key;        /* host, written by aspd_build_branch_meta: the launch shape the plan in plan_d
+                               was built for (0: none).  An attention call whose shape differs (the two
+                               hints above were changed, or aspd_attn_branch_chunk is called on a step that
+                               gives no max_new_per_seq) ignores the plan and builds its own           */
 } aspd_step;
 
 /* Sec. 3.2 Eq. 4 and the bookkeeping behind Eq. 2-3; Sec. 3.3 for the stage switches.
@@ -164,7 +177,11 @@ typedef struct aspd_step {
  *   sequence-major; out->cu_new_d [NB+1] holds the first row of every branch, then NQ.  The attention
  *   call for such a step is aspd_attn_parallel_decode or aspd_attn_branch_chunk.
  * pos_mode: one of ASPD_POS_*, the same in every call on a state.  out->NQ must equal the sum of new_len (known to the caller;
- * rows beyond it are dropped and ASPD_FAULT_ROW_COUNT is raised). */
+ * rows beyond it are dropped and ASPD_FAULT_ROW_COUNT is raised).
+ * When out->plan_d is given, a second small kernel writes the step's attention plan there, for the launch
+ * shape that out->max_new_per_seq and out->max_workgroups select, and out->plan_key (a HOST field of the
+ * caller's struct, the only one the library writes) names that shape.  The plan holds copies of block-table
+ * entries; the attention kernels check them against the block table they are given. */
 ASPD_API int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int32_t stage, int32_t pos_mode,
                            const int32_t* new_len_d, aspd_step* out, void* stream);
 
@@ -189,28 +206,19 @@ ASPD_API int aspd_renumber_branches(const aspd_state* state, const int32_t* new_
 ASPD_API int aspd_rope_append(const aspd_kv* kv, const aspd_step* step, void* q_d, const void* k_new_d,
                               const void* v_new_d, float rope_theta, void* stream);
 
-/* Caps the number of workgroups (one per compute unit for bf16, two for fp32) an attention launch may
- * use, for callers that run other kernels next to the attention calls and want compute units left for
- * them.  Process-wide, takes effect with the next attention call; 0 (the default) removes the cap.
- * Results do not depend on it.  Returns the previous value. */
-ASPD_API int32_t aspd_set_max_workgroups(int32_t max_workgroups);
-
-/* Bytes of device scratch the attention calls need: arrival counters, the per-workgroup records
- * described with aspd_workspace_init, and the partial softmax results of split key ranges
- * (host-only computation, needs no GPU).  Returns 0 on invalid arguments. */
+/* Bytes of device scratch the attention calls of a step with NQ rows need at most: arrival counters, room
+ * for a plan, and the partial softmax results of split key ranges (host-only computation; sized for the
+ * current device's compute units, for 256 of them when there is no device).  Returns 0 on invalid arguments. */
 ASPD_API size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ);
 
+/* Bytes a step's plan buffer (aspd_step.plan_d) needs at most for B sequences and NQ rows (host-only). */
+ASPD_API size_t aspd_plan_bytes(const aspd_kv* kv, int32_t B, int32_t NQ);
+
 /* Prepares a freshly allocated workspace (256-byte aligned, at least aspd_workspace_bytes): enqueues
- * a small kernel that clears the arrival counters and the records at its head.  Call once after
- * allocation, on the stream (or ordered before the stream) of the first attention call.  Attention
- * calls leave the counters cleared, so one workspace serves any number of calls, one at a time: two
- * attention calls that run concurrently must not share a workspace.
- * Between calls the workspace belongs to the library: every workgroup of an attention launch leaves a
- * record of the key range it had, and the next launch that finds the batch unchanged in everything
- * its schedule depends on (typical of a decoding loop, layer after layer and step after step) starts
- * from the record instead of working the schedule out again.  Calls with any other batch, shape or
- * entry point may follow one another on the same workspace in any order; nothing but the library may
- * write to it (or call aspd_workspace_init again after doing so). */
+ * a small kernel that clears the arrival counters at its head.  Call once after allocation, on the stream
+ * (or ordered before the stream) of the first attention call.  Attention calls leave the counters
+ * cleared, so one workspace serves any number of calls, one at a time: two attention calls that run
+ * concurrently must not share a workspace.  Nothing else in the workspace outlives a call. */
 ASPD_API int aspd_workspace_init(void* workspace_d, size_t workspace_bytes, void* stream);
 
 /* Sec. 3.2 Eq. 1-3, "The Parallel Branch's Perspective"; Sec. 3.3.  One new token per active branch

@@ -26,7 +26,7 @@ def POS_FIX_N(n: int) -> int:
 
 FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES, FAULT_STAGE, FAULT_INTERVAL = 1, 2, 4, 8, 16, 32
 
-EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_rope_append", "aspd_set_max_workgroups",
+EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_rope_append", "aspd_plan_bytes",
            "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
            "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_attn_parallel_decode_static",
            "aspd_probe_read_bandwidth", "aspd_status_string")
@@ -47,9 +47,11 @@ class aspd_state(C.Structure):
 
 
 class aspd_step(C.Structure):
-    _fields_ = [("NQ", C.c_int32), ("max_new_per_seq", C.c_int32), ("cu_new_d", C.c_void_p), ("cu_seq_new_d", C.c_void_p),
+    _fields_ = [("NQ", C.c_int32), ("max_new_per_seq", C.c_int32), ("max_workgroups", C.c_int32),
+                ("cu_new_d", C.c_void_p), ("cu_seq_new_d", C.c_void_p),
                 ("q_seq_d", C.c_void_p), ("q_branch_d", C.c_void_p), ("position_ids_d", C.c_void_p),
-                ("logical_slot_d", C.c_void_p), ("slot_mapping_d", C.c_void_p), ("kv_len_d", C.c_void_p)]
+                ("logical_slot_d", C.c_void_p), ("slot_mapping_d", C.c_void_p), ("kv_len_d", C.c_void_p),
+                ("plan_d", C.c_void_p), ("plan_bytes", C.c_size_t), ("plan_key", C.c_uint64)]
 
 
 class AspdError(RuntimeError):
@@ -76,8 +78,8 @@ def lib() -> C.CDLL:
         L.aspd_rope_append.restype = C.c_int
         L.aspd_rope_append.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_step), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_float, C.c_void_p]
-        L.aspd_set_max_workgroups.restype = C.c_int32
-        L.aspd_set_max_workgroups.argtypes = [C.c_int32]
+        L.aspd_plan_bytes.restype = C.c_size_t
+        L.aspd_plan_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
         L.aspd_workspace_bytes.restype = C.c_size_t
         L.aspd_workspace_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
         for name in ("aspd_attn_parallel_decode", "aspd_attn_branch_chunk", "aspd_attn_serial_decode"):
@@ -164,9 +166,12 @@ class BatchState:
 class Step:
     """Outputs of one aspd_build_branch_meta call (device arrays sized for NQ rows)."""
 
-    def __init__(self, NQ: int, n_cu: int, B: int, device, max_new_per_seq: int = 0):
+    def __init__(self, NQ: int, n_cu: int, B: int, device, max_new_per_seq: int = 0, max_workgroups: int = 0):
         self.NQ = int(NQ)
         self.max_new_per_seq = int(max_new_per_seq)   # tuning hint, 0 = unknown
+        self.max_workgroups = int(max_workgroups)     # cap of the attention grids, 0 = none
+        self.plan = None                              # device buffer for the step's plan (see aspd_step.plan_d)
+        self.plan_key = 0                             # as aspd_build_branch_meta left it
         i32 = dict(dtype=torch.int32, device=device)
         n = max(self.NQ, 1)
         self.cu_new = torch.zeros(n_cu + 1, **i32)
@@ -179,16 +184,18 @@ class Step:
         self.kv_len = torch.zeros(n, **i32)
 
     def struct(self) -> aspd_step:
-        return aspd_step(self.NQ, self.max_new_per_seq, _ptr(self.cu_new), _ptr(self.cu_seq_new), _ptr(self.q_seq), _ptr(self.q_branch),
-                         _ptr(self.position_ids), _ptr(self.logical_slot), _ptr(self.slot_mapping),
-                         _ptr(self.kv_len))
+        plan_bytes = 0 if self.plan is None else self.plan.numel() * self.plan.element_size()
+        return aspd_step(self.NQ, self.max_new_per_seq, self.max_workgroups, _ptr(self.cu_new), _ptr(self.cu_seq_new),
+                         _ptr(self.q_seq), _ptr(self.q_branch), _ptr(self.position_ids), _ptr(self.logical_slot),
+                         _ptr(self.slot_mapping), _ptr(self.kv_len), _ptr(self.plan), plan_bytes, self.plan_key)
 
 
 def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: torch.Tensor | None,
                            NQ: int = 0, step: Step | None = None, stream=None,
-                           max_new_per_seq: int = 0) -> Step | None:
+                           max_new_per_seq: int = 0, max_workgroups: int = 0, plan: bool = True) -> Step | None:
     """See aspd.h.  `NQ` = sum of new_len, known to the caller.  Returns the Step (None for MERGE,
-    where new_len, if given, says per sequence whether its stage ends)."""
+    where new_len, if given, says per sequence whether its stage ends).  `plan`: give the step a plan
+    buffer (allocated here on the step's first use) so that the attention calls start from the plan."""
     kvs, sts = kv.struct(), state.struct()
     if stage == STAGE_MERGE:
         rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, state.pos_mode, _ptr(new_len), None,
@@ -198,12 +205,15 @@ def aspd_build_branch_meta(kv: KVCache, state: BatchState, stage: int, new_len: 
         return None
     if step is None:
         step = Step(NQ, state.B if stage == STAGE_SERIAL else state.NB, state.B, state.device,
-                    max_new_per_seq)
+                    max_new_per_seq, max_workgroups)
+    if plan and step.plan is None and step.NQ > 0:
+        step.plan = torch.empty(aspd_plan_bytes(kv, state.B, step.NQ), dtype=torch.uint8, device=state.device)
     sps = step.struct()
     rc = lib().aspd_build_branch_meta(C.byref(kvs), C.byref(sts), stage, state.pos_mode, _ptr(new_len),
                                       C.byref(sps), _stream(stream))
     if rc != OK:
         raise AspdError(rc, "aspd_build_branch_meta")
+    step.plan_key = int(sps.plan_key)   # the one host field the library writes
     return step
 
 
@@ -235,14 +245,14 @@ def aspd_rope_append(kv: KVCache, step: Step, q: torch.Tensor, k_new: torch.Tens
     return q
 
 
-def aspd_set_max_workgroups(n: int) -> int:
-    """See aspd.h: process-wide cap of the attention grids (0 = none).  Returns the previous value."""
-    return int(lib().aspd_set_max_workgroups(int(n)))
-
-
 def aspd_workspace_bytes(kv: KVCache, B: int, NQ: int) -> int:
     kvs = kv.struct()
     return int(lib().aspd_workspace_bytes(C.byref(kvs), B, NQ))
+
+
+def aspd_plan_bytes(kv: KVCache, B: int, NQ: int) -> int:
+    kvs = kv.struct()
+    return int(lib().aspd_plan_bytes(C.byref(kvs), B, NQ))
 
 
 def _attn(name, kv, state, step, q, out, lse, sm_scale, workspace, stream):

@@ -1,6 +1,6 @@
 // Branch-isolated attention over a paged KV cache for gfx950 (ASPD Sec. 3.2 Eq. 1-3, Sec. 3.3).
 //
-// The three attention entry points share one rule, one schedule and one way of combining partial
+// The three attention entry points share one rule, one plan and one way of combining partial
 // results; two bf16 kernels (one that streams keys past few rows, one that splits many rows among its
 // waves) and an fp32 kernel apply it.  A query row q of sequence s sees key slot j iff
 //     j <= slot(q)  and  ( j < stage_base[s]  or  tag(q) == 0  or  slot_owner[s][j] == tag(q) )
@@ -11,20 +11,20 @@
 // they bring.
 //
 // Work decomposition: the (sequence, row group, KV head, page) space is flattened; every workgroup
-// takes an equal contiguous share of pages and walks the segments in it.  All rows of a row group
-// (the active branches of the sequence times the query heads of the KV-head's group) are processed
-// against a KV page while it is in the workgroup's LDS, so the shared prefix is fetched once for all
-// branches.  A segment that covers its item completely writes the output; otherwise it writes an
-// unnormalised partial (running max, sum, accumulator); the workgroup that delivers the last partial
+// takes a contiguous share of pages and walks the segments in it.  Which workgroup takes what is the
+// step's plan (aspd_plan.h): a kernel only loads its workgroup's header and starts.  All rows of a row
+// group (the active branches of the sequence times the query heads of the KV-head's group) are
+// processed against a KV page while it is in the workgroup's LDS, so the shared prefix is fetched once
+// for all branches.  A segment that covers its item completely writes the output; otherwise it writes
+// an unnormalised partial (running max, sum, accumulator); the workgroup that delivers the last partial
 // of an item combines them, in the same launch.
 #include <algorithm>
-#include <atomic>
 #include <cmath>
 #include <mutex>
 #include <set>
 #include <utility>
 
-#include "aspd_common.h"
+#include "aspd_plan.h"
 
 namespace {
 
@@ -34,56 +34,13 @@ constexpr int THREADS = NW * 64;
 // registers each) and one pair of pages in flight per wave, 64 KB per compute unit.  Measured: deeper
 // prefetch (rings of 2 or 3 pairs per wave) and 8 waves both lower the read rate of the whole device
 // and make it uneven between the XCDs; the ring depth stays a template parameter.
-#ifndef ASPD_TUNE_NW1
-#define ASPD_TUNE_NW1 4
-#define ASPD_TUNE_PF1 1
-#endif
-#ifndef ASPD_TUNE_NW2
-#define ASPD_TUNE_NW2 4
-#endif
-#define BF16_NW(NT_) ((NT_) == 1 ? ASPD_TUNE_NW1 : ((NT_) == 2 ? ASPD_TUNE_NW2 : 4))
-#ifndef ASPD_TUNE_PF2
-#define ASPD_TUNE_PF2 1
-#define ASPD_TUNE_PF3 1
-#endif
-#define BF16_PF(NT_) ((NT_) == 1 ? ASPD_TUNE_PF1 : ((NT_) == 2 ? ASPD_TUNE_PF2 : ASPD_TUNE_PF3))
-constexpr int NT_MAX = 3;             // 16-row MFMA tiles per row group (bf16 path)
+constexpr int STREAM_NW = 4;
+constexpr int STREAM_PF = 1;
 constexpr int BF16_ROWS = 16 * NT_MAX;
-constexpr int F32_ROWS = 4;           // rows per row group (fp32 vector path)
-constexpr int MIN_PAGES_PER_WG = 16;  // do not split finer than this
-#ifndef ASPD_TUNE_PAD
-#define ASPD_TUNE_PAD 32
-#endif
-constexpr int PAD_STREAM = ASPD_TUNE_PAD;  // virtual units per item start, bandwidth-bound kernel at D = 128
-constexpr int PAD_COMPUTE = 8;             // the same for the compute-bound kernels
-#ifndef ASPD_TUNE_ROWS_NW
-#define ASPD_TUNE_ROWS_NW 8
-#endif
-constexpr int ROWS_NW = ASPD_TUNE_ROWS_NW;            // waves per workgroup of the row-splitting (chunk) kernel
-#ifndef ASPD_TUNE_ROWS_NT
-#define ASPD_TUNE_ROWS_NT 2
-#endif
-constexpr int ROWS_NT = ASPD_TUNE_ROWS_NT;            // 16-row tiles per wave there (Q operands and accumulators in 256 registers)
-#ifndef ASPD_TUNE_RD
-#define ASPD_TUNE_RD 1
-#endif
-constexpr int ROWS_PREFETCH = ASPD_TUNE_RD;  // groups of pages that kernel keeps on their way per workgroup
-#ifndef ASPD_TUNE_PPS
-#define ASPD_TUNE_PPS 2
-#endif
-constexpr int ROWS_PPS = ASPD_TUNE_PPS;      // pairs of pages it stages (and computes) between two barriers
-constexpr int MAX_WG_ROWS = 256;      // its largest grid (its partial slots are ROWS_NW * 16 * ROWS_NT rows each)
+constexpr int ROWS_PREFETCH = 1;      // groups of pages the row-splitting kernel keeps on their way per workgroup
+constexpr int ROWS_PPS = 2;           // pairs of pages it stages (and computes) between two barriers
 constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
-constexpr int RECORD_INTS = 128;      // per workgroup, in ints:
-constexpr int REC_IDS = 4;            //   0: a segment (16 bytes);  4: two block ids per wave
-constexpr int REC_ITEM = 12;          //  12: first and last workgroup of the segment's item, its pages, its prefix pages
-constexpr int REC_SIG = 16;           //  16: the launch constants the schedule depends on (0: none recorded)
-constexpr int REC_SEQ = 32;           //  32: per sequence (FAST_B of them): pages, prefix pages, first row, end row
-constexpr int FAST_B = 16;            // batches up to this size can skip the schedule, see attn_bf16_kernel
-constexpr int RECORD_BYTES = 1024 * RECORD_INTS * 4;  // MAX_WG records after the counters
-constexpr int PARTIAL_OFFSET = COUNTER_BYTES + RECORD_BYTES;  // the partial slots follow
-constexpr int MAX_WG = 1024;          // upper bound of the grid (workspace is sized for it)
-static_assert(RECORD_BYTES == MAX_WG * RECORD_INTS * 4 && COUNTER_BYTES == MAX_WG * 4, "workspace head");
+static_assert(COUNTER_BYTES == MAX_WG * 4, "workspace head");
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float LAZY = 6.f;           // log2 slack of the running softmax reference (bf16 path)
@@ -97,20 +54,17 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // 16 bytes in 
 
 struct AttnArgs {
   KvView         kv;
-  const int32_t* stage_base;
-  const int32_t* seq_len;
   const int32_t* cu_branches;   // null when no row carries a branch tag
   const uint8_t* slot_owner;
   int            owner_stride;
-  const int32_t* cu_seq_new;
   const int32_t* q_branch;
   const int32_t* logical_slot;
   const void*    q;
   void*          out;
   float*         lse;
-  float*         partial;       // [2 * nwg] slots of {[rows_per_group][D] accumulators, [rows_per_group][4]: reference, sum, pad}
+  float*         partial;       // [2 * nwg] slots of {[rows_cap][D] accumulators, [rows_cap][4]: reference, sum, pad}
   int*           counters;      // [nwg] arrivals per split item, zero between calls
-  int*           records;       // [nwg][RECORD_INTS]: the first segment each workgroup had in the last call
+  const int32_t* plan;          // the step's plan for this launch shape (aspd_plan.h)
   int            NQ;            // rows of q / out
   float          scale_log2;    // sm_scale * log2(e)
   int            B;
@@ -118,333 +72,60 @@ struct AttnArgs {
   int            G;             // query heads per KV head
   int            qpg;           // queries per row group
   int            rows_cap;      // rows per row group the partial slots are sized for
-  int            pad;           // virtual units in front of every item (ragged batches): a segment's fixed cost in pages
 };
 
 // ---------------------------------------------------------------------------------------------
-// Scheduling: identical in the attention kernels and in the merge kernel.
+// The plan, as the kernels read it.
 // ---------------------------------------------------------------------------------------------
-struct Item {
-  int s, rg, h;     // sequence, row group, KV head
-  int np;           // pages of the item
-  int lp;           // pages of it that lie wholly before stage_base (no owner tags, no masking)
-  int q0, nq;       // first packed query row and number of queries of the row group
-  int first_unit;   // flattened index of the item's page 0
+struct Seg {
+  int s, h;           // sequence, KV head
+  int q0, nq;         // first packed query row and number of queries of the row group
+  int page0, page1;   // the segment's pages
+  int np;             // pages of the whole item
+  int owner, w_last;  // first and last workgroup that hold a part of the item
+  int L;              // stage_base of the sequence
 };
 
-// Per-sequence scalars, fetched once per workgroup into LDS so that walking from segment to segment
-// needs no further dependent global loads, and the table of share boundaries.
-struct Sched {
-  int* cu_units;  // [B+1] exclusive scan of (pages + pad) * row groups * KV heads
-  int* T;         // [B]   seq_len
-  int* L;         // [B]   stage_base
-  int* q0;        // [B+1] cu_seq_new
-  int* wgb;       // [MAX_WG+1] first unit of every workgroup's share (ragged regime only)
-};
-__device__ __forceinline__ Sched sched_at(int* base, int B) {
-  Sched sc;
-  sc.cu_units = base;
-  sc.T = base + (B + 1);
-  sc.L = sc.T + B;
-  sc.q0 = sc.L + B;
-  sc.wgb = sc.q0 + (B + 1);
-  return sc;
+// Plan words through the scalar (constant) path: the address is the same in every lane, the words were
+// written by an earlier kernel, and scalar loads neither take vector registers nor queue up with the
+// page loads.
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ i32x8 load_words8(const int32_t* p /* 32-byte aligned, uniform */) {
+  return *(const __attribute__((address_space(4))) i32x8*)(uintptr_t)p;
 }
-constexpr int sched_ints(int B) { return 4 * B + 2 + MAX_WG + 1; }
+__device__ __forceinline__ i32x2 load_words2(const int32_t* p /* 8-byte aligned, uniform */) {
+  return *(const __attribute__((address_space(4))) i32x2*)(uintptr_t)p;
+}
+__device__ __forceinline__ Seg load_seg(const int32_t* p) {
+  const i32x8 w = load_words8(p);
+  Seg g;
+  g.s = w[0] & 0xffff;
+  g.h = (int)((unsigned)w[0] >> 16);
+  g.q0 = w[1];
+  g.nq = w[2];
+  g.page0 = w[3];
+  g.page1 = w[4];
+  g.np = w[5];
+  g.owner = w[6] & 0xffff;
+  g.w_last = (int)((unsigned)w[6] >> 16);
+  g.L = w[7];
+  return g;
+}
+// Everything a kernel derives an address from.  A plan is written by the library's own kernel; the
+// check keeps a workgroup that is handed anything else (a buffer of the wrong step, say) from reading
+// or writing outside the call's arrays: it then does nothing.
+__device__ __forceinline__ bool seg_ok(const AttnArgs& a, const Seg& g) {
+  return g.s < a.B && g.h < a.kv.num_kv_heads && g.q0 >= 0 && g.nq >= 1 && g.nq <= a.qpg && g.q0 <= a.NQ - g.nq &&
+         g.page0 >= 0 && g.page0 < g.page1 && g.page1 <= g.np && g.np <= a.kv.max_blocks_per_seq && g.L >= 0 &&
+         g.owner <= (int)blockIdx.x && (int)blockIdx.x <= g.w_last && g.w_last < a.nwg;
+}
+__device__ __forceinline__ bool seg_complete(const Seg& g) { return g.page0 == 0 && g.page1 == g.np; }
 
-__device__ __forceinline__ int pages_of(const AttnArgs& a, const Sched& sc, int s) {
-  int np = (sc.T[s] + ASPD_BLOCK - 1) / ASPD_BLOCK;
-  return min(np, a.kv.max_blocks_per_seq);
-}
-__device__ __forceinline__ int groups_of(const AttnArgs& a, const Sched& sc, int s) {
-  int nq = sc.q0[s + 1] - sc.q0[s];
-  return (nq + a.qpg - 1) / a.qpg;
-}
-
-// Shares of the unit space, one per workgroup used.  A unit is a page of an item or, in the ragged
-// regime, one of `pad` virtual units in front of every item: they price the fixed cost a workgroup
-// pays for starting a segment (start-up, reduction, a partial to be merged), so that equal shares of
-// units are about equal shares of time.  Two regimes, chosen per launch:
-//
-// ALIGNED (every item at least two shares long: few long sequences; pad = 0).  Item i gets the
-// workgroups [rnd(U_i), rnd(U_i + np_i)) with U_i its first unit and rnd(x) = x * n / total rounded
-// to nearest, and is cut evenly among them.  Every workgroup then has exactly one segment, and
-// shares differ by a page or two.
-//
-// RAGGED.  Workgroup w nominally takes [w * total / n, (w + 1) * total / n); a boundary inside an
-// item's padding, or within `tol` units after it or before the item's end, is moved onto the item
-// boundary: a sliver of a neighbouring item would cost a whole extra segment for a few pages.  The
-// boundaries are tabulated in LDS (wgb), which also gives the owner of a unit by binary search.
-struct Shares {
-  int total, n, tol, pad;
-  bool aligned;
-  double per_page;  // n / total: workgroups per unit
-  double share;     // total / n: units per workgroup
-  // Any monotone map with rnd(0) = 0 and rnd(total) = n serves, as long as every caller uses this one;
-  // double arithmetic avoids 64-bit integer division.
-  __device__ __forceinline__ int rnd(int x) const { return min(n, (int)((double)x * per_page + 0.5)); }
-  __device__ __forceinline__ int nominal_begin(int w) const { return min(total, (int)((double)w * share)); }
-};
-
-// The item that holds unit `u`, and the unit's index within it (padding first, then the pages).
-// WAVE: every lane of the wave calls with the same u; batches of up to 64 sequences are then searched
-// in one step (lane s looks at sequence s) instead of a chain of dependent LDS reads.
-template <bool WAVE>
-__device__ Item locate(const AttnArgs& a, const Sched& sc, int pad, int u, int* vpage) {
-  int lo = 0;  // the last sequence that starts at or before u
-  if (WAVE && a.B <= 64) {
-    const int lane = threadIdx.x & 63;
-    const int start = lane < a.B ? sc.cu_units[lane] : 0x7fffffff;
-    lo = 63 - __clzll(__ballot(start <= u));  // cu_units[0] = 0 <= u: the mask is not empty
-  } else {
-    int hi = a.B - 1;
-    while (lo < hi) {
-      int mid = (lo + hi + 1) >> 1;
-      if (sc.cu_units[mid] <= u) lo = mid; else hi = mid - 1;
-    }
-  }
-  Item it;
-  it.s = lo;
-  it.np = pages_of(a, sc, lo);
-  const int vl = it.np + pad;
-  const int rel = u - sc.cu_units[lo];
-  const int idx = rel / vl;
-  *vpage = rel - idx * vl;
-  const int ngroups = groups_of(a, sc, lo);
-  it.h = idx / ngroups;       // row groups of one KV head are neighbours: they read the same pages
-  it.rg = idx - it.h * ngroups;
-  it.first_unit = sc.cu_units[lo] + idx * vl;
-  it.lp = a.slot_owner ? min(it.np, sc.L[lo] / ASPD_BLOCK) : it.np;
-  const int qs = sc.q0[lo];
-  const int nq = sc.q0[lo + 1] - qs;
-  it.q0 = qs + it.rg * a.qpg;
-  it.nq = min(a.qpg, nq - it.rg * a.qpg);
-  return it;
-}
-
-// Cutting one item among its k workgroups (aligned regime).  A page of the branch region costs a wave
-// more than a page before it (owner tags, masking, scores that are thrown away): measured between 1.1
-// and 1.5 times, taken as 1.25.  The cut is therefore even in cost(p) = 4p + max(0, p - lp) rather than
-// in pages: piece j starts at the first page p with cost(p) * k >= j * cost(np), and page p belongs to
-// piece cost(p) * k / cost(np).
-__device__ __forceinline__ int item_cut(const Item& it, int j, int k) {
-  const int total = 4 * it.np + (it.np - it.lp);
-  const int t = (int)(((unsigned)j * (unsigned)total + (unsigned)k - 1u) / (unsigned)k);
-  return t <= 4 * it.lp ? (t + 3) >> 2 : it.lp + (t - 4 * it.lp + 4) / 5;
-}
-__device__ __forceinline__ int item_piece(const Item& it, int page, int k) {
-  const int total = 4 * it.np + (it.np - it.lp);
-  const int cost = 4 * page + max(0, page - it.lp);
-  return min(k - 1, (int)((unsigned)cost * (unsigned)k / (unsigned)total));
-}
-
-template <bool WAVE>
-__device__ int share_begin(const AttnArgs& a, const Sched& sc, const Shares& sh, int w) {
-  if (w <= 0) return 0;
-  if (w >= sh.n) return sh.total;
-  const int nominal = sh.nominal_begin(w);
-  int vpage;
-  Item it = locate<WAVE>(a, sc, sh.pad, nominal, &vpage);
-  if (sh.aligned) {
-    // rounding moves an item's first workgroup by half a share at most: the item that holds the
-    // nominal boundary, or its neighbour
-    if (w < sh.rnd(it.first_unit)) it = locate<WAVE>(a, sc, 0, it.first_unit - 1, &vpage);
-    else if (w >= sh.rnd(it.first_unit + it.np)) it = locate<WAVE>(a, sc, 0, it.first_unit + it.np, &vpage);
-    const int w0 = sh.rnd(it.first_unit);
-    const int k = sh.rnd(it.first_unit + it.np) - w0;
-    return it.first_unit + item_cut(it, w - w0, k);
-  }
-  const int vl = it.np + sh.pad;
-  if (vpage <= sh.pad + sh.tol) return it.first_unit;
-  if (vl - vpage <= sh.tol) return it.first_unit + vl;
-  return nominal;
-}
-
-// The per-sequence scalars of the thread's sequences, as loaded (the first memory round trip of a
-// launch; issuing it apart from its use lets a kernel put other loads in flight beside it).
-template <int THREADS>
-struct SeqLoads {
-  static constexpr int PER = (ASPD_MAX_BATCH + THREADS - 1) / THREADS;  // sequences per thread
-  int T[PER], q0[PER], q1[PER], L[PER];
-};
-template <int THREADS>
-__device__ __forceinline__ SeqLoads<THREADS> schedule_issue(const AttnArgs& a) {
-  SeqLoads<THREADS> ld;
-#pragma unroll
-  for (int j = 0; j < SeqLoads<THREADS>::PER; ++j) {
-    const int s = threadIdx.x * SeqLoads<THREADS>::PER + j;
-    ld.T[j] = ld.q0[j] = ld.q1[j] = ld.L[j] = 0;
-    if (s < a.B) {
-      ld.T[j] = a.seq_len[s];
-      ld.q0[j] = a.cu_seq_new[s];
-      ld.q1[j] = a.cu_seq_new[s + 1];
-      ld.L[j] = a.stage_base[s];
-    }
-  }
-  return ld;
-}
-
-// Fills the LDS tables and returns the shares.  All threads of the workgroup call it.
-template <int THREADS>
-__device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratch /* 3 * THREADS / 64 ints */,
-                                 const SeqLoads<THREADS>& ld) {
-  constexpr int PER = SeqLoads<THREADS>::PER;
-  constexpr int NWV = THREADS / 64;
-  const int tid = threadIdx.x;
-  int mine_p[PER], mine_i[PER];
-  int sum_p = 0, sum_i = 0;
-  int shortest = 0x7fffffff;
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    const int s = tid * PER + j;
-    mine_p[j] = 0;
-    mine_i[j] = 0;
-    if (s < a.B) {
-      const int T = ld.T[j];
-      const int q0 = ld.q0[j];
-      const int q1 = ld.q1[j];
-      sc.T[s] = T;
-      sc.L[s] = ld.L[j];
-      sc.q0[s] = q0;
-      if (s == a.B - 1) sc.q0[a.B] = q1;
-      const int np = min((T + ASPD_BLOCK - 1) / ASPD_BLOCK, a.kv.max_blocks_per_seq);
-      const int ng = (q1 - q0 + a.qpg - 1) / a.qpg;
-      if (np * ng > 0) {
-        mine_i[j] = ng * a.kv.num_kv_heads;
-        mine_p[j] = np * mine_i[j];
-        shortest = min(shortest, np);
-      }
-    }
-    sum_p += mine_p[j];
-    sum_i += mine_i[j];
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) shortest = min(shortest, __shfl_xor(shortest, off));
-  // scans: inside the wave by shuffles, across the waves through LDS (one barrier)
-  int incl_p = sum_p, incl_i = sum_i;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int vp = __shfl_up(incl_p, off);
-    const int vi = __shfl_up(incl_i, off);
-    if ((tid & 63) >= off) {
-      incl_p += vp;
-      incl_i += vi;
-    }
-  }
-  if ((tid & 63) == 63) {
-    scratch[tid >> 6] = incl_p;
-    scratch[NWV + (tid >> 6)] = incl_i;
-    scratch[2 * NWV + (tid >> 6)] = shortest;
-  }
-  __syncthreads();
-  int run_p = incl_p - sum_p, run_i = incl_i - sum_i;  // exclusive within the wave
-  int pages = 0, items = 0;
-  int mn = 0x7fffffff;
-#pragma unroll
-  for (int w = 0; w < NWV; ++w) {
-    const int tp = scratch[w], ti = scratch[NWV + w];
-    if (w < (tid >> 6)) {
-      run_p += tp;
-      run_i += ti;
-    }
-    pages += tp;
-    items += ti;
-    mn = min(mn, scratch[2 * NWV + w]);
-  }
-  Shares sh;
-  const int n0 = max(1, min(a.nwg, pages / MIN_PAGES_PER_WG));
-  sh.aligned = (double)mn * n0 >= 2.0 * pages;
-  sh.pad = sh.aligned ? 0 : a.pad;
-  sh.total = pages + sh.pad * items;
-  sh.n = max(1, min(a.nwg, sh.total / MIN_PAGES_PER_WG));
-  sh.tol = min((sh.total / sh.n) >> 3, a.pad);
-  sh.per_page = (double)sh.n / (double)max(sh.total, 1);
-  sh.share = (double)sh.total / (double)sh.n;
-#pragma unroll
-  for (int j = 0; j < PER; ++j) {
-    const int s = tid * PER + j;
-    if (s < a.B) sc.cu_units[s] = run_p + sh.pad * run_i;
-    run_p += mine_p[j];
-    run_i += mine_i[j];
-  }
-  if (tid == 0) sc.cu_units[a.B] = sh.total;
-  __syncthreads();
-  if (!sh.aligned) {
-    for (int w = tid; w <= sh.n; w += THREADS) sc.wgb[w] = share_begin<false>(a, sc, sh, w);  // w differs per lane
-    __syncthreads();
-  }
-  return sh;
-}
-template <int THREADS>
-__device__ Shares build_schedule(const AttnArgs& a, const Sched& sc, int* scratch) {
-  return build_schedule<THREADS>(a, sc, scratch, schedule_issue<THREADS>(a));
-}
-
-// The workgroup whose share holds unit u.
-__device__ int share_owner(const AttnArgs& a, const Sched& sc, const Shares& sh, int u) {
-  if (sh.aligned) {
-    int page;
-    const Item it = locate<true>(a, sc, 0, u, &page);
-    const int w0 = sh.rnd(it.first_unit);
-    const int k = sh.rnd(it.first_unit + it.np) - w0;
-    return w0 + item_piece(it, page, k);
-  }
-  int lo = 0, hi = sh.n - 1;  // last w with wgb[w] <= u
-  while (lo < hi) {
-    const int mid = (lo + hi + 1) >> 1;
-    if (sc.wgb[mid] <= u) lo = mid; else hi = mid - 1;
-  }
-  return lo;
-}
-
-// Aligned regime: a workgroup's share is one run of pages of one item, found with one look-up (the
-// same item, and the same cuts, as share_begin gives for w and w + 1).
-__device__ __forceinline__ bool aligned_share(const AttnArgs& a, const Sched& sc, const Shares& sh, int w, Item* out,
-                                              int* page0, int* page1) {
-  int vpage;
-  Item it = locate<true>(a, sc, 0, sh.nominal_begin(w), &vpage);
-  if (w < sh.rnd(it.first_unit)) it = locate<true>(a, sc, 0, it.first_unit - 1, &vpage);
-  else if (w >= sh.rnd(it.first_unit + it.np)) it = locate<true>(a, sc, 0, it.first_unit + it.np, &vpage);
-  const int w0 = sh.rnd(it.first_unit);
-  const int k = sh.rnd(it.first_unit + it.np) - w0;
-  *page0 = item_cut(it, w - w0, k);
-  *page1 = item_cut(it, w + 1 - w0, k);
-  *out = it;
-  return *page1 > *page0;
-}
-
-// One workgroup's walk over its share [*u, end): the next run of real pages, or false at the end.
-__device__ __forceinline__ void share_range(const AttnArgs& a, const Sched& sc, const Shares& sh, int* u, int* end) {
-  if (sh.aligned) {
-    *u = share_begin<true>(a, sc, sh, blockIdx.x);
-    *end = share_begin<true>(a, sc, sh, blockIdx.x + 1);
-  } else {
-    *u = sc.wgb[blockIdx.x];
-    *end = sc.wgb[blockIdx.x + 1];
-  }
-}
-__device__ __forceinline__ bool next_segment(const AttnArgs& a, const Sched& sc, const Shares& sh, int* u, int end,
-                                             Item* it, int* page0, int* page1) {
-  while (*u < end) {
-    int v0;
-    *it = locate<true>(a, sc, sh.pad, *u, &v0);
-    const int v1 = min(it->np + sh.pad, v0 + (end - *u));
-    *u += v1 - v0;
-    *page0 = max(0, v0 - sh.pad);
-    *page1 = max(0, v1 - sh.pad);
-    if (*page1 > *page0) return true;
-  }
-  return false;
-}
-
-// Defined after the kernels (it needs the merge): called by every thread of a workgroup that has
-// written a partial of `it`, pages [page0, page1).
+// Called by every thread of a workgroup that has written a partial of the item of `g` (defined after
+// the kernels: it needs the merge).
 template <int D, bool BF16, int THREADS, int ELEMS>
-__device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh, int page0,
-                                 int page1, int* flag /* LDS */, int* owner_out = nullptr, int* w_last_out = nullptr);
-// The same for a caller that knows the item's first and last workgroup.
-template <int D, bool BF16, int THREADS, int ELEMS>
-__device__ void announce_partial_to(const AttnArgs& a, const Item& it, int owner, int w_last, int* flag /* LDS */);
+__device__ void announce_partial(const AttnArgs& a, const Seg& g, int* flag /* LDS */);
 
 __device__ __forceinline__ float* partial_slot(const AttnArgs& a, int wg, int starts_item, int D) {
   return a.partial + ((long)(2 * wg + starts_item)) * a.rows_cap * (D + 4);
@@ -714,16 +395,6 @@ __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qt
 
 constexpr int BLK_WIN = 512;   // pages of a segment whose block ids are staged in LDS at once
 
-// What the start-up loads of a segment depend on.
-struct SegDesc {
-  int s, h;          // sequence, KV head
-  int q0, nq;        // first packed query row and number of queries of the row group
-  int page0, page1;  // the segment's pages
-};
-__device__ __forceinline__ bool same_segment(const SegDesc& x, const SegDesc& y) {
-  return x.s == y.s && x.h == y.h && x.q0 == y.q0 && x.nq == y.nq && x.page0 == y.page0 && x.page1 == y.page1;
-}
-
 // The start-up loads of a segment, in registers: block ids of the first window, the Q rows, the row
 // descriptors, and the first pair of pages of every wave (pair `wave` of the segment).
 template <int D, int NT, int NW>
@@ -739,13 +410,11 @@ struct SegLoads {
   PairRegs<D> first;
 };
 
-// Segment start-up, part one: the loads.  Three dependent memory round trips are needed at least
-// (lengths -> block ids -> pages); the Q rows and row descriptors are fetched alongside the block ids,
-// and each wave fetches the two block ids of its first pair itself, so that the pages are on their way
-// before anything passes through LDS.  Touches no LDS; every address stays in bounds for any `d` with
-// 0 <= s < B, 0 <= h < KV heads, 0 <= q0, 1 <= nq, q0 + nq <= NQ, 0 <= page0 < page1 <= max blocks.
+// Segment start-up, part one: the loads that depend on nothing but the segment.  The Q rows and row
+// descriptors are fetched alongside the block ids, and each wave fetches the two block ids of its
+// first pair itself.  Touches no LDS; every address stays in bounds for any `d` that passed seg_ok.
 template <int D, int NT, int NW>
-__device__ __forceinline__ void segment_issue_ids(const AttnArgs& a, const SegDesc& d, SegLoads<D, NT, NW>& ld) {
+__device__ __forceinline__ void segment_issue_ids(const AttnArgs& a, const Seg& d, SegLoads<D, NT, NW>& ld) {
   using C = Bf16Cfg<D>;
   using LD = SegLoads<D, NT, NW>;
   constexpr int ROWS = 16 * NT;
@@ -798,20 +467,23 @@ __device__ __forceinline__ void segment_issue_ids(const AttnArgs& a, const SegDe
     ld.first.own[1] = *(const uint32_t*)(own_p0 + own_step);
   }
 }
-// ... and, once the two block ids have arrived, the pages of the wave's first pair.
+// ... and the pages of the wave's first pair, from two block ids: those the plan carries for a
+// workgroup's first segment (one round trip after the kernel starts), or those just loaded from the
+// block table.  Any two blocks of the pool are safe to read; the segment compares them with the block
+// table before it uses the pages.
 template <int D, int NT, int NW, bool STREAM>
-__device__ __forceinline__ void segment_issue_pair(const AttnArgs& a, const SegDesc& d, SegLoads<D, NT, NW>& ld) {
-  ld.used0 = min(max(__builtin_amdgcn_readfirstlane(ld.b0), 0), a.kv.num_blocks - 1);
-  ld.used1 = min(max(__builtin_amdgcn_readfirstlane(ld.b1), 0), a.kv.num_blocks - 1);
+__device__ __forceinline__ void segment_issue_pair(const AttnArgs& a, const Seg& d, SegLoads<D, NT, NW>& ld, int b0,
+                                                   int b1) {
+  ld.used0 = min(max(__builtin_amdgcn_readfirstlane(b0), 0), a.kv.num_blocks - 1);
+  ld.used1 = min(max(__builtin_amdgcn_readfirstlane(b1), 0), a.kv.num_blocks - 1);
   issue_pair<D, STREAM>(ld.first, a, d.h, ld.used0, ld.used1, threadIdx.x & 63, nullptr, 0);
 }
 
-// Segment start-up, part two, the stream and the epilogue.  `ld` holds the loads segment_issue made
-// for this very segment.
+// Segment start-up, part two, the stream and the epilogue.  `ld` holds the loads made for this very
+// segment.
 template <int D, int NT, int NW, int PF, bool STREAM>
-__device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
-                             bool complete, float* pslot, const SegLoads<D, NT, NW>& ld,
-                             int* rec_ids /* where to leave the first pairs' block ids, or null */) {
+__device__ void segment_bf16(const AttnArgs& a, char* smem, const Seg& it, bool complete, float* pslot,
+                             const SegLoads<D, NT, NW>& ld) {
   using C = Bf16Cfg<D>;
   using LD = SegLoads<D, NT, NW>;
   constexpr int ROWS = 16 * NT;
@@ -822,6 +494,7 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   const int c = lane & 15;
   const int g = lane >> 4;
   const int R = it.nq * a.G;
+  const int page0 = it.page0, page1 = it.page1, L = it.L;
 
   u32x4* stage = (u32x4*)(smem + wave * C::STAGE_BYTES);                // this wave's K0 K1 V0 V1
   u32x4* qtile = (u32x4*)(smem + NW * C::STAGE_BYTES);                  // [ROWS][LROW]
@@ -855,15 +528,21 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
 
   RowState<D, NT> ts;
   int mask_from = L;  // keys below this slot are visible to every row of the group
+  int last_slot = 0;  // keys above this slot are visible to none
 #pragma unroll
   for (int n = 0; n < NT; ++n) {
     ts.slot[n] = rowslot[16 * n + c];
     ts.tag[n] = rowtag[16 * n + c];
     mask_from = min(mask_from, ts.slot[n]);
+    last_slot = max(last_slot, ts.slot[n]);
   }
 #pragma unroll
-  for (int off = 1; off < 16; off <<= 1) mask_from = min(mask_from, __shfl_xor(mask_from, off));
+  for (int off = 1; off < 16; off <<= 1) {
+    mask_from = min(mask_from, __shfl_xor(mask_from, off));
+    last_slot = max(last_slot, __shfl_xor(last_slot, off));
+  }
   mask_from = __builtin_amdgcn_readfirstlane(mask_from);
+  last_slot = __builtin_amdgcn_readfirstlane(last_slot);
 
   // LDS addressing: every position used in the loop is one of a few lane-dependent bases
   // plus a compile-time offset (which the LDS instructions carry as an immediate).
@@ -925,15 +604,11 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
       if (sl == 0 && wbase == page0) {  // fetched at start-up
         idx[0] = wave;
         pr[0] = ld.first;
-        // ... with block ids that may have come from the last launch's record: fetched again if the
-        // block table has changed since
+        // ... with block ids that may have come from the plan: fetched again if the block table the
+        // call was given says otherwise
         const int a0 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * wave, wpages - 1)]);
         const int a1 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * wave + 1, wpages - 1)]);
         if (a0 != ld.used0 || a1 != ld.used1) issue_pair<D, STREAM>(pr[0], a, it.h, a0, a1, lane, nullptr, 0);
-        if (rec_ids && lane == 0) {
-          rec_ids[2 * wave] = a0;
-          rec_ids[2 * wave + 1] = a1;
-        }
         continue;
       }
       idx[sl] = take();
@@ -954,39 +629,51 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
           more = false;
           break;
         }
-      // ---- registers -> this wave's LDS stage
+        const int pair = idx[sl];
+        const int P0 = wbase + 2 * pair;
+        // Slots past the last row's own slot have never been written (the tail of the last page) and may
+        // hold anything: their V rows enter the second product with weight zero, and zero times a NaN
+        // is a NaN, so they are cleared on the way into LDS.  (Their K rows only reach scores that the
+        // mask replaces.)
+        if ((P0 + 2) * ASPD_BLOCK > last_slot + 1) {
 #pragma unroll
-      for (int i = 0; i < C::LPP; ++i) {
-        // the position is a lane-dependent base plus a compile-time offset
-        constexpr int STEP = C::RPL * C::LROW;  // load i of a page is rows i * RPL .. of it
-        stage[0 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[0][i];
-        stage[1 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[1][i];
-        stage[2 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[2][i];
-        stage[3 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[3][i];
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      // ---- refill the set: the next pair streams in while this one is computed
-      const int pair = idx[sl];
-      idx[sl] = ahead;
-      const uint32_t own0 = pr[sl].own[0], own1 = pr[sl].own[1];  // of the pair about to be computed
-      if (ahead < npairs) {
-        const int b0 = __builtin_amdgcn_readfirstlane(blk_lds[2 * ahead]);
-        const int b1 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * ahead + 1, wpages - 1)]);
-        issue_pair<D, STREAM>(pr[sl], a, it.h, b0, b1, lane, own_ptr(wbase + 2 * ahead), own_step(wbase + 2 * ahead));
-      }
-      ahead = take();
+          for (int i = 0; i < C::LPP; ++i) {
+            const int key = P0 * ASPD_BLOCK + wrow + i * C::RPL;
+            if (key > last_slot) pr[sl].r[2][i] = u32x4{0u, 0u, 0u, 0u};
+            if (key + ASPD_BLOCK > last_slot) pr[sl].r[3][i] = u32x4{0u, 0u, 0u, 0u};
+          }
+        }
+        // ---- registers -> this wave's LDS stage
+#pragma unroll
+        for (int i = 0; i < C::LPP; ++i) {
+          // the position is a lane-dependent base plus a compile-time offset
+          constexpr int STEP = C::RPL * C::LROW;  // load i of a page is rows i * RPL .. of it
+          stage[0 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[0][i];
+          stage[1 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[1][i];
+          stage[2 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[2][i];
+          stage[3 * C::LPAGE_U4 + i * STEP + kw] = pr[sl].r[3][i];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        // ---- refill the set: the next pair streams in while this one is computed
+        idx[sl] = ahead;
+        const uint32_t own0 = pr[sl].own[0], own1 = pr[sl].own[1];  // of the pair about to be computed
+        if (ahead < npairs) {
+          const int b0 = __builtin_amdgcn_readfirstlane(blk_lds[2 * ahead]);
+          const int b1 = __builtin_amdgcn_readfirstlane(blk_lds[min(2 * ahead + 1, wpages - 1)]);
+          issue_pair<D, STREAM>(pr[sl], a, it.h, b0, b1, lane, own_ptr(wbase + 2 * ahead), own_step(wbase + 2 * ahead));
+        }
+        ahead = take();
 
-      const int P0 = wbase + 2 * pair;
-      const bool second_valid = (P0 + 1) < wend;
+        const bool second_valid = (P0 + 1) < wend;
 
-      constexpr bool ROOMY = (NW <= 4);  // one wave per SIMD: 512 registers
-      constexpr int KB = (NT == 1 || ROOMY) ? C::KSTEPS : (NT == 2 ? 2 : 1);
-      constexpr int VB = (NT == 1 || ROOMY) ? C::MT : (NT == 2 ? 4 : 2);
-      pair_compute<D, NT, KB, VB>(stage, qtile, ts, kr_even, kr_odd, vu, g, L, mask_from, P0, second_valid, own0,
-                                  own1, a.scale_log2);
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+        constexpr bool ROOMY = (NW <= 4);  // one wave per SIMD: 512 registers
+        constexpr int KB = (NT == 1 || ROOMY) ? C::KSTEPS : (NT == 2 ? 2 : 1);
+        constexpr int VB = (NT == 1 || ROOMY) ? C::MT : (NT == 2 ? 4 : 2);
+        pair_compute<D, NT, KB, VB>(stage, qtile, ts, kr_even, kr_odd, vu, g, L, mask_from, P0, second_valid, own0,
+                                    own1, a.scale_log2);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
       }
     }
   }
@@ -1076,10 +763,24 @@ __device__ void segment_bf16(const AttnArgs& a, char* smem, const Item& it, int 
   }
 }
 
+
 template <int D, int NT, int NW>
-size_t bf16_smem_bytes(int B) {
+size_t bf16_smem_bytes() {
   return NW * Bf16Cfg<D>::STAGE_BYTES + 16 * NT * Bf16Cfg<D>::LROW * 16 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
-         (BLK_WIN + 4) * 4 + (size_t)sched_ints(B) * 4;
+         (BLK_WIN + 4) * 4;
+}
+
+// What every kernel does first: its workgroup's header of the plan.  Returns the number of segments
+// (0: nothing to do, also for a header that fails seg_ok).
+__device__ __forceinline__ int plan_begin(const AttnArgs& a, Seg* first, int* next) {
+  const int32_t* hdr = a.plan + (long)PLAN_HDR * blockIdx.x;
+  *first = load_seg(hdr);
+  const i32x2 m = load_words2(hdr + PLAN_HDR_NSEG);
+  *next = m[1];
+  return (m[0] > 0 && seg_ok(a, *first)) ? m[0] : 0;
+}
+__device__ __forceinline__ Seg plan_segment(const AttnArgs& a, int index) {
+  return load_seg(a.plan + (long)PLAN_HDR * a.nwg + (long)PLAN_SEG * index);
 }
 
 template <int D, int NT, int NW, int PF, bool STREAM>
@@ -1087,170 +788,34 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
     AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int merge_flag;
-  using C = Bf16Cfg<D>;
   constexpr int THREADS = NW * 64;
-  // after the stages, the Q tile, row descriptors and wave statistics: the unit scan
-  int* sched_base = (int*)(smem + NW * C::STAGE_BYTES + 16 * NT * C::LROW * 16 + 2 * 16 * NT * 4 + 2 * NW * 16 * NT * 4 +
-                          (BLK_WIN + 4) * 4);
-  int* scratch = (int*)smem;  // the stage area is idle until the first segment
-  const Sched sc = sched_at(sched_base, a.B);
-  const SeqLoads<THREADS> seq = schedule_issue<THREADS>(a);
-  asm volatile("" ::: "memory");  // these loads start here, not where the schedule first uses them
-  // A workgroup's first segment is, launch after launch of a decoding loop, mostly the one it had the
-  // last time (same batch, lengths one token longer).  Each workgroup therefore leaves a record of it
-  // in the workspace, and the next launch starts that segment's loads at once, beside the loads of the
-  // lengths, instead of after the schedule has been worked out from them: two of the three dependent
-  // round trips of a launch overlap.  The schedule is computed as always; loads made for a segment
-  // that turns out not to be the workgroup's first are dropped.  A record only chooses addresses to
-  // read early (checked against the call's bounds first); results never depend on it.
-  constexpr bool GUESS = (NT <= 2);  // three tiles leave no registers to hold the loads meanwhile
-  static_assert(REC_IDS + 2 * NW <= REC_ITEM, "record holds two block ids per wave");
+  static_assert(2 * NW <= PLAN_IDS, "the plan carries two block ids per wave");
+  // One memory round trip after the kernel starts the workgroup knows its first segment and the blocks
+  // of each wave's first pair of pages (scalar loads of the plan header), and the pages, the block ids of
+  // the whole segment, the Q rows and the row descriptors all leave together.
+  Seg seg;
+  int next;
+  const int nseg = plan_begin(a, &seg, &next);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const i32x2 ids = load_words2(a.plan + (long)PLAN_HDR * blockIdx.x + PLAN_HDR_IDS + 2 * wave);
+  if (nseg == 0) return;
   SegLoads<D, NT, NW> ld;
-  SegDesc guess = {0, 0, 0, 0, 0, 0};
-  bool guessed = false;
-  int* record = a.records + (long)blockIdx.x * RECORD_INTS;
-  // Small batches go one step further.  The schedule is a function of a few launch constants and, per
-  // sequence, of its page count, its prefix page count and its rows; the record keeps those as well,
-  // every wave loads the current ones (lane s: sequence s), and when all of them are EQUAL the recorded
-  // segment is this launch's segment by construction: the schedule is then not worked out at all.
-  const int lane = threadIdx.x & 63;
-  const bool small = GUESS && a.B <= FAST_B;
-  const uint32_t sig0 = (uint32_t)a.nwg | ((uint32_t)a.qpg << 16);
-  const uint32_t sig1 = (uint32_t)a.pad | ((uint32_t)a.kv.num_kv_heads << 16);
-  const uint32_t sig2 = (uint32_t)a.B | (a.slot_owner ? 0x10000u : 0u) | 0x80000000u;
-  const uint32_t sig3 = (uint32_t)a.kv.max_blocks_per_seq;
-  int l_np = 0, l_lp = 0, l_q0 = 0, l_q1 = 0, l_L = 0;  // lane s: sequence s as this launch has it
-  bool fast = false;
-  Item it;
-  int page0 = 0, page1 = 0, owner_rec = 0, w_last_rec = 0;
-  if (GUESS) {
-    // one 16-byte load: sequence (12 bits), KV head (12), queries (8) | first row | first page | end page
-    u32x4 r0 = *(const u32x4*)record;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int rb0 = record[REC_IDS + 2 * wave], rb1 = record[REC_IDS + 2 * wave + 1];  // block ids of the wave's first pair
-    u32x4 ritem = {0u, 0u, 0u, 0u}, rsig = {0u, 0u, 0u, 0u}, rseq = {0u, 0u, 0u, 0u};
-    int l_T = 0, l_q0n = 0, l_q1n = 0;
-    if (small) {
-      ritem = *(const u32x4*)(record + REC_ITEM);
-      rsig = *(const u32x4*)(record + REC_SIG);
-      if (lane < a.B) {
-        rseq = *(const u32x4*)(record + REC_SEQ + 4 * lane);
-        l_T = a.seq_len[lane];
-        l_L = a.stage_base[lane];
-        l_q0n = a.cu_seq_new[lane];
-        l_q1n = a.cu_seq_new[lane + 1];
-      }
-    }
-    // all of these loads leave before any of them is waited for
-    asm volatile("" : "+v"(r0), "+v"(rb0), "+v"(rb1), "+v"(ritem), "+v"(rsig), "+v"(rseq), "+v"(l_T), "+v"(l_L),
-                 "+v"(l_q0n), "+v"(l_q1n));
-    const uint32_t w0 = __builtin_amdgcn_readfirstlane(r0[0]);
-    guess.s = (int)(w0 & 0xfffu);
-    guess.h = (int)((w0 >> 12) & 0xfffu);
-    guess.nq = (int)(w0 >> 24);
-    guess.q0 = (int)__builtin_amdgcn_readfirstlane(r0[1]);
-    guess.page0 = (int)__builtin_amdgcn_readfirstlane(r0[2]);
-    guess.page1 = (int)__builtin_amdgcn_readfirstlane(r0[3]);
-    guessed = guess.s >= 0 && guess.s < a.B && guess.h >= 0 && guess.h < a.kv.num_kv_heads && guess.q0 >= 0 &&
-              guess.nq >= 1 && guess.nq <= a.qpg && guess.q0 <= a.NQ - guess.nq && guess.page0 >= 0 &&
-              guess.page0 < guess.page1 && guess.page1 <= a.kv.max_blocks_per_seq;
-    if (small) {
-      l_np = min((l_T + ASPD_BLOCK - 1) / ASPD_BLOCK, a.kv.max_blocks_per_seq);
-      l_lp = a.slot_owner ? min(l_np, l_L / ASPD_BLOCK) : l_np;
-      l_q0 = l_q0n;
-      l_q1 = l_q1n;
-      const bool same = lane >= a.B || ((int)rseq[0] == l_np && (int)rseq[1] == l_lp && (int)rseq[2] == l_q0 &&
-                                        (int)rseq[3] == l_q1);
-      const bool all_same = __all(same) != 0;
-      const bool sig_same = __builtin_amdgcn_readfirstlane(rsig[0]) == sig0 &&
-                            __builtin_amdgcn_readfirstlane(rsig[1]) == sig1 &&
-                            __builtin_amdgcn_readfirstlane(rsig[2]) == sig2 &&
-                            __builtin_amdgcn_readfirstlane(rsig[3]) == sig3;
-      owner_rec = (int)__builtin_amdgcn_readfirstlane(ritem[0]);
-      w_last_rec = (int)__builtin_amdgcn_readfirstlane(ritem[1]);
-      const int np_rec = (int)__builtin_amdgcn_readfirstlane(ritem[2]);
-      const int lp_rec = (int)__builtin_amdgcn_readfirstlane(ritem[3]);
-      // (the last line only guards against a workspace someone else has written to)
-      fast = guessed && all_same && sig_same && owner_rec >= 0 && owner_rec <= (int)blockIdx.x &&
-             (int)blockIdx.x <= w_last_rec && w_last_rec < a.nwg && guess.page1 <= np_rec && lp_rec <= np_rec &&
-             np_rec <= a.kv.max_blocks_per_seq;
-      if (fast) {
-        it.s = guess.s;
-        it.h = guess.h;
-        it.rg = 0;
-        it.np = np_rec;
-        it.lp = lp_rec;
-        it.q0 = guess.q0;
-        it.nq = guess.nq;
-        it.first_unit = 0;
-        page0 = guess.page0;
-        page1 = guess.page1;
-      }
-    }
-    // (a record that fails the checks is replaced by a segment every call has, so that the loads are
-    // the same on every path, see segment_issue_ids)
-    if (!guessed) guess = SegDesc{0, 0, 0, 1, 0, 1};
-    segment_issue_ids<D, NT, NW>(a, guess, ld);
-    // the pages go with the block ids of the record (any two blocks of the pool are safe to read; the
-    // segment compares them with the block table before it uses the pages)
-    ld.used0 = min(max(__builtin_amdgcn_readfirstlane(rb0), 0), a.kv.num_blocks - 1);
-    ld.used1 = min(max(__builtin_amdgcn_readfirstlane(rb1), 0), a.kv.num_blocks - 1);
-    issue_pair<D, STREAM>(ld.first, a, guess.h, ld.used0, ld.used1, lane, nullptr, 0);
-    asm volatile("" ::: "memory");  // and all of these before the schedule is worked out
-  }
-  Shares sh;
-  sh.aligned = true;
-  int u = 0, end = 0;
-  bool pending = true;
-  if (!fast) {
-    sh = build_schedule<THREADS>(a, sc, scratch, seq);
-    if ((int)blockIdx.x >= sh.n) return;
-    if (sh.aligned) {
-      pending = aligned_share(a, sc, sh, blockIdx.x, &it, &page0, &page1);
-    } else {
-      share_range(a, sc, sh, &u, &end);
-      pending = next_segment(a, sc, sh, &u, end, &it, &page0, &page1);
-    }
-  }
-  bool first = true;
-  for (; pending; pending = !sh.aligned && next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
-    const bool complete = (page0 == 0) && (page1 == it.np);
-    float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    const SegDesc desc = {it.s, it.h, it.q0, it.nq, page0, page1};
-    const bool hit = GUESS && first && guessed && same_segment(desc, guess);
-    if (!hit) {
-      segment_issue_ids<D, NT, NW>(a, desc, ld);
-      segment_issue_pair<D, NT, NW, STREAM>(a, desc, ld);
-      if (GUESS && first && threadIdx.x == 0 && desc.s < 4096 && desc.h < 4096 && desc.nq < 256)
-        *(u32x4*)record = u32x4{(uint32_t)desc.s | ((uint32_t)desc.h << 12) | ((uint32_t)desc.nq << 24),
-                                (uint32_t)desc.q0, (uint32_t)desc.page0, (uint32_t)desc.page1};
-    }
-    const bool was_first = first;
-    first = false;
-    // stage_base of the item's sequence
-    const int L = fast ? __builtin_amdgcn_readlane(l_L, __builtin_amdgcn_readfirstlane(it.s)) : sc.L[it.s];
-    segment_bf16<D, NT, NW, PF, STREAM>(a, smem, it, page0, page1, L, complete, pslot, ld,
-                                        (GUESS && was_first) ? record + REC_IDS : nullptr);
+  segment_issue_pair<D, NT, NW, STREAM>(a, seg, ld, ids[0], ids[1]);
+  segment_issue_ids<D, NT, NW>(a, seg, ld);
+  for (int i = 0;;) {
+    // the next segment's words are on their way while this one streams
+    Seg after = seg;
+    if (i + 1 < nseg) after = plan_segment(a, next + i);
+    const bool complete = seg_complete(seg);
+    float* pslot = partial_slot(a, blockIdx.x, seg.page0 == 0 ? 1 : 0, D);
+    segment_bf16<D, NT, NW, PF, STREAM>(a, smem, seg, complete, pslot, ld);
     // the merging workgroup has 16 * NT rows of D / 4 chunks to combine: one pass of its 64 * NW threads
-    int owner = (int)blockIdx.x, w_last = (int)blockIdx.x;
-    if (!complete) {
-      if (fast)
-        announce_partial_to<D, true, THREADS, (NT == 1 ? 2 : 3)>(a, it, owner_rec, w_last_rec, &merge_flag);
-      else
-        announce_partial<D, true, THREADS, (NT == 1 ? 2 : 3)>(a, sc, it, sh, page0, page1, &merge_flag, &owner,
-                                                              &w_last);
-    }
-    // what a later launch with the same lengths needs in order to skip the schedule
-    if (GUESS && was_first && !fast) {
-      const bool keep = small && sh.aligned && desc.s < 4096 && desc.h < 4096 && desc.nq < 256;
-      if (threadIdx.x == 0) {
-        *(u32x4*)(record + REC_ITEM) = u32x4{(uint32_t)owner, (uint32_t)w_last, (uint32_t)it.np, (uint32_t)it.lp};
-        *(u32x4*)(record + REC_SIG) = keep ? u32x4{sig0, sig1, sig2, sig3} : u32x4{0u, 0u, 0u, 0u};
-      }
-      if (keep && (int)threadIdx.x < a.B)
-        *(u32x4*)(record + REC_SEQ + 4 * threadIdx.x) =
-            u32x4{(uint32_t)l_np, (uint32_t)l_lp, (uint32_t)l_q0, (uint32_t)l_q1};
-    }
+    if (!complete) announce_partial<D, true, THREADS, (NT == 1 ? 2 : 3)>(a, seg, &merge_flag);
+    if (++i >= nseg) break;
+    seg = after;
+    if (!seg_ok(a, seg)) break;
+    segment_issue_ids<D, NT, NW>(a, seg, ld);
+    segment_issue_pair<D, NT, NW, STREAM>(a, seg, ld, ld.b0, ld.b1);
   }
 }
 
@@ -1268,13 +833,12 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
 // tokens of other branches).
 // ---------------------------------------------------------------------------------------------
 template <int D, int NT, int NW>
-size_t rows_smem_bytes(int B) {
-  return 2 * ROWS_PPS * Bf16Cfg<D>::STAGE_BYTES + (BLK_WIN + 4) * 4 + (size_t)sched_ints(B) * 4;
+size_t rows_smem_bytes() {
+  return 2 * ROWS_PPS * Bf16Cfg<D>::STAGE_BYTES + (BLK_WIN + 4) * 4;
 }
 
 template <int D, int NT, int NW>
-__device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
-                             bool complete, float* pslot) {
+__device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool complete, float* pslot) {
   using C = Bf16Cfg<D>;
   constexpr int ROWS = 16 * NT;        // rows per wave
   constexpr int THREADS = NW * 64;
@@ -1289,6 +853,7 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
   const int c = lane & 15;
   const int g = lane >> 4;
   const int R = it.nq * a.G;                       // rows of the whole row group
+  const int page0 = it.page0, page1 = it.page1, L = it.L;
   const int Rw = min(ROWS, R - wave * ROWS);       // rows this wave owns (<= 0: none)
   const bool wave_active = Rw > 0;
 
@@ -1297,6 +862,10 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
 
   const int* bt = a.kv.block_tables + (long)it.s * a.kv.max_blocks_per_seq;
   const uint8_t* owner_row = a.slot_owner ? uniform_ptr(a.slot_owner + (long)it.s * a.owner_stride) : nullptr;
+  // The rows of a group are packed in the order of their slots: the last row's slot bounds what any row
+  // of the group may see.  Slots past it have never been written (the tail of the last page) and may hold
+  // anything; their V rows are cleared on the way into LDS (zero weight times a NaN would be a NaN).
+  const int last_slot = __builtin_amdgcn_readfirstlane(a.logical_slot[it.q0 + it.nq - 1]);
 
   // ---- start-up: block ids of the first window; this wave's Q operands and row descriptors go
   // straight to registers (lane (c, g) holds, of row c of every tile, the 16-byte pieces 4t + g)
@@ -1377,9 +946,13 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
     // This thread's slice of group gi.  Issued for every ring slot, also past the end of the window (the
     // last pages again, which the caches hold): the number of loads younger than a slot is then fixed,
     // so waiting for the oldest slot leaves the younger ones in flight.
-    auto issue = [&](u32x4 (&dst)[LPT], int gi) {
+    // the page (of the window) this thread loads for group gi
+    auto page_of = [&](int gi) -> int {
       const int p = min(gi * PPS + (lpage >> 2), npairs - 1);
-      const int pg = min(2 * p + (lpage & 1), wpages - 1);
+      return min(2 * p + (lpage & 1), wpages - 1);
+    };
+    auto issue = [&](u32x4 (&dst)[LPT], int gi) {
+      const int pg = page_of(gi);
       const int b = blk_lds[pg];
       const u32x4* src = (const u32x4*)(l_is_k ? a.kv.k : a.kv.v) + ((long)b * a.kv.num_kv_heads + it.h) * C::PAGE_U4;
 #pragma unroll
@@ -1408,6 +981,12 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Item& it, int 
       const int gi = gbase + d;
       if (gi >= ngroups) break;
       u32x4* stage = stage0 + (gi & 1) * (PPS * C::STAGE_BYTES / 16);
+      const int key0 = (wbase + page_of(gi)) * ASPD_BLOCK;  // first slot of the page this thread staged
+      if (!l_is_k && key0 + ASPD_BLOCK > last_slot + 1) {
+#pragma unroll
+        for (int k = 0; k < LPT; ++k)
+          if (key0 + (lt + k * PER_PAGE) / C::CH > last_slot) nxt[d][k] = u32x4{0u, 0u, 0u, 0u};
+      }
 #pragma unroll
       for (int k = 0; k < LPT; ++k) stage[lpage * C::LPAGE_U4 + lpos[k]] = nxt[d][k];
       u32x4 tc[PPS][2];
@@ -1486,27 +1065,19 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
     AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int merge_flag;
-  using C = Bf16Cfg<D>;
   constexpr int THREADS = NW * 64;
-  int* sched_base = (int*)(smem + 2 * ROWS_PPS * C::STAGE_BYTES + (BLK_WIN + 4) * 4);
-  int* scratch = (int*)smem;  // the stage area is idle until the first segment
-  const Sched sc = sched_at(sched_base, a.B);
-  const Shares sh = build_schedule<THREADS>(a, sc, scratch);
-  if ((int)blockIdx.x >= sh.n) return;
-  int u = 0, end = 0, page0, page1;
-  Item it;
-  bool pending;
-  if (sh.aligned) {
-    pending = aligned_share(a, sc, sh, blockIdx.x, &it, &page0, &page1);
-  } else {
-    share_range(a, sc, sh, &u, &end);
-    pending = next_segment(a, sc, sh, &u, end, &it, &page0, &page1);
-  }
-  for (; pending; pending = !sh.aligned && next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
-    const bool complete = (page0 == 0) && (page1 == it.np);
-    float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    segment_rows<D, NT, NW>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
-    if (!complete) announce_partial<D, true, THREADS, 2>(a, sc, it, sh, page0, page1, &merge_flag);
+  Seg seg;
+  int next;
+  const int nseg = plan_begin(a, &seg, &next);
+  for (int i = 0; i < nseg; ++i) {
+    if (i > 0) {
+      seg = plan_segment(a, next + i - 1);
+      if (!seg_ok(a, seg)) break;
+    }
+    const bool complete = seg_complete(seg);
+    float* pslot = partial_slot(a, blockIdx.x, seg.page0 == 0 ? 1 : 0, D);
+    segment_rows<D, NT, NW>(a, smem, seg, complete, pslot);
+    if (!complete) announce_partial<D, true, THREADS, 2>(a, seg, &merge_flag);
   }
 }
 
@@ -1517,8 +1088,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
 // (one per page) and they are combined once at the end of the segment.
 // ---------------------------------------------------------------------------------------------
 template <int D>
-__device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int page0, int page1, int L,
-                            bool complete, float* pslot) {
+__device__ void segment_f32(const AttnArgs& a, char* smem, const Seg& it, bool complete, float* pslot) {
   constexpr int QD = D / 4;  // floats per lane per key
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -1526,6 +1096,7 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
   const int k = lane & 15;
   const int g = lane >> 4;
   const int R = it.nq * a.G;
+  const int page0 = it.page0, page1 = it.page1, L = it.L;
 
   float* qtile = (float*)smem;                           // [F32_ROWS][D]
   int* rowslot = (int*)(qtile + F32_ROWS * D);
@@ -1558,6 +1129,10 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
 #pragma unroll
     for (int e = 0; e < QD; ++e) acc[r][e] = 0.f;
   }
+  // slots past the last row's own slot have never been written and may hold anything: see below
+  int last_slot = 0;
+#pragma unroll
+  for (int r = 0; r < F32_ROWS; ++r) last_slot = max(last_slot, rowslot[r]);
   const long bt_base = (long)it.s * a.kv.max_blocks_per_seq;
   const uint8_t* owner_row = a.slot_owner ? a.slot_owner + (long)it.s * a.owner_stride : nullptr;
 
@@ -1577,6 +1152,10 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
       kv_v[e] = y.x; kv_v[e + 1] = y.y; kv_v[e + 2] = y.z; kv_v[e + 3] = y.w;
     }
     const int j = P * ASPD_BLOCK + k;
+    if (j > last_slot) {  // zero weight times a NaN would be a NaN
+#pragma unroll
+      for (int e = 0; e < QD; ++e) kv_v[e] = 0.f;
+    }
     const int own = (owner_row && j >= L && j < a.owner_stride) ? owner_row[j] : 0;
 #pragma unroll
     for (int r = 0; r < F32_ROWS; ++r) {
@@ -1647,35 +1226,29 @@ __device__ void segment_f32(const AttnArgs& a, char* smem, const Item& it, int p
 }
 
 template <int D>
-size_t f32_smem_bytes(int B) {
-  return F32_ROWS * D * 4 + 2 * F32_ROWS * 4 + (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4 + (size_t)sched_ints(B) * 4;
+size_t f32_smem_bytes() {
+  return F32_ROWS * D * 4 + 2 * F32_ROWS * 4 + (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4;
 }
 
+// One workgroup per compute unit stays resident (271 vector registers per lane at head_dim 128, 150 KB of
+// LDS); the grid is twice that, so a compute unit takes its second workgroup when the first is done.
 template <int D>
 __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int merge_flag;
-  int* sched_base = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4 +
-                          (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4);
-  int* scratch = (int*)(smem + F32_ROWS * D * 4 + 2 * F32_ROWS * 4);  // idle until the first segment ends
-  const Sched sc = sched_at(sched_base, a.B);
-  const Shares sh = build_schedule<THREADS>(a, sc, scratch);
-  if ((int)blockIdx.x >= sh.n) return;
-  int u = 0, end = 0, page0, page1;
-  Item it;
-  bool pending;
-  if (sh.aligned) {
-    pending = aligned_share(a, sc, sh, blockIdx.x, &it, &page0, &page1);
-  } else {
-    share_range(a, sc, sh, &u, &end);
-    pending = next_segment(a, sc, sh, &u, end, &it, &page0, &page1);
-  }
-  for (; pending; pending = !sh.aligned && next_segment(a, sc, sh, &u, end, &it, &page0, &page1)) {
-    const bool complete = (page0 == 0) && (page1 == it.np);
-    float* pslot = partial_slot(a, blockIdx.x, page0 == 0 ? 1 : 0, D);
-    segment_f32<D>(a, smem, it, page0, page1, sc.L[it.s], complete, pslot);
+  Seg seg;
+  int next;
+  const int nseg = plan_begin(a, &seg, &next);
+  for (int i = 0; i < nseg; ++i) {
+    if (i > 0) {
+      seg = plan_segment(a, next + i - 1);
+      if (!seg_ok(a, seg)) break;
+    }
+    const bool complete = seg_complete(seg);
+    float* pslot = partial_slot(a, blockIdx.x, seg.page0 == 0 ? 1 : 0, D);
+    segment_f32<D>(a, smem, seg, complete, pslot);
     // F32_ROWS rows of D / 4 chunks never exceed the workgroup's threads: one element per thread
-    if (!complete) announce_partial<D, false, THREADS, 1>(a, sc, it, sh, page0, page1, &merge_flag);
+    if (!complete) announce_partial<D, false, THREADS, 1>(a, seg, &merge_flag);
   }
 }
 
@@ -1687,7 +1260,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
 // item" slots of the following ones.
 // ---------------------------------------------------------------------------------------------
 template <int D, bool BF16, int THREADS, int ELEMS>
-__device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_last) {
+__device__ void merge_item(const AttnArgs& a, const Seg& it, int owner, int w_last) {
   constexpr int CPR = D / 4;  // float4 chunks per row
   // ELEMS: (row, chunk) elements a thread combines concurrently; BATCH: partials fetched at once, per
   // element.  A second batch costs a second round trip to memory, so the batch is as large as the
@@ -1769,19 +1342,10 @@ __device__ void merge_item(const AttnArgs& a, const Item& it, int owner, int w_l
   }
 }
 
-// Called by every thread of the workgroup after it has written a partial of `it`.
+// Called by every thread of the workgroup after it has written a partial of the item of `it`.
 template <int D, bool BF16, int THREADS, int ELEMS>
-__device__ void announce_partial(const AttnArgs& a, const Sched& sc, const Item& it, const Shares& sh, int page0,
-                                 int page1, int* flag /* LDS */, int* owner_out, int* w_last_out) {
-  // the workgroups that hold the item's first and last page
-  const int owner = page0 == 0 ? (int)blockIdx.x : share_owner(a, sc, sh, it.first_unit + sh.pad);
-  const int w_last = page1 == it.np ? (int)blockIdx.x : share_owner(a, sc, sh, it.first_unit + sh.pad + it.np - 1);
-  if (owner_out) *owner_out = owner;
-  if (w_last_out) *w_last_out = w_last;
-  announce_partial_to<D, BF16, THREADS, ELEMS>(a, it, owner, w_last, flag);
-}
-template <int D, bool BF16, int THREADS, int ELEMS>
-__device__ void announce_partial_to(const AttnArgs& a, const Item& it, int owner, int w_last, int* flag /* LDS */) {
+__device__ void announce_partial(const AttnArgs& a, const Seg& it, int* flag /* LDS */) {
+  const int owner = it.owner, w_last = it.w_last;
   // the write-through stores of the partial have completed before the arrival is counted
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
@@ -1806,53 +1370,6 @@ __device__ void announce_partial_to(const AttnArgs& a, const Item& it, int owner
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
-// Rows per row group and queries per row group.  For bf16 the group is `nt` MFMA tiles of 16 rows:
-// as few as the caller's bound on new tokens per sequence allows (fewer tiles leave more registers
-// for loads in flight), three when there is no bound.  A sequence with more rows than one group
-// holds is processed in several groups, whatever the hint said.
-int rows_per_group(const aspd_kv* kv, int max_new_per_seq, int* qpg, int* nt) {
-  const int G = kv->num_q_heads / kv->num_kv_heads;
-  int cap = F32_ROWS;
-  *nt = 0;
-  if (kv->dtype == ASPD_BF16) {
-    int tiles = NT_MAX;
-    if (max_new_per_seq > 0) tiles = std::min(NT_MAX, (max_new_per_seq * G + 15) / 16);
-    while (tiles < NT_MAX && 16 * tiles < G) ++tiles;
-    cap = 16 * tiles;
-    *nt = tiles;
-  }
-  if (G > cap) return 0;
-  *qpg = cap / G;
-  return cap;
-}
-
-// Compute units of the current device (256 when there is none to ask, as on a build host).
-constexpr int MAX_DEVICES = 64;
-int device_cu_count() {
-  static std::atomic<int> cached[MAX_DEVICES];
-  int dev = 0, n = 0;
-  if (hipGetDevice(&dev) != hipSuccess) return 256;
-  if (dev >= 0 && dev < MAX_DEVICES && (n = cached[dev].load(std::memory_order_relaxed)) > 0) return n;
-  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
-  if (dev >= 0 && dev < MAX_DEVICES) cached[dev].store(n, std::memory_order_relaxed);
-  return n;
-}
-
-// Workgroups of the largest grid an attention launch uses on the current device.
-long grid_limit(int dtype, bool by_rows) {
-  long nwg = (dtype == ASPD_BF16 ? 1L : 2L) * device_cu_count();
-  if (by_rows) nwg = std::min(nwg, (long)MAX_WG_ROWS);
-  return std::min(nwg, (long)MAX_WG);
-}
-// Scratch a launch of `nwg` workgroups with row groups of `rows_cap` rows needs: the head (counters,
-// records) and two partial slots per workgroup.
-size_t scratch_need(int head_dim, long nwg, int rows_cap) {
-  return PARTIAL_OFFSET + (size_t)2 * nwg * rows_cap * (head_dim + 4) * sizeof(float);
-}
-
-// Process-wide cap of the attention grids (0: none), see aspd_set_max_workgroups.
-std::atomic<int> g_workgroup_cap{0};
-
 constexpr int LDS_BYTES = 160 * 1024;  // per compute unit on gfx950
 constexpr int STATIC_LDS_RESERVE = 256;  // room for the kernels' few static LDS variables
 
@@ -1869,6 +1386,13 @@ int allow_big_lds(const void* kernel) {
   return ASPD_OK;
 }
 
+// Workspace: arrival counters, room for a plan (used when the step brings none that fits the launch),
+// two partial slots per workgroup.
+size_t plan_area_bytes(size_t plan_words) { return (plan_words * sizeof(int32_t) + 255) & ~(size_t)255; }
+size_t scratch_need(int head_dim, size_t plan_words, long nwg, int rows_cap) {
+  return COUNTER_BYTES + plan_area_bytes(plan_words) + (size_t)2 * nwg * rows_cap * (head_dim + 4) * sizeof(float);
+}
+
 enum Mode { MODE_PARALLEL, MODE_CHUNK, MODE_SERIAL };
 
 int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const aspd_step* step, const void* q_d,
@@ -1878,7 +1402,8 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   if (rc != ASPD_OK) return rc;
   if (!state || !step || state->B <= 0 || !state->stage_base_d || !state->seq_len_d) return ASPD_ERR_INVALID_ARG;
   if (state->B > ASPD_MAX_BATCH) return ASPD_ERR_UNSUPPORTED;
-  if (step->NQ < 0 || step->max_new_per_seq < 0 || !step->cu_seq_new_d) return ASPD_ERR_INVALID_ARG;
+  if (step->NQ < 0 || step->max_new_per_seq < 0 || step->max_workgroups < 0 || !step->cu_seq_new_d)
+    return ASPD_ERR_INVALID_ARG;
   if (step->NQ == 0) return ASPD_OK;
   if (!step->q_branch_d || !step->logical_slot_d || !q_d || !out_d) return ASPD_ERR_INVALID_ARG;
   if (((uintptr_t)q_d & 15) || ((uintptr_t)out_d & 15)) return ASPD_ERR_INVALID_ARG;
@@ -1890,67 +1415,46 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
         ((uintptr_t)state->slot_owner_d & 3))
       return ASPD_ERR_INVALID_ARG;
   }
-  int qpg = 0, nt = 0;
-  int rows_cap = rows_per_group(kv, step->max_new_per_seq, &qpg, &nt);
-  if (rows_cap == 0) return ASPD_ERR_UNSUPPORTED;
-  // Branch chunks bring many rows per KV head: the waves then split the rows (one fetch of the pages per
-  // ROWS_NW * 16 * ROWS_NT rows) instead of the keys.
-  const int G_ = kv->num_q_heads / kv->num_kv_heads;
-  // Calls that say so through the hint (a prefill through the serial call, say) take the same kernel.
-  const bool many_rows = step->max_new_per_seq * G_ > 16 * NT_MAX;
-  const bool by_rows = kv->dtype == ASPD_BF16 && G_ <= 16 * NT_MAX && (long)step->NQ * G_ > 16 * NT_MAX &&
-                       (many_rows || (mode == MODE_CHUNK && step->max_new_per_seq == 0));
-  if (by_rows) {
-    rows_cap = ROWS_NW * 16 * ROWS_NT;
-    qpg = rows_cap / G_;
-  }
-  if (aspd_workspace_bytes(kv, state->B, step->NQ) == 0) return ASPD_ERR_INVALID_ARG;
+  AttnVariant v;
+  if (!aspd_choose_variant(kv, state->B, step->NQ, step->max_new_per_seq, step->max_workgroups, mode == MODE_CHUNK,
+                           branches, &v))
+    return ASPD_ERR_UNSUPPORTED;
   if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
-  const long nwg_limit = grid_limit(kv->dtype, by_rows);
-  if (workspace_bytes < scratch_need(kv->head_dim, nwg_limit, rows_cap)) return ASPD_ERR_WORKSPACE;
+  const size_t plan_words = aspd_plan_words(kv, v, state->B, step->NQ);
+  if (workspace_bytes < scratch_need(kv->head_dim, plan_words, v.nwg, v.rows_cap)) return ASPD_ERR_WORKSPACE;
+  hipStream_t hs = (hipStream_t)stream;
+
+  // The step's own plan when it was built for this launch shape; otherwise (no plan buffer, a hint that
+  // changed since, the other entry point) one is built now, into the workspace, by the same kernel.
+  const int32_t* plan = step->plan_d;
+  if (!plan || step->plan_key != aspd_plan_key(v, state->B) || step->plan_bytes < plan_words * sizeof(int32_t)) {
+    int32_t* own = (int32_t*)((char*)workspace_d + COUNTER_BYTES);
+    rc = aspd_plan_launch(kv, v, state->B, state->stage_base_d, state->seq_len_d, step->cu_seq_new_d, own, hs);
+    if (rc != ASPD_OK) return rc;
+    plan = own;
+  }
 
   AttnArgs a;
   a.kv = make_view(kv);
-  a.stage_base = state->stage_base_d;
-  a.seq_len = state->seq_len_d;
   a.cu_branches = branches ? state->cu_branches_d : nullptr;
   a.slot_owner = branches ? state->slot_owner_d : nullptr;
   a.owner_stride = branches ? state->owner_stride : 0;
-  a.cu_seq_new = step->cu_seq_new_d;
   a.q_branch = step->q_branch_d;
   a.logical_slot = step->logical_slot_d;
   a.q = q_d;
   a.out = out_d;
   a.lse = lse_d;
   a.counters = (int*)workspace_d;
-  a.records = (int*)((char*)workspace_d + COUNTER_BYTES);
+  a.partial = (float*)((char*)workspace_d + COUNTER_BYTES + plan_area_bytes(plan_words));
+  a.plan = plan;
   a.NQ = step->NQ;
-  a.partial = (float*)((char*)workspace_d + PARTIAL_OFFSET);
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)kv->head_dim) : sm_scale) * LOG2E;
   a.B = state->B;
+  a.nwg = v.nwg;
   a.G = kv->num_q_heads / kv->num_kv_heads;
-  a.qpg = qpg;
-  a.rows_cap = rows_cap;
-  // A segment's fixed cost (start-up, reduction across waves, partial, merge) in units of the time one
-  // more page takes its workgroup: measured at about 12 us against 0.4 us per 8 KB page when streaming,
-  // and against 0.9 us per page in the compute-bound kernels.
-  if (by_rows || kv->dtype != ASPD_BF16) a.pad = PAD_COMPUTE;
-  else a.pad = PAD_STREAM * 128 / kv->head_dim;
+  a.qpg = v.qpg;
+  a.rows_cap = v.rows_cap;
 
-  // Grid: as many workgroups as stay resident at once (one of 8 waves per compute unit for bf16, two of
-  // 4 waves for fp32), never more than the pages can feed.
-  const long groups_max = (long)state->B + step->NQ / qpg;
-  const long units_max = groups_max * kv->num_kv_heads * kv->max_blocks_per_seq;
-  long nwg = nwg_limit;
-  // pages are read once when no sequence can have more than one row group
-  const bool stream_once = step->max_new_per_seq > 0 && step->max_new_per_seq <= qpg;
-  nwg = std::min(nwg, (units_max + MIN_PAGES_PER_WG - 1) / MIN_PAGES_PER_WG);
-  const int cap = g_workgroup_cap.load(std::memory_order_relaxed);
-  if (cap > 0) nwg = std::min(nwg, (long)cap);
-  nwg = std::max(1L, std::min(nwg, (long)MAX_WG));
-  a.nwg = (int)nwg;
-
-  hipStream_t hs = (hipStream_t)stream;
   const int D = kv->head_dim;
 #define ASPD_LAUNCH(KERNEL, NTHREADS, SMEM)                                          \
   do {                                                                               \
@@ -1960,36 +1464,37 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
     hipLaunchKernelGGL(KERNEL, dim3(a.nwg), dim3(NTHREADS), SMEM, hs, a);            \
     ASPD_HIP_CHECK(hipGetLastError());                                               \
   } while (0)
-  if (by_rows) {
+  if (v.kernel == KERNEL_BF16_ROWS) {
     if (D == 128)
       ASPD_LAUNCH((attn_bf16_rows_kernel<128, ROWS_NT, ROWS_NW>), ROWS_NW * 64,
-                  (rows_smem_bytes<128, ROWS_NT, ROWS_NW>(state->B)));
+                  (rows_smem_bytes<128, ROWS_NT, ROWS_NW>()));
     else
       ASPD_LAUNCH((attn_bf16_rows_kernel<64, ROWS_NT, ROWS_NW>), ROWS_NW * 64,
-                  (rows_smem_bytes<64, ROWS_NT, ROWS_NW>(state->B)));
-  } else if (kv->dtype == ASPD_BF16) {
+                  (rows_smem_bytes<64, ROWS_NT, ROWS_NW>()));
+  } else if (v.kernel == KERNEL_BF16_STREAM) {
+    // pages that no second row group reads are fetched with non-temporal loads
 #define ASPD_BF16_CASE(DD, NN)                                                                            \
   do {                                                                                                    \
-    if (stream_once)                                                                                      \
-      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, BF16_NW(NN), BF16_PF(NN), true>), BF16_NW(NN) * 64,           \
-                  (bf16_smem_bytes<DD, NN, BF16_NW(NN)>(state->B)));                                      \
+    if (v.stream_once)                                                                                    \
+      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, STREAM_NW, STREAM_PF, true>), STREAM_NW * 64,                 \
+                  (bf16_smem_bytes<DD, NN, STREAM_NW>()));                                                \
     else                                                                                                  \
-      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, BF16_NW(NN), BF16_PF(NN), false>), BF16_NW(NN) * 64,          \
-                  (bf16_smem_bytes<DD, NN, BF16_NW(NN)>(state->B)));                                      \
+      ASPD_LAUNCH((attn_bf16_kernel<DD, NN, STREAM_NW, STREAM_PF, false>), STREAM_NW * 64,                \
+                  (bf16_smem_bytes<DD, NN, STREAM_NW>()));                                                \
   } while (0)
     if (D == 128) {
-      if (nt == 1) ASPD_BF16_CASE(128, 1);
-      else if (nt == 2) ASPD_BF16_CASE(128, 2);
+      if (v.nt == 1) ASPD_BF16_CASE(128, 1);
+      else if (v.nt == 2) ASPD_BF16_CASE(128, 2);
       else ASPD_BF16_CASE(128, 3);
     } else {
-      if (nt == 1) ASPD_BF16_CASE(64, 1);
-      else if (nt == 2) ASPD_BF16_CASE(64, 2);
+      if (v.nt == 1) ASPD_BF16_CASE(64, 1);
+      else if (v.nt == 2) ASPD_BF16_CASE(64, 2);
       else ASPD_BF16_CASE(64, 3);
     }
 #undef ASPD_BF16_CASE
   } else {
-    if (D == 128) ASPD_LAUNCH(attn_f32_kernel<128>, THREADS, f32_smem_bytes<128>(state->B));
-    else ASPD_LAUNCH(attn_f32_kernel<64>, THREADS, f32_smem_bytes<64>(state->B));
+    if (D == 128) ASPD_LAUNCH(attn_f32_kernel<128>, THREADS, f32_smem_bytes<128>());
+    else ASPD_LAUNCH(attn_f32_kernel<64>, THREADS, f32_smem_bytes<64>());
   }
 #undef ASPD_LAUNCH
   return ASPD_OK;
@@ -2001,23 +1506,33 @@ extern "C" size_t aspd_workspace_bytes(const aspd_kv* kv, int32_t B, int32_t NQ)
   if (!kv || B <= 0 || NQ < 0 || kv->num_kv_heads <= 0 || kv->num_q_heads <= 0) return 0;
   if (kv->head_dim != 64 && kv->head_dim != 128) return 0;
   if (kv->dtype != ASPD_F32 && kv->dtype != ASPD_BF16) return 0;
-  int qpg = 0, nt = 0;
-  const int rows_cap = rows_per_group(kv, 0, &qpg, &nt);  // the widest row group of the streaming kernels
-  if (rows_cap == 0) return 0;
-  // two partial slots per workgroup of the largest grid of the current device (of a device with 256
-  // compute units when there is none), for whichever kernel the NQ rows may be given to
-  size_t need = scratch_need(kv->head_dim, grid_limit(kv->dtype, false), rows_cap);
-  const long G = kv->num_q_heads / kv->num_kv_heads;
-  if (kv->dtype == ASPD_BF16 && (long)NQ * G > 16 * NT_MAX && G <= 16 * NT_MAX)  // rows enough for the row-splitting kernel
-    need = std::max(need, scratch_need(kv->head_dim, grid_limit(kv->dtype, true), ROWS_NW * 16 * ROWS_NT));
+  if (kv->num_q_heads % kv->num_kv_heads != 0 || kv->max_blocks_per_seq <= 0) return 0;
+  // the largest need over the launch shapes the NQ rows may take (hints 0 .. 3 tiles' worth, either call)
+  const int G = kv->num_q_heads / kv->num_kv_heads;
+  size_t need = 0;
+  for (int tiles = 0; tiles <= NT_MAX + 1; ++tiles) {
+    for (int chunk = 0; chunk < 2; ++chunk) {
+      AttnVariant v;
+      const int hint = tiles == 0 ? 0 : std::max(1, 16 * tiles / G);
+      if (!aspd_choose_variant(kv, B, NQ, hint, 0, chunk != 0, true, &v)) continue;
+      need = std::max(need, scratch_need(kv->head_dim, aspd_plan_words(kv, v, B, NQ), v.nwg, v.rows_cap));
+    }
+  }
   return need;
 }
 
+extern "C" size_t aspd_plan_bytes(const aspd_kv* kv, int32_t B, int32_t NQ) {
+  if (!kv || B <= 0 || NQ < 0 || kv->num_kv_heads <= 0 || kv->num_q_heads <= 0) return 0;
+  if (kv->num_q_heads % kv->num_kv_heads != 0) return 0;
+  // a row group holds at least one query; a grid at most MAX_WG workgroups
+  const size_t items = ((size_t)B + (size_t)NQ) * kv->num_kv_heads;
+  return ((size_t)PLAN_HDR * MAX_WG + (size_t)PLAN_SEG * (items + MAX_WG)) * sizeof(int32_t);
+}
+
 namespace {
-// Counters at zero; records all zero, which no launch takes for a segment (it would have no rows).
 __global__ void zero_counters_kernel(int* head) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < PARTIAL_OFFSET / 4) head[i] = 0;
+  if (i < COUNTER_BYTES / 4) head[i] = 0;
 }
 }  // namespace
 
@@ -2050,21 +1565,17 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict
 
 extern "C" int aspd_probe_read_bandwidth(const void* src_d, size_t bytes, void* sink_d, void* stream) {
   if (!src_d || !sink_d || ((uintptr_t)src_d & 15) || bytes < 16) return ASPD_ERR_INVALID_ARG;
-  const int grid = 8 * device_cu_count();
+  const int grid = 8 * aspd_device_cu_count();
   hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const u32x4*)src_d,
                      bytes / 16, (unsigned*)sink_d);
   ASPD_HIP_CHECK(hipGetLastError());
   return ASPD_OK;
 }
 
-extern "C" int32_t aspd_set_max_workgroups(int32_t max_workgroups) {
-  return g_workgroup_cap.exchange(max_workgroups > 0 ? max_workgroups : 0, std::memory_order_relaxed);
-}
-
 extern "C" int aspd_workspace_init(void* workspace_d, size_t workspace_bytes, void* stream) {
   if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
-  if (workspace_bytes < (size_t)PARTIAL_OFFSET) return ASPD_ERR_WORKSPACE;
-  hipLaunchKernelGGL(zero_counters_kernel, dim3(PARTIAL_OFFSET / 4 / 256), dim3(256), 0, (hipStream_t)stream,
+  if (workspace_bytes < (size_t)COUNTER_BYTES) return ASPD_ERR_WORKSPACE;
+  hipLaunchKernelGGL(zero_counters_kernel, dim3(COUNTER_BYTES / 4 / 256), dim3(256), 0, (hipStream_t)stream,
                      (int*)workspace_d);
   ASPD_HIP_CHECK(hipGetLastError());
   return ASPD_OK;
@@ -2102,6 +1613,7 @@ namespace {
 // Device address of `scratch` on the current device (the array's name is only a host-side handle).
 int static_scratch(void** out) {
   static std::mutex mu;
+  constexpr int MAX_DEVICES = 64;
   static void* ptrs[MAX_DEVICES];
   int dev = 0;
   ASPD_HIP_CHECK(hipGetDevice(&dev));

@@ -5,7 +5,7 @@
 // sequence: the packed row of its first token (the number of tokens appended to earlier sequences)
 // and nothing else, so it sums new_len over the earlier branches itself instead of waiting for a
 // batch-wide scan: new_len is an input no workgroup writes, hence no ordering between workgroups.
-#include "aspd_common.h"
+#include "aspd_plan.h"
 
 namespace {
 
@@ -320,6 +320,19 @@ extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int3
   if (out->NQ > 0 && (!out->q_seq_d || !out->q_branch_d || !out->position_ids_d || !out->logical_slot_d ||
                       !out->slot_mapping_d || !out->kv_len_d))
     return ASPD_ERR_INVALID_ARG;
+  if (out->max_new_per_seq < 0 || out->max_workgroups < 0) return ASPD_ERR_INVALID_ARG;
+  // the plan of the step's attention launches, for the launch shape the step's hints select
+  AttnVariant variant;
+  bool with_plan = false;
+  out->plan_key = 0;
+  if (out->plan_d && out->NQ > 0 &&
+      aspd_choose_variant(kv, state->B, out->NQ, out->max_new_per_seq, out->max_workgroups, false,
+                          stage != ASPD_STAGE_SERIAL, &variant)) {
+    if (((uintptr_t)out->plan_d & 255) ||
+        out->plan_bytes < aspd_plan_words(kv, variant, state->B, out->NQ) * sizeof(int32_t))
+      return ASPD_ERR_INVALID_ARG;
+    with_plan = true;
+  }
   KvView kvv = make_view(kv);
   StepView spv = make_view(out);
   if (stage == ASPD_STAGE_PARALLEL || stage == ASPD_STAGE_MIXED) {
@@ -334,6 +347,12 @@ extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int3
                        same_seq);
   }
   ASPD_HIP_CHECK(hipGetLastError());
+  if (with_plan) {
+    rc = aspd_plan_launch(kv, variant, state->B, state->stage_base_d, state->seq_len_d, out->cu_seq_new_d,
+                          out->plan_d, hs);
+    if (rc != ASPD_OK) return rc;
+    out->plan_key = aspd_plan_key(variant, state->B);
+  }
   return ASPD_OK;
 }
 

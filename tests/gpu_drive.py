@@ -23,7 +23,8 @@ class GpuBatch:
         self.kv = A.KVCache(k.to(self.dev), v.to(self.dev),
                             torch.from_numpy(wl.block_tables).to(self.dev), wl.num_q_heads)
         self.state = A.BatchState(wl.B, wl.max_blocks_per_seq * wl.block_size, self.dev)
-        self.workspace = A.new_workspace(self.kv, wl.B, 1 << 20)   # any number of rows, chunk calls included
+        # for any step this batch can take: no call brings more rows than the block tables hold tokens
+        self.workspace = A.new_workspace(self.kv, wl.B, int((wl.block_tables >= 0).sum()) * wl.block_size)
 
     def _dev_i32(self, x):
         return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(self.dev)

@@ -217,32 +217,31 @@ def test_mixed_rejects_main_tokens_under_open_branches(A):
 
 # --------------------------------------------------------------------------------------------- limits
 def test_capped_grid_and_long_segments(A):
-    """With the grid capped to two workgroups a 70 000-token sequence gives each of them more pages
-    than the block-id window holds (512), so the kernels walk several windows; results must not
-    depend on the cap.  Also: the cap is honoured when lifted again."""
+    """With the grid capped to two workgroups (aspd_step.max_workgroups) a 70 000-token sequence gives each
+    of them more pages than the block-id window holds (512), so the kernels walk several windows; results
+    must not depend on the cap.  The cap is set before the metadata call for the decode step (the step's
+    plan is built for it) and after it for the chunk (the attention call then builds its own plan)."""
     wl = W.random_small(seed=61, dtype="bf16", head_dim=64, num_q_heads=2, num_kv_heads=1, batch=1,
                         prefix_range=(70000, 70000), branches_range=(3, 3), branch_len_range=(40, 40),
                         extra_tokens_per_branch=8)
     gb, tt = _grow_both(A, wl, np.minimum(wl.branch_len, 2) - 1, False)
-    prev = A.aspd_set_max_workgroups(2)
-    try:
-        ones = np.ones(wl.NB, dtype=np.int32)
-        meta = tt.append_parallel(ones)
-        step = gb.parallel(ones)
-        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label="cap 2 parallel")
-        chunk = np.full(wl.NB, 30, dtype=np.int32)           # 90 tokens x 2 heads: the row-splitting kernel
-        meta = tt.append_parallel(chunk)
-        step = gb.parallel(chunk)
-        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label="cap 2 chunk")
-        assert A.aspd_set_max_workgroups(0) == 2
-        tt.merge()
-        gb.merge()
-        one = np.ones(wl.B, dtype=np.int32)
-        meta = tt.append_serial(one)
-        step = gb.serial(one)
-        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label="uncapped serial")
-    finally:
-        A.aspd_set_max_workgroups(prev)
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = A.aspd_build_branch_meta(gb.kv, gb.state, A.STAGE_PARALLEL, gb._dev_i32(ones), NQ=int(ones.sum()),
+                                    max_workgroups=2)
+    assert step.plan_key != 0
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label="cap 2 parallel")
+    chunk = np.full(wl.NB, 30, dtype=np.int32)           # 90 tokens x 2 heads: the row-splitting kernel
+    meta = tt.append_parallel(chunk)
+    step = gb.parallel(chunk)
+    step.max_workgroups = 2
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label="cap 2 chunk")
+    tt.merge()
+    gb.merge()
+    one = np.ones(wl.B, dtype=np.int32)
+    meta = tt.append_serial(one)
+    step = gb.serial(one)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label="uncapped serial")
 
 
 @pytest.mark.parametrize("branches", [3, 6], ids=["one_tile", "two_tiles"])

@@ -64,8 +64,8 @@ def test_static_scratch_matches_the_workspace_call_twice_in_a_row(A, dtype):
 def test_static_scratch_rejects_what_does_not_fit(A):
     """A step whose hint sends it to the row-splitting kernel needs 69 MB of partial slots: refused with
     its own error code, nothing launched, output untouched."""
-    wl = W.random_small(seed=813, batch=2, prefix_range=(100, 300), branches_range=(20, 20), branch_len_range=(2, 4),
-                        num_q_heads=32, num_kv_heads=8)
+    wl = W.random_small(seed=813, batch=4, prefix_range=(3000, 4000), branches_range=(20, 20), branch_len_range=(2, 4),
+                        num_q_heads=32, num_kv_heads=8)    # pages enough for a full grid of the row-splitting kernel
     gb, step = _batch_at_decode_step(A, wl)
     step.max_new_per_seq = 64           # 64 tokens x 4 heads per KV head: more rows than the streaming kernels take
     q = wl.draw_q(step.NQ).to(gb.dev)
