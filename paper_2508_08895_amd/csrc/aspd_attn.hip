@@ -53,7 +53,13 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;  // 16 bytes in 
                                                                   // vector, so arrays of it stay in VGPRs)
 
 struct AttnArgs {
+  // (what a workgroup needs before its first page loads leave comes first: one line of the argument block)
+  const int32_t* plan;          // the step's plan for this launch shape (aspd_plan.h)
   KvView         kv;
+  int            NQ;            // rows of q / out
+  int            B;
+  int            nwg;
+  int            qpg;           // queries per row group
   const int32_t* cu_branches;   // null when no row carries a branch tag
   const uint8_t* slot_owner;
   int            owner_stride;
@@ -64,13 +70,8 @@ struct AttnArgs {
   float*         lse;
   float*         partial;       // [2 * nwg] slots of {[rows_cap][D] accumulators, [rows_cap][4]: reference, sum, pad}
   int*           counters;      // [nwg] arrivals per split item, zero between calls
-  const int32_t* plan;          // the step's plan for this launch shape (aspd_plan.h)
-  int            NQ;            // rows of q / out
   float          scale_log2;    // sm_scale * log2(e)
-  int            B;
-  int            nwg;
   int            G;             // query heads per KV head
-  int            qpg;           // queries per row group
   int            rows_cap;      // rows per row group the partial slots are sized for
 };
 
@@ -89,16 +90,20 @@ struct Seg {
 // Plan words through the scalar (constant) path: the address is the same in every lane, the words were
 // written by an earlier kernel, and scalar loads neither take vector registers nor queue up with the
 // page loads.
+typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ i32x16 load_words16(const int32_t* p /* 64-byte aligned, uniform */) {
+  return *(const __attribute__((address_space(4))) i32x16*)(uintptr_t)p;
+}
 __device__ __forceinline__ i32x8 load_words8(const int32_t* p /* 32-byte aligned, uniform */) {
   return *(const __attribute__((address_space(4))) i32x8*)(uintptr_t)p;
 }
 __device__ __forceinline__ i32x2 load_words2(const int32_t* p /* 8-byte aligned, uniform */) {
   return *(const __attribute__((address_space(4))) i32x2*)(uintptr_t)p;
 }
-__device__ __forceinline__ Seg load_seg(const int32_t* p) {
-  const i32x8 w = load_words8(p);
+template <typename V>
+__device__ __forceinline__ Seg seg_of(const V& w) {
   Seg g;
   g.s = w[0] & 0xffff;
   g.h = (int)((unsigned)w[0] >> 16);
@@ -112,13 +117,16 @@ __device__ __forceinline__ Seg load_seg(const int32_t* p) {
   g.L = w[7];
   return g;
 }
+__device__ __forceinline__ Seg load_seg(const int32_t* p) { return seg_of(load_words8(p)); }
 // Everything a kernel derives an address from.  A plan is written by the library's own kernel; the
 // check keeps a workgroup that is handed anything else (a buffer of the wrong step, say) from reading
 // or writing outside the call's arrays: it then does nothing.
 __device__ __forceinline__ bool seg_ok(const AttnArgs& a, const Seg& g) {
-  return g.s < a.B && g.h < a.kv.num_kv_heads && g.q0 >= 0 && g.nq >= 1 && g.nq <= a.qpg && g.q0 <= a.NQ - g.nq &&
-         g.page0 >= 0 && g.page0 < g.page1 && g.page1 <= g.np && g.np <= a.kv.max_blocks_per_seq && g.L >= 0 &&
-         g.owner <= (int)blockIdx.x && (int)blockIdx.x <= g.w_last && g.w_last < a.nwg;
+  // (no short-circuit: one straight run of scalar compares instead of a chain of branches)
+  return (int)(g.s < a.B) & (int)(g.h < a.kv.num_kv_heads) & (int)(g.q0 >= 0) & (int)(g.nq >= 1) & (int)(g.nq <= a.qpg) &
+         (int)(g.q0 <= a.NQ - g.nq) & (int)(g.page0 >= 0) & (int)(g.page0 < g.page1) & (int)(g.page1 <= g.np) &
+         (int)(g.np <= a.kv.max_blocks_per_seq) & (int)(g.L >= 0) & (int)(g.owner <= (int)blockIdx.x) &
+         (int)((int)blockIdx.x <= g.w_last) & (int)(g.w_last < a.nwg);
 }
 __device__ __forceinline__ bool seg_complete(const Seg& g) { return g.page0 == 0 && g.page1 == g.np; }
 
@@ -458,14 +466,14 @@ __device__ __forceinline__ void segment_issue_ids(const AttnArgs& a, const Seg& 
     ld.d_slot = a.logical_slot[q];
     ld.d_branch = a.q_branch[q];
   }
-  // owner tags travel with the pair whenever the call has any (the rows that need them are not known yet)
-  ld.first.own[0] = ld.first.own[1] = 0;
-  if (owner_row) {
-    const uint8_t* own_p0 = owner_row + P0 * ASPD_BLOCK + 4 * g;
-    const int own_step = min(ASPD_BLOCK, a.owner_stride - 4 - (P0 * ASPD_BLOCK + 4 * g));  // stays inside the owner row
-    ld.first.own[0] = *(const uint32_t*)own_p0;
-    ld.first.own[1] = *(const uint32_t*)(own_p0 + own_step);
-  }
+  // Owner tags travel with the pair whenever the call has any (the rows that need them are not known yet).
+  // A call without tags loads two words it never looks at instead of branching: with the same loads in
+  // flight on every path the compiler's wait counts stay exact (a branch here made the page loads below
+  // wait for every load above).
+  const uint8_t* own_p0 = owner_row ? owner_row + P0 * ASPD_BLOCK + 4 * g : (const uint8_t*)a.logical_slot;
+  const int own_step = owner_row ? min(ASPD_BLOCK, a.owner_stride - 4 - (P0 * ASPD_BLOCK + 4 * g)) : 0;  // stays inside the owner row
+  ld.first.own[0] = *(const uint32_t*)own_p0;
+  ld.first.own[1] = *(const uint32_t*)(own_p0 + own_step);
 }
 // ... and the pages of the wave's first pair, from two block ids: those the plan carries for a
 // workgroup's first segment (one round trip after the kernel starts), or those just loaded from the
@@ -771,13 +779,22 @@ size_t bf16_smem_bytes() {
 }
 
 // What every kernel does first: its workgroup's header of the plan.  Returns the number of segments
-// (0: nothing to do, also for a header that fails seg_ok).
-__device__ __forceinline__ int plan_begin(const AttnArgs& a, Seg* first, int* next) {
+// (0: nothing to do, also for a header that fails seg_ok).  `ids`: the block ids of the pages
+// first_id, first_id + 1 of the first segment (first_id even, below PLAN_IDS).  Two loads, no branch
+// between them and their uses: scalar loads return in any order, so a wait between them would make each
+// a memory round trip of its own.
+__device__ __forceinline__ int plan_begin(const AttnArgs& a, Seg* first, int* next, int first_id = 0,
+                                          i32x2* ids = nullptr) {
+  static_assert(PLAN_HDR_NSEG == 8 && PLAN_HDR_NEXT == 9, "segment and counts in one 64-byte load");
   const int32_t* hdr = a.plan + (long)PLAN_HDR * blockIdx.x;
-  *first = load_seg(hdr);
-  const i32x2 m = load_words2(hdr + PLAN_HDR_NSEG);
-  *next = m[1];
-  return (m[0] > 0 && seg_ok(a, *first)) ? m[0] : 0;
+  const i32x16 w = load_words16(hdr);
+  const i32x2 b = load_words2(hdr + PLAN_HDR_IDS + first_id);
+  // (both are needed here, so neither load is moved further down, behind other waits)
+  asm volatile("" ::"s"(w[0]), "s"(b[0]), "s"(b[1]));
+  if (ids) *ids = b;
+  *first = seg_of(w);
+  *next = w[PLAN_HDR_NEXT];
+  return ((int)(w[PLAN_HDR_NSEG] > 0) & (int)seg_ok(a, *first)) ? w[PLAN_HDR_NSEG] : 0;
 }
 __device__ __forceinline__ Seg plan_segment(const AttnArgs& a, int index) {
   return load_seg(a.plan + (long)PLAN_HDR * a.nwg + (long)PLAN_SEG * index);
@@ -795,13 +812,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
   // the whole segment, the Q rows and the row descriptors all leave together.
   Seg seg;
   int next;
-  const int nseg = plan_begin(a, &seg, &next);
+  i32x2 ids;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const i32x2 ids = load_words2(a.plan + (long)PLAN_HDR * blockIdx.x + PLAN_HDR_IDS + 2 * wave);
+  const int nseg = plan_begin(a, &seg, &next, 2 * wave, &ids);
   if (nseg == 0) return;
   SegLoads<D, NT, NW> ld;
-  segment_issue_pair<D, NT, NW, STREAM>(a, seg, ld, ids[0], ids[1]);
+  // (loads return in order: the small ones first, the LDS set-up waits for them and not for the pages)
   segment_issue_ids<D, NT, NW>(a, seg, ld);
+  segment_issue_pair<D, NT, NW, STREAM>(a, seg, ld, ids[0], ids[1]);
+  asm volatile("" ::: "memory");  // the loads leave here, not where their results are first used
   for (int i = 0;;) {
     // the next segment's words are on their way while this one streams
     Seg after = seg;

@@ -13,7 +13,7 @@
 
 namespace {
 
-constexpr int PLAN_THREADS = 256;
+constexpr int PLAN_THREADS = 1024;  // one workgroup; a thread per workgroup of the largest attention grid
 
 struct PlanArgs {
   const int32_t* stage_base;
@@ -307,24 +307,19 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanArgs a) {
   const int tid = threadIdx.x;
   const Shares sh = build_schedule(a, sc, scratch);
 
-  // ---- pass 1: how many segments each workgroup has
-  constexpr int PER_T = MAX_WG / PLAN_THREADS;  // workgroups per thread, consecutive: thread t owns t * PER_T ..
-  int cnt[PER_T];
-  int sum = 0;
-#pragma unroll
-  for (int j = 0; j < PER_T; ++j) {
-    const int w = tid * PER_T + j;
-    cnt[j] = 0;
-    if (w < a.nwg) {
-      Walk wk = walk_begin(sc, sh, w);
-      Item it;
-      int p0, p1;
-      while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1)) ++cnt[j];
-    }
-    sum += max(cnt[j] - 1, 0);
+  // ---- pass 1: how many segments each workgroup has (thread w: workgroup w)
+  static_assert(PLAN_THREADS >= MAX_WG, "a thread per workgroup");
+  const int w = tid;
+  int cnt = 0;
+  if (w < a.nwg) {
+    Walk wk = walk_begin(sc, sh, w);
+    Item it;
+    int p0, p1;
+    while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1)) ++cnt;
   }
-  // exclusive scan of the extras over the workgroups
-  int incl = sum;
+  // exclusive scan, over the workgroups, of the segments beyond the first
+  const int extra = max(cnt - 1, 0);
+  int incl = extra;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const int v = __shfl_up(incl, off);
@@ -332,42 +327,38 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanArgs a) {
   }
   if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
   __syncthreads();
-  int run = incl - sum;
+  int run = incl - extra;
   for (int wv = 0; wv < (tid >> 6); ++wv) run += wave_tot[wv];
 
   // ---- pass 2: headers and segments
+  if (w >= a.nwg) return;
   int32_t* seg_list = a.plan + PLAN_HDR * a.nwg;
+  int32_t* hdr = a.plan + PLAN_HDR * w;
+  hdr[PLAN_HDR_NSEG] = cnt;
+  hdr[PLAN_HDR_NEXT] = run;
+  Walk wk = walk_begin(sc, sh, w);
+  Item it;
+  int p0, p1;
+  int i = 0;
+  while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1)) {
+    const int owner = p0 == 0 ? w : share_owner(a, sc, sh, it.first_unit + sh.pad);
+    const int w_last = p1 == it.np ? w : share_owner(a, sc, sh, it.first_unit + sh.pad + it.np - 1);
+    int32_t* d = i == 0 ? hdr : seg_list + PLAN_SEG * (run + i - 1);
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    *(i32x4*)d = i32x4{it.s | (it.h << 16), it.q0, it.nq, p0};
+    *(i32x4*)(d + 4) = i32x4{p1, it.np, owner | (w_last << 16), sc.L[it.s]};
+    if (i == 0) {
+      const int32_t* bt = a.block_tables + (long)it.s * a.max_blocks_per_seq;
+      int ids[PLAN_IDS];
 #pragma unroll
-  for (int j = 0; j < PER_T; ++j) {
-    const int w = tid * PER_T + j;
-    if (w >= a.nwg) break;
-    int32_t* hdr = a.plan + PLAN_HDR * w;
-    hdr[PLAN_HDR_NSEG] = cnt[j];
-    hdr[PLAN_HDR_NEXT] = run;
-    Walk wk = walk_begin(sc, sh, w);
-    Item it;
-    int p0, p1;
-    int i = 0;
-    while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1)) {
-      const int owner = p0 == 0 ? w : share_owner(a, sc, sh, it.first_unit + sh.pad);
-      const int w_last = p1 == it.np ? w : share_owner(a, sc, sh, it.first_unit + sh.pad + it.np - 1);
-      int32_t* d = i == 0 ? hdr : seg_list + PLAN_SEG * (run + i - 1);
-      d[0] = it.s | (it.h << 16);
-      d[1] = it.q0;
-      d[2] = it.nq;
-      d[3] = p0;
-      d[4] = p1;
-      d[5] = it.np;
-      d[6] = owner | (w_last << 16);
-      d[7] = sc.L[it.s];
-      if (i == 0) {
-        const int32_t* bt = a.block_tables + (long)it.s * a.max_blocks_per_seq;
-        for (int k = 0; k < PLAN_IDS; ++k)
-          hdr[PLAN_HDR_IDS + k] = min(max(bt[min(p0 + k, p1 - 1)], 0), a.num_blocks - 1);
-      }
-      ++i;
+      for (int k = 0; k < PLAN_IDS; ++k) ids[k] = bt[min(p0 + k, p1 - 1)];  // all on their way at once
+#pragma unroll
+      for (int k = 0; k < PLAN_IDS; k += 4)
+        *(i32x4*)(hdr + PLAN_HDR_IDS + k) =
+            i32x4{min(max(ids[k], 0), a.num_blocks - 1), min(max(ids[k + 1], 0), a.num_blocks - 1),
+                  min(max(ids[k + 2], 0), a.num_blocks - 1), min(max(ids[k + 3], 0), a.num_blocks - 1)};
     }
-    run += max(cnt[j] - 1, 0);
+    ++i;
   }
 }
 
