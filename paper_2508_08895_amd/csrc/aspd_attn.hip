@@ -1278,13 +1278,11 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
 // another.  The partials are the "starts item" slot of the first workgroup and the "continues
 // item" slots of the following ones.
 // ---------------------------------------------------------------------------------------------
-template <int D, bool BF16, int THREADS, int ELEMS>
-__device__ void merge_item(const AttnArgs& a, const Seg& it, int owner, int w_last) {
+template <int D, bool BF16, int THREADS, int ELEMS, int BATCH>
+__device__ void merge_parts(const AttnArgs& a, const Seg& it, int owner, int w_last) {
   constexpr int CPR = D / 4;  // float4 chunks per row
   // ELEMS: (row, chunk) elements a thread combines concurrently; BATCH: partials fetched at once, per
-  // element.  A second batch costs a second round trip to memory, so the batch is as large as the
-  // registers allow (sixteen in the one-tile streaming kernel, one wave per SIMD).
-  constexpr int BATCH = (BF16 && ELEMS == 2 && THREADS == 256) ? 16 : 8;
+  // element.
   const int R = it.nq * a.G;
   const long stride = (long)a.rows_cap * (D + 4);
   const int nparts = w_last - owner + 1;
@@ -1359,6 +1357,19 @@ __device__ void merge_item(const AttnArgs& a, const Seg& it, int owner, int w_la
       if (a.lse && cc[x] == 0) a.lse[(long)q * a.kv.num_q_heads + head] = (m[x] + log2f(l[x])) * LN2;
     }
   }
+}
+
+// A second batch costs a second round trip to memory, so the batch is as large as the registers allow
+// (sixteen in the one-tile streaming kernel, one wave per SIMD) - but no larger than the parts there are:
+// with one wave per SIMD the merge is bound by the instructions it issues, and every slot of a batch costs
+// its loads and its arithmetic whether a part stands behind it or not.
+template <int D, bool BF16, int THREADS, int ELEMS>
+__device__ void merge_item(const AttnArgs& a, const Seg& it, int owner, int w_last) {
+  constexpr bool WIDE = BF16 && ELEMS == 2 && THREADS == 256;
+  const int nparts = w_last - owner + 1;
+  if (nparts <= 4) merge_parts<D, BF16, THREADS, ELEMS, 4>(a, it, owner, w_last);
+  else if (!WIDE || nparts <= 8) merge_parts<D, BF16, THREADS, ELEMS, 8>(a, it, owner, w_last);
+  else merge_parts<D, BF16, THREADS, ELEMS, WIDE ? 16 : 8>(a, it, owner, w_last);
 }
 
 // Called by every thread of the workgroup after it has written a partial of the item of `it`.
