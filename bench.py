@@ -1,19 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the ASPD attention hot path on one MI355X.
 
-A step is one pass of the whole hot path over one batch, per attention layer: the branch-chunk
-fill that opens a parallel stage (metadata + attention), one parallel-decode step (metadata +
-attention), the merge (metadata only), and the serial-decode steps that follow (metadata +
-attention each), all through the C ABI of libaspd.so on one HIP stream.  Inputs (KV pool, block
-tables, queries) are resident in HBM before the timed region.  The decode state is restored from a
-snapshot at the start of every step (four small device copies, inside the timed region) so that
-every step does identical work.
+Metric (one attention layer): branch-query tokens per second of the parallel-decode call, with the HBM
+bandwidth it achieves against the 8 TB/s peak.  The default run measures it on all five named
+configurations (`per_config`); the headline `value` is the figure of configuration 5, the largest.
 
-Prints ONE JSON line.  Besides the throughput of the step (`value`, query tokens per second) it carries
-`per_call` (every call kind: average launch, algorithmic bytes, fraction of 8 TB/s, and the bound
-max(bytes / 8 TB/s, dispatch floor)), `roofline` (the streaming decode kernel against the HBM peak, with
-the counter-measured traffic, the rate of a plain read stream on the same device and the dispatch floor)
-and `cpu_baseline` (the CPU oracle on a bounded sample of the same workload).  One GPU only.
+A step is one pass of the whole hot path over configuration 5's batch, per attention layer: the
+16-token branch-chunk fill that opens a parallel stage (metadata + attention), one parallel-decode step
+(metadata + attention), the merge (metadata only) and the serial-decode steps that follow (metadata +
+attention each), all through the C ABI of libaspd.so on one HIP stream, captured in a HIP graph.  Inputs
+(KV pools, block tables, queries) are resident in HBM before the timed region; the decode state is
+restored from a snapshot at the start of every step (small device copies inside the timed region), so
+that every step does identical work.  `ms_per_step` is that step, timed over `--steps` steps.
+
+Per call kind the average launch is measured separately: REP back-to-back launches of the one attention
+kernel (no metadata calls between them), captured once, timed with events on the launch stream, each
+launch on another KV pool so that no timed byte comes from a cache.  `roofline` is the parallel-decode
+kernel on configuration 5 alone against the HBM peak; `roofline_chunk` the branch-chunk kernel against the
+dense bf16 MFMA peak; `cpu_baseline` the CPU oracle (numpy, BLAS-threaded) on a bounded sample.
+One GPU only.
 """
 from __future__ import annotations
 
@@ -29,56 +34,44 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
     if p not in sys.path:
         sys.path.insert(0, p)
 
-HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+MFMA_BF16_TFLOPS = 2500.0  # MI355X published dense bf16 matrix peak
 
-# name -> (config index, chunk tokens per branch, serial steps after the merge, tokens every branch
-#          holds before the step relative to the config's branch_len)
+# name -> configuration index, chunk tokens per branch (0: no chunk call), serial steps after the merge,
+#         tokens every branch holds before the step relative to the configuration's branch_len
 WORKLOADS = {
-    "cycle4": dict(index=4, chunk=16, serial=32, base_offset=-17,
-                   what="config 4 batch (B=4, 32q/8kv/128 bf16, prefix 16384, 6 branches of 32..192, paged 16): "
-                        "16-token branch chunk, parallel-decode step, merge, 32 serial-decode steps"),
+    "cfg1": dict(index=1, chunk=0, serial=1, base_offset=-1,
+                 what="config 1 (B=1, 4q/4kv/64 fp32, prefix 64, branches 5/9/16, contiguous KV): "
+                      "parallel-decode step, merge, one serial-decode step"),
     "cfg2": dict(index=2, chunk=0, serial=0, base_offset=-1,
-                 what="config 2 (B=1, prefix 2048, 4 branches at 64): one parallel-decode step"),
+                 what="config 2 (B=1, 32q/8kv/128 bf16, prefix 2048, 4 branches at 64, paged 16): one parallel-decode step"),
     "cfg3": dict(index=3, chunk=0, serial=0, base_offset=-1,
-                 what="config 3 (B=16 mixed): one parallel-decode step"),
+                 what="config 3 (B=16 mixed, prefix 512..4096, 2..8 branches of 16..256): one parallel-decode step"),
     "cfg4": dict(index=4, chunk=0, serial=32, base_offset=-1,
-                 what="config 4 (B=4, prefix 16384, 6 branches): parallel-decode step, merge, 32 serial-decode steps"),
-    "cycle5": dict(index=5, chunk=16, serial=4, base_offset=0,
-                   what="config 5 batch (B=64): 16-token branch chunk, parallel-decode step, merge, 4 serial-decode steps"),
-    "cfg5": dict(index=5, chunk=16, serial=0, base_offset=0,
-                 what="config 5 (B=64, prefix 1024..8192, 2..10 branches of 8..128): 16-token branch chunk, "
-                      "then one parallel-decode step"),
+                 what="config 4 (B=4, prefix 16384, 6 branches of 32..192): parallel-decode step, merge, "
+                      "32 serial-decode steps"),
+    "cfg5": dict(index=5, chunk=16, serial=4, base_offset=0,
+                 what="config 5 (B=64, prefix 1024..8192, 2..10 branches of 8..128, paged 16): 16-token branch chunk, "
+                      "parallel-decode step, merge, 4 serial-decode steps"),
+    "cycle4": dict(index=4, chunk=16, serial=32, base_offset=-17,
+                   what="config 4's batch with a 16-token branch chunk before the decode step and 32 serial steps after"),
 }
+DEFAULT_SET = ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5")
+HEADLINE = "cfg5"
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cycle4", choices=sorted(WORKLOADS))
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate through (0 = enough for 1.5 GB)")
-    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build is one-GPU only (the path shards by sequence or KV head without "
-              "exchange, nothing here uses a second GPU); run with --gpus 1", file=sys.stderr)
-        return 2
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
-    import numpy as np
-    import torch
 
-    import aspd_workloads as W
-    from paper_2508_08895_amd import binding as A
-
-    A.lib()  # fail loudly when the HIP library is missing
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
+def measure(name, args, timed, mods):
+    """Everything about one workload: per-call launch times (always) and the timed step (`timed`)."""
+    np, torch, W, A = mods
     dev = torch.device("cuda:0")
-    spec = WORKLOADS[args.workload]
+    spec = WORKLOADS[name]
     t0 = time.time()
     wl = W.config(spec["index"])
-    print(f"[bench] workload {args.workload}: generated in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+    log(f"{name}: generated in {time.time() - t0:.1f}s")
 
     bt_dev = torch.from_numpy(wl.block_tables).to(dev)
     kv = A.KVCache(wl.k_cache.to(dev), wl.v_cache.to(dev), bt_dev, wl.num_q_heads)
@@ -87,22 +80,23 @@ def main() -> int:
     # Distinct KV pools ("layers", as a model has one cache per layer) that consecutive attention calls
     # rotate through, so that no call finds its pages in the 256 MB memory-side cache from the call
     # before: every timed byte comes from HBM.  Layer 0 is the seeded pool; the others hold values
-    # of the same distribution drawn on the device.
+    # of the same distribution drawn on the device.  (Configurations 1 and 2 are smaller than the caches
+    # however many pools there are: their launches are bound by latency, see latency_aware_bound_us.)
     elt = 2 if wl.dtype == "bf16" else 4
     active = int(wl.prefix_len.sum() + wl.branch_len.sum()) * 2 * wl.num_kv_heads * wl.head_dim * elt
-    n_layers = args.layers or int(min(64, max(2, -(-int(1.5e9) // active))))
+    n_layers = args.layers or int(min(32, max(2, -(-int(1.5e9) // active))))
     kvs = [kv]
     for _ in range(n_layers - 1):
         k2 = (torch.randn(wl.k_cache.shape, device=dev, dtype=torch.float32) * wl.sigma).to(wl.torch_dtype)
         v2 = (torch.randn(wl.v_cache.shape, device=dev, dtype=torch.float32) * wl.sigma).to(wl.torch_dtype)
         kvs.append(A.KVCache(k2, v2, bt_dev, wl.num_q_heads))
-    print(f"[bench] {n_layers} KV pools of {2 * wl.k_cache.numel() * elt / 1e6:.0f} MB, "
-          f"{active / 1e6:.1f} MB read per call", file=sys.stderr, flush=True)
+    log(f"{name}: {n_layers} KV pools of {2 * wl.k_cache.numel() * elt / 1e6:.0f} MB, {active / 1e6:.1f} MB read per call")
     rot = [0]
 
     def next_kv():
         rot[0] = (rot[0] + 1) % n_layers
         return kvs[rot[0]]
+
     base_len = wl.branch_len + spec["base_offset"]
     assert (base_len >= 0).all()
 
@@ -110,14 +104,14 @@ def main() -> int:
         return torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
 
     # ---- bring the cache state to the start of a step (untimed)
-    A.aspd_build_branch_meta(kv, state, A.STAGE_SERIAL, dev_i32(wl.prefix_len), NQ=int(wl.prefix_len.sum()))
+    A.aspd_build_branch_meta(kv, state, A.STAGE_SERIAL, dev_i32(wl.prefix_len), NQ=int(wl.prefix_len.sum()), plan=False)
     state.open_parallel(torch.from_numpy(wl.cu_branches))
     for new_len in W.interleaved_history(base_len):
-        A.aspd_build_branch_meta(kv, state, A.STAGE_PARALLEL, dev_i32(new_len), NQ=int(new_len.sum()))
+        A.aspd_build_branch_meta(kv, state, A.STAGE_PARALLEL, dev_i32(new_len), NQ=int(new_len.sum()), plan=False)
     torch.cuda.synchronize()
     assert int(state.fault.item()) == 0
-    snap = [t.clone() for t in (state.stage_base, state.seq_len, state.branch_len, state.slot_owner)]
-    live = (state.stage_base, state.seq_len, state.branch_len, state.slot_owner)
+    live = (state.stage_base, state.seq_len, state.branch_len, state.slot_owner, state.stage_open)
+    snap = [t.clone() for t in live]
 
     # ---- pre-allocated per-call inputs and outputs
     C, S = spec["chunk"], spec["serial"]
@@ -127,11 +121,12 @@ def main() -> int:
         return (torch.randn(n, wl.num_q_heads, wl.head_dim, generator=g) * wl.sigma).to(wl.torch_dtype).to(dev)
 
     ws = A.new_workspace(kv, B, max(C * NB, NB, B))
-    calls = []  # (kind, stage, new_len_d, step, q, out, fn)
+    kmax = int(wl.num_branches.max())
+    calls = []  # (kind, stage, new_len_d, step, q, fn)
     if C:
-        calls.append(("chunk", A.STAGE_PARALLEL, dev_i32(np.full(NB, C)), A.Step(C * NB, NB, B, dev, max_new_per_seq=int(C * wl.num_branches.max())),
+        calls.append(("chunk", A.STAGE_PARALLEL, dev_i32(np.full(NB, C)), A.Step(C * NB, NB, B, dev, max_new_per_seq=C * kmax),
                       rand_q(C * NB), A.aspd_attn_branch_chunk))
-    calls.append(("parallel", A.STAGE_PARALLEL, dev_i32(np.ones(NB)), A.Step(NB, NB, B, dev, max_new_per_seq=int(wl.num_branches.max())), rand_q(NB),
+    calls.append(("parallel", A.STAGE_PARALLEL, dev_i32(np.ones(NB)), A.Step(NB, NB, B, dev, max_new_per_seq=kmax), rand_q(NB),
                   A.aspd_attn_parallel_decode))
     if S:
         calls.append(("merge", A.STAGE_MERGE, None, None, None, None))
@@ -140,7 +135,6 @@ def main() -> int:
             calls.append(("serial", A.STAGE_SERIAL, ones_b, A.Step(B, B, B, dev, max_new_per_seq=1), rand_q(B),
                           A.aspd_attn_serial_decode))
     outs = {id(c): (torch.empty_like(c[4]) if c[4] is not None else None) for c in calls}
-
     n_attn = sum(1 for c in calls if c[5] is not None)
     ROUND = -(-n_layers // n_attn)   # steps after which every pool has been read once
 
@@ -157,13 +151,14 @@ def main() -> int:
                 snaps[kind] = ([t.clone() for t in live], c)
             fn(next_kv(), state, step, q, ws, out=outs[id(c)])
 
-    # ---- algorithmic bytes of every attention call (unique visible KV + Q and O + tables + tags)
+    # ---- algorithmic bytes (unique visible KV + Q and O + tables + tags) and, for the chunk, flops
     kv_tok_bytes = 2 * wl.num_kv_heads * wl.head_dim * elt
     cu = wl.cu_branches
     per_seq_branch_tokens = np.add.reduceat(base_len, cu[:-1]).astype(np.int64)
     T = wl.prefix_len.astype(np.int64) + per_seq_branch_tokens
     bytes_of, tokens_of = {}, {}
     Tn = T.copy()
+    chunk_flops = 0
     for c in calls:
         kind = c[0]
         if kind == "merge":
@@ -171,6 +166,10 @@ def main() -> int:
         if kind == "chunk":
             Tn = Tn + C * wl.num_branches
             nq = C * NB
+            # token j of a branch that held n tokens attends prefix + n + j + 1 keys: 4 * D flops per key and head
+            seq_of = np.repeat(np.arange(B), wl.num_branches)
+            keys = (wl.prefix_len[seq_of].astype(np.int64) + base_len) * C + C * (C + 1) // 2
+            chunk_flops = int(keys.sum()) * 4 * wl.head_dim * wl.num_q_heads
         elif kind == "parallel":
             Tn = Tn + wl.num_branches
             nq = NB
@@ -181,25 +180,22 @@ def main() -> int:
             + 4 * int(((Tn + 15) // 16).sum()) + (0 if kind == "serial" else int((Tn - wl.prefix_len).sum()))
         bytes_of.setdefault(kind, []).append(b)
         tokens_of.setdefault(kind, []).append(nq)
-    step_tokens = sum(sum(v) for v in tokens_of.values())
 
     # ---- the step as a HIP graph (every call only enqueues kernels on the current stream, so the
-    # whole step is capturable); replay must reproduce the eager outputs exactly
+    # whole step is capturable); replay must reproduce the eager outputs
     snaps = {}
     one_step(snaps)
     torch.cuda.synchronize()
+    assert int(state.fault.item()) == 0
     eager_out = {k: v.clone() for k, v in outs.items() if v is not None}
-    def run_step(t):
-        one_step(offset=t % ROUND)
-
+    graphs = []
     if not args.no_graph:
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             one_step()
         torch.cuda.current_stream().wait_stream(side)
-        graphs = []
-        for r in range(ROUND):          # one captured step per rotation offset
+        for r in range(ROUND if timed else 1):          # one captured step per rotation offset
             g_r = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g_r):
                 one_step(offset=r)
@@ -209,64 +205,41 @@ def main() -> int:
                 v.zero_()
         graphs[0].replay()
         torch.cuda.synchronize()
+        tol = 2e-2 if wl.dtype == "bf16" else 1e-5
         for k, v in eager_out.items():
             # pairs of pages are handed to waves dynamically, so the summation order (not the math) may differ
-            assert torch.allclose(outs[k].float(), v.float(), atol=2e-2, rtol=0), "graph replay differs from the eager step"
+            assert torch.allclose(outs[k].float(), v.float(), atol=tol, rtol=0), "graph replay differs from the eager step"
 
-        def run_step(t):
-            graphs[t % ROUND].replay()
+    def run_step(t):
+        if graphs:
+            graphs[t % len(graphs)].replay()
+        else:
+            one_step(offset=t % ROUND)
 
-    # ---- timed region
-    for t in range(args.warmup):
-        run_step(t)
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for t in range(args.steps):
-        run_step(args.warmup + t)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    ms_per_step = elapsed / args.steps * 1e3
-    assert int(state.fault.item()) == 0
+    result = {"workload": spec["what"], "B": B, "NB": NB, "kv_tokens": int(T.sum()), "kv_pools_rotated": n_layers,
+              "dtype": wl.dtype}
+    # ---- timed region (the headline workload only)
+    if timed:
+        for t in range(args.warmup):
+            run_step(t)
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for t in range(args.steps):
+            run_step(args.warmup + t)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
+        result["ms_per_step"] = elapsed / args.steps * 1e3
+        result["timed_region_s"] = elapsed
+        result["query_tokens_per_step"] = int(sum(sum(v) for v in tokens_of.values()))
+        assert int(state.fault.item()) == 0
 
-    # ---- average launch duration of each kind of attention call: REP back-to-back launches of the
-    # call (state restored to what that call sees), captured once, timed with events on the
-    # launch stream
+    # ---- dispatch floor: back-to-back launches of a kernel that does nothing to speak of (a one-element
+    # fill), timed the same way.  A call whose traffic at 8 TB/s takes less than this (configs 1-2) is bound
+    # by it, not by HBM: per_call reports max(bytes / 8 TB/s, floor) next to the plain figure.
     REP = max(20, n_layers)
-    per_call, dur = {}, {}
-
-    # ---- dispatch floor: the same number of back-to-back launches of a kernel that does nothing to speak of
-    # (a one-element fill), timed the same way.  A call whose traffic at 8 TB/s takes less than this (configs 1-2)
-    # is bound by it, not by HBM: per_call reports max(bytes / 8 TB/s, floor) next to the plain figure.
     tiny = torch.zeros(1, dtype=torch.float32, device=dev)
 
-    def floor_body():
-        for _ in range(REP):
-            tiny.fill_(1.0)
-
-    floor_body()
-    floor_runner = floor_body
-    if not args.no_graph:
-        gf = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gf):
-            floor_body()
-        floor_runner = gf.replay
-    floor_runner()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    floor_runner()
-    e1.record()
-    torch.cuda.synchronize()
-    dispatch_floor = e0.elapsed_time(e1) * 1e-3 / REP
-    for kind, (st_snap, c) in snaps.items():
-        _, stage, new_len, step, q, fn = c
-
-        def body():
-            for dst, src in zip(live, st_snap):
-                dst.copy_(src)
-            for _ in range(REP):
-                fn(next_kv(), state, step, q, ws, out=outs[id(c)])
-
+    def timed_runner(body, reps=5):
         body()
         runner = body
         if not args.no_graph:
@@ -277,100 +250,158 @@ def main() -> int:
         runner()
         torch.cuda.synchronize()
         times = []
-        for _ in range(5):
+        for _ in range(reps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             runner()
             e1.record()
             torch.cuda.synchronize()
             times.append(e0.elapsed_time(e1) * 1e-3 / REP)
+        return times
+
+    def floor_body():
+        for _ in range(REP):
+            tiny.fill_(1.0)
+
+    dispatch_floor = float(np.mean(timed_runner(floor_body, reps=3)))
+    result["dispatch_floor_us"] = round(dispatch_floor * 1e6, 2)
+
+    # ---- average launch of each kind of attention call: REP back-to-back launches of the call (state
+    # restored to what that call sees, its step's plan as the metadata call left it)
+    per_call = {}
+    for kind, (st_snap, c) in snaps.items():
+        _, stage, new_len, step, q, fn = c
+
+        def body():
+            for dst, src in zip(live, st_snap):
+                dst.copy_(src)
+            for _ in range(REP):
+                fn(next_kv(), state, step, q, ws, out=outs[id(c)])
+
+        times = timed_runner(body)
         avg = float(np.mean(times))
-        dur[kind] = avg
         bts = float(np.mean(bytes_of[kind]))
-        per_call[kind] = {"launches_per_step": len(bytes_of[kind]), "avg_us": round(avg * 1e6, 2),
-                          "min_us": round(float(np.min(times)) * 1e6, 2),
-                          "query_tokens_per_launch": int(np.mean(tokens_of[kind])),
-                          "query_tokens_per_s": round(float(np.mean(tokens_of[kind])) / avg, 1),
-                          "algorithmic_MB": round(bts / 1e6, 3), "GBps": round(bts / avg / 1e9, 1),
-                          "frac_of_8TBps": round(bts / avg / 1e9 / HBM_PEAK_GBS, 4),
-                          "latency_aware_bound_us": round(max(bts / (HBM_PEAK_GBS * 1e9), dispatch_floor) * 1e6, 2),
-                          "frac_of_latency_aware_bound": round(max(bts / (HBM_PEAK_GBS * 1e9), dispatch_floor) / avg, 4)}
+        ntok = float(np.mean(tokens_of[kind]))
+        bound = max(bts / (HBM_PEAK_GBS * 1e9), dispatch_floor)
+        entry = {"launches_per_step": len(bytes_of[kind]), "avg_us": round(avg * 1e6, 2),
+                 "min_us": round(float(np.min(times)) * 1e6, 2), "query_tokens_per_launch": int(ntok),
+                 "query_tokens_per_s": round(ntok / avg, 1), "algorithmic_MB": round(bts / 1e6, 3),
+                 "GBps": round(bts / avg / 1e9, 1), "frac_of_8TBps": round(bts / avg / 1e9 / HBM_PEAK_GBS, 4),
+                 "latency_aware_bound_us": round(bound * 1e6, 2), "frac_of_latency_aware_bound": round(bound / avg, 4)}
+        if kind == "chunk":
+            entry["TFLOPs"] = round(chunk_flops / avg / 1e12, 1)
+            entry["frac_of_bf16_mfma_peak"] = round(chunk_flops / avg / 1e12 / MFMA_BF16_TFLOPS, 4)
+            entry["algorithmic_GFLOP"] = round(chunk_flops / 1e9, 1)
+        tr = profile_figure(name, kind)
+        if tr is not None:
+            entry["hbm_traffic_MB_counters"] = round(tr / 1e6, 1)
+        per_call[kind] = entry
 
-    # ---- the step before the attention call: rotary encoding of the new tokens fused with their cache append
-    # (aspd_rope_append), for the rows of the parallel-decode call; not part of the timed step above
-    if "parallel" in snaps:
-        _, c = snaps["parallel"]
-        step_p, q_p = c[3], c[4].clone()
-        k_new = (torch.randn(step_p.NQ, wl.num_kv_heads, wl.head_dim, device=dev) * wl.sigma).to(wl.torch_dtype)
-        v_new = (torch.randn(step_p.NQ, wl.num_kv_heads, wl.head_dim, device=dev) * wl.sigma).to(wl.torch_dtype)
+    if args.extras:
+        extras(name, args, mods, locals(), per_call)
+    result["per_call"] = per_call
+    result["_wl"] = (wl, base_len, C)
+    return result
 
-        def rope_body():
-            for _ in range(REP):
-                A.aspd_rope_append(kv, step_p, q_p, k_new, v_new, 1e6)
 
-        rope_body()
-        runner = rope_body
-        if not args.no_graph:
-            gk = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gk):
-                rope_body()
-            runner = gk.replay
-        runner()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        runner()
-        e1.record()
-        torch.cuda.synchronize()
-        per_call["rope_append"] = {"launches_per_step": 0, "avg_us": round(e0.elapsed_time(e1) * 1e3 / REP, 2),
-                                   "query_tokens_per_launch": int(step_p.NQ),
-                                   "note": "rows of the parallel-decode call; outside the timed step"}
+def profile_figure(workload, kind):
+    """HBM bytes per launch as the counters saw them: the figure of the committed rocprofv3 summary of this
+    workload (a line "traffic_bytes_per_<kind>_launch = N" in profiles/attn_<workload>_hbm_traffic.md), None
+    when there is none."""
+    path = os.path.join(ROOT, "profiles", f"attn_{workload}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    m = re.search(rf"^traffic_bytes_per_{kind}_launch\s*=\s*(\d+)", open(path).read(), re.M)
+    return int(m.group(1)) if m else None
 
-    # ---- a mixed step: half of the sequences end their stage and decode serially next to the others'
-    # branches, all in one launch (last: it renumbers the branches of `state`)
-    if "parallel" in snaps and B >= 2:
-        st_snap, _ = snaps["parallel"]
-        for dst, src in zip(live, st_snap):
-            dst.copy_(src)
-        ending = np.array([1 if s < B // 2 else 0 for s in range(B)], dtype=np.int32)
-        A.aspd_build_branch_meta(kv, state, A.STAGE_MERGE, dev_i32(ending))
-        keep = np.where(ending == 1, 0, wl.num_branches).astype(np.int64)
-        new_cu = np.zeros(B + 1, dtype=np.int32)
-        np.cumsum(keep, out=new_cu[1:])
-        A.aspd_renumber_branches(state, torch.from_numpy(new_cu))
-        nb2 = int(new_cu[-1])
-        mixed_len = dev_i32(np.concatenate([np.ones(nb2), ending]))
-        nq_mixed = nb2 + int(ending.sum())
-        step_m = A.aspd_build_branch_meta(kv, state, A.STAGE_MIXED, mixed_len, NQ=nq_mixed,
-                                          max_new_per_seq=int(max(keep.max(), 1)))
-        q_m, out_m = rand_q(nq_mixed), None
-        out_m = torch.empty_like(q_m)
 
-        def mixed_body():
-            for _ in range(REP):
-                A.aspd_attn_parallel_decode(next_kv(), state, step_m, q_m, ws, out=out_m)
+def extras(name, args, mods, env, per_call):
+    """Two more launches around the hot path, outside the timed step: the rotary encoding + cache append of the
+    parallel-decode rows, and a mixed step (half of the sequences serial, half in their parallel stage)."""
+    np, torch, W, A = mods
+    wl, kv, state, snaps, live, ws, dev, B = (env[k] for k in ("wl", "kv", "state", "snaps", "live", "ws", "dev", "B"))
+    timed_runner, next_kv, rand_q, dev_i32, REP, bytes_of = (env[k] for k in ("timed_runner", "next_kv", "rand_q", "dev_i32",
+                                                                            "REP", "bytes_of"))
+    st_snap, c = snaps["parallel"]
+    step_p, q_p = c[3], c[4].clone()
+    k_new = (torch.randn(step_p.NQ, wl.num_kv_heads, wl.head_dim, device=dev) * wl.sigma).to(wl.torch_dtype)
+    v_new = (torch.randn(step_p.NQ, wl.num_kv_heads, wl.head_dim, device=dev) * wl.sigma).to(wl.torch_dtype)
 
-        mixed_body()
-        runner = mixed_body
-        if not args.no_graph:
-            gk = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gk):
-                mixed_body()
-            runner = gk.replay
-        runner()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        runner()
-        e1.record()
-        torch.cuda.synchronize()
-        avg = e0.elapsed_time(e1) * 1e-3 / REP
-        bts = float(bytes_of["parallel"][0])
-        per_call["mixed"] = {"launches_per_step": 0, "avg_us": round(avg * 1e6, 2), "query_tokens_per_launch": nq_mixed,
-                             "algorithmic_MB": round(bts / 1e6, 3), "GBps": round(bts / avg / 1e9, 1),
-                             "note": f"{int(ending.sum())} sequences serial, {B - int(ending.sum())} in their parallel stage, "
-                                     "one launch; outside the timed step"}
-        assert int(state.fault.item()) == 0
+    def rope_body():
+        for _ in range(REP):
+            A.aspd_rope_append(kv, step_p, q_p, k_new, v_new, 1e6)
+
+    per_call["rope_append"] = {"launches_per_step": 0, "avg_us": round(float(np.mean(timed_runner(rope_body, reps=2))) * 1e6, 2),
+                               "query_tokens_per_launch": int(step_p.NQ),
+                               "note": "rows of the parallel-decode call; outside the timed step"}
+    if B < 2:
+        return
+    for dst, src in zip(live, st_snap):
+        dst.copy_(src)
+    ending = np.array([1 if s < B // 2 else 0 for s in range(B)], dtype=np.int32)
+    A.aspd_build_branch_meta(kv, state, A.STAGE_MERGE, dev_i32(ending))
+    keep = np.where(ending == 1, 0, wl.num_branches).astype(np.int64)
+    new_cu = np.zeros(B + 1, dtype=np.int32)
+    np.cumsum(keep, out=new_cu[1:])
+    A.aspd_renumber_branches(state, torch.from_numpy(new_cu))
+    nb2 = int(new_cu[-1])
+    mixed_len = dev_i32(np.concatenate([np.ones(nb2), ending]))
+    nq_mixed = nb2 + int(ending.sum())
+    step_m = A.aspd_build_branch_meta(kv, state, A.STAGE_MIXED, mixed_len, NQ=nq_mixed, max_new_per_seq=int(max(keep.max(), 1)))
+    q_m = rand_q(nq_mixed)
+    out_m = torch.empty_like(q_m)
+
+    def mixed_body():
+        for _ in range(REP):
+            A.aspd_attn_parallel_decode(next_kv(), state, step_m, q_m, ws, out=out_m)
+
+    avg = float(np.mean(timed_runner(mixed_body, reps=2)))
+    bts = float(bytes_of["parallel"][0])
+    per_call["mixed"] = {"launches_per_step": 0, "avg_us": round(avg * 1e6, 2), "query_tokens_per_launch": nq_mixed,
+                         "algorithmic_MB": round(bts / 1e6, 3), "GBps": round(bts / avg / 1e9, 1),
+                         "note": f"{int(ending.sum())} sequences serial, {B - int(ending.sum())} in their parallel stage, "
+                                 "one launch; outside the timed step"}
+    assert int(state.fault.item()) == 0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="all", choices=["all"] + sorted(WORKLOADS),
+                    help="all: the five configurations, headline configuration 5; one name: that workload alone")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate through (0 = enough for 1.5 GB)")
+    ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
+    ap.add_argument("--extras", action="store_true", help="also time the rotary append and a mixed step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is one-GPU only (the path shards by sequence or KV head without "
+              "exchange, nothing here uses a second GPU); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import aspd_workloads as W
+    from paper_2508_08895_amd import binding as A
+
+    A.lib()  # fail loudly when the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    mods = (np, torch, W, A)
+    dev = torch.device("cuda:0")
+
+    names = DEFAULT_SET if args.workload == "all" else (args.workload,)
+    head_name = HEADLINE if args.workload == "all" else args.workload
+    results = {}
+    for name in names:
+        results[name] = measure(name, args, timed=(name == head_name), mods=mods)
+        if name != head_name:
+            results[name].pop("_wl")
+        torch.cuda.empty_cache()
+    head = results[head_name]
+    wl, base_len, C = head.pop("_wl")
 
     # ---- what a plain read-only stream reaches on this device (2 GiB, larger than any cache)
     probe_src = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
@@ -388,49 +419,53 @@ def main() -> int:
     read_ceiling = 5 * probe_src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
     del probe_src
 
-    # the dominant kernel: the streaming decode launches (parallel + serial share one kernel)
-    dom = [k for k in ("parallel", "serial") if k in dur]
-    dom_launches = sum(len(bytes_of[k]) for k in dom)
-    dom_time = sum(dur[k] * len(bytes_of[k]) for k in dom)
-    dom_bytes = sum(float(np.sum(bytes_of[k])) for k in dom)
-    achieved = dom_bytes / dom_time / 1e9
-    # HBM bytes per launch as the counters saw them: the figure of the committed rocprofv3 summary of this
-    # workload (a line "traffic_bytes_per_decode_launch = N"), null when there is none
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"attn_bf16_{args.workload}_hbm_traffic.md")
-    if os.path.exists(tpath):
-        m = re.search(r"^traffic_bytes_per_decode_launch\s*=\s*(\d+)", open(tpath).read(), re.M)
-        traffic = int(m.group(1)) if m else None
-    roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel (parallel + serial decode launches)",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "avg_launch_us": round(dom_time / dom_launches * 1e6, 2),
+    # ---- the dominant kernel of the metric: the parallel-decode launch of the headline workload, alone
+    par = head["per_call"]["parallel"]
+    roofline = {"bound": "hbm", "kernel": f"attn_bf16_kernel, parallel-decode launch of {head_name}",
+                "achieved": par["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": par["frac_of_8TBps"],
+                "traffic": profile_figure(head_name, "parallel"),
+                "traffic_source": f"profiles/attn_{head_name}_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command)",
+                "avg_launch_us": par["avg_us"], "algorithmic_bytes_per_launch": int(par["algorithmic_MB"] * 1e6),
                 "plain_read_stream_GBps": round(read_ceiling, 1),
-                "frac_of_plain_read_stream": round(achieved / read_ceiling, 4),
-                "algorithmic_bytes_per_launch": int(dom_bytes / dom_launches),
-                "dispatch_floor_us": round(dispatch_floor * 1e6, 2)}
+                "frac_of_plain_read_stream": round(par["GBps"] / read_ceiling, 4),
+                "dispatch_floor_us": head["dispatch_floor_us"]}
+    roofline_chunk = None
+    if "chunk" in head["per_call"]:
+        ch = head["per_call"]["chunk"]
+        roofline_chunk = {"bound": "mfma", "kernel": f"attn_bf16_rows_kernel, branch-chunk launch of {head_name}",
+                          "achieved": ch["TFLOPs"], "peak": MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                          "frac": ch["frac_of_bf16_mfma_peak"], "avg_launch_us": ch["avg_us"],
+                          "algorithmic_GFLOP": ch["algorithmic_GFLOP"],
+                          "hbm": {"algorithmic_MB": ch["algorithmic_MB"], "GBps": ch["GBps"], "frac_of_8TBps": ch["frac_of_8TBps"],
+                                  "traffic": profile_figure(head_name, "chunk")}}
 
-    # ---- CPU baseline: the oracle on the parallel-decode call of this workload
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(wl, base_len, C, np)
 
-    line = {"metric": "query tokens/s through the ASPD attention hot path, one attention layer "
-                      "(branch-query tokens/s of the parallel-decode call in per_call.parallel)",
-            "value": round(step_tokens / (ms_per_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1,
-            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
-            "data": "synthetic", "launch": "eager" if args.no_graph else "hip_graph", "config": {"workload": f"{args.workload}: {spec['what']}",
-                                           "query_tokens_per_step": int(step_tokens), "B": B, "NB": NB, "kv_pools_rotated": n_layers,
-                                           "kv_tokens": int(T.sum())},
-            "per_call": per_call, "roofline": roofline, "cpu_baseline": cpu}
+    per_config = {}
+    for name, r in results.items():
+        per_config[name] = {k: v for k, v in r.items() if k not in ("ms_per_step", "timed_region_s", "query_tokens_per_step")}
+    line = {"metric": "branch-query tokens/s of the parallel-decode attention call, one attention layer "
+                      "(achieved HBM GB/s and fraction of 8 TB/s in roofline and per_config)",
+            "value": par["query_tokens_per_s"], "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(head["ms_per_step"], 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"],
+            "data": "synthetic", "launch": "eager" if args.no_graph else "hip_graph",
+            "config": {"workload": f"{head_name}: {WORKLOADS[head_name]['what']}",
+                       "value_is": "branch queries of one parallel-decode launch / its average duration (per_config."
+                                   f"{head_name}.per_call.parallel)",
+                       "step_is": "the whole hot path on this batch: " + WORKLOADS[head_name]["what"].split(": ", 1)[1],
+                       "query_tokens_per_step": head["query_tokens_per_step"], "B": head["B"], "NB": head["NB"],
+                       "kv_tokens": head["kv_tokens"], "kv_pools_rotated": head["kv_pools_rotated"],
+                       "timed_region_s": round(head["timed_region_s"], 3)},
+            "per_config": per_config, "roofline": roofline, "roofline_chunk": roofline_chunk, "cpu_baseline": cpu}
     print(json.dumps(line), flush=True)
     return 0
 
 
 def cpu_baseline(wl, base_len, chunk, np):
     """The oracle as it stands, timed on this host for the parallel-decode call of the workload."""
-    import aspd_workloads as W
     from oracle import TokenTable, attend
     try:
         from threadpoolctl import threadpool_info
@@ -461,6 +496,7 @@ def cpu_baseline(wl, base_len, chunk, np):
         steps += 1
     dt = time.perf_counter() - t0
     return {"value": round(done / dt, 3), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "implementation": "numpy float64, dense mask, matrix products through the BLAS numpy links (its threads are `cores`)",
             "sample": f"{steps} consecutive parallel-decode calls: {done} of {total} branch queries x "
                       f"{wl.num_q_heads} heads, metadata + float64 dense-mask attention, {dt:.1f}s"}
 
