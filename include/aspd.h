@@ -139,7 +139,7 @@ typedef struct aspd_step {
                                row tile); results do not depend on it, even when it is wrong.        */
   int32_t  max_workgroups;  /* host: most workgroups an attention launch of this step may use, for callers
                                that run other kernels next to attention and want compute units left for
-                               them; 0 = one per compute unit (two for fp32).  Results do not depend on it. */
+                               them; 0 = one per compute unit.  Results do not depend on it.            */
   int32_t* cu_new_d;        /* [NB+1] (PARALLEL) or [B+1] (SERIAL): first row of each branch / sequence */
   int32_t* cu_seq_new_d;    /* [B+1] first row of each sequence                                    */
   int32_t* q_seq_d;         /* [NQ] sequence of the token                                          */

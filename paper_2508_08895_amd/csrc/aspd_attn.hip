@@ -28,7 +28,7 @@
 
 namespace {
 
-constexpr int NW = 4;                 // waves per workgroup, fp32 kernel (two workgroups per compute unit)
+constexpr int NW = 4;                 // waves per workgroup, fp32 kernel
 constexpr int THREADS = NW * 64;
 // bf16 streaming kernel: one workgroup of 4 waves per compute unit (one wave per SIMD, so up to 512
 // registers each) and one pair of pages in flight per wave, 64 KB per compute unit.  Measured: deeper
@@ -1249,10 +1249,12 @@ size_t f32_smem_bytes() {
   return F32_ROWS * D * 4 + 2 * F32_ROWS * 4 + (size_t)THREADS * F32_ROWS * (D / 4 + 2) * 4;
 }
 
-// One workgroup per compute unit stays resident (271 vector registers per lane at head_dim 128, 150 KB of
-// LDS); the grid is twice that, so a compute unit takes its second workgroup when the first is done.
+// One workgroup per compute unit (255 vector registers per lane and 138 KB of LDS at head_dim 128), one wave
+// per SIMD; the grid is sized for that.
+static_assert(F32_ROWS * 128 * 4 + 2 * F32_ROWS * 4 + THREADS * F32_ROWS * (128 / 4 + 2) * 4 <= 160 * 1024 - 256,
+              "fp32 kernel: query tile, row descriptors and one reduction slot per thread fit the LDS of a compute unit");
 template <int D>
-__global__ __launch_bounds__(THREADS) void attn_f32_kernel(AttnArgs a) {
+__global__ __launch_bounds__(THREADS) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_f32_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ int merge_flag;
   Seg seg;

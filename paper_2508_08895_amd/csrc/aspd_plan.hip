@@ -404,9 +404,10 @@ int aspd_choose_variant(const aspd_kv* kv, int32_t B, int32_t NQ, int32_t max_ne
   // A segment's fixed cost (start-up, reduction across waves, partial, merge) in units of the time one
   // more page takes its workgroup.
   v->pad = v->kernel == KERNEL_BF16_STREAM ? PAD_STREAM * 128 / kv->head_dim : PAD_COMPUTE;
-  // Grid: as many workgroups as stay resident at once (one per compute unit for bf16, two for fp32),
-  // never more than the pages can feed, never more than the caller allows.
-  long nwg = (kv->dtype == ASPD_BF16 ? 1L : 2L) * aspd_device_cu_count();
+  // Grid: as many workgroups as stay resident at once (one per compute unit: every kernel here needs more
+  // than half of a compute unit's LDS or registers), never more than the pages can feed, never more than
+  // the caller allows.
+  long nwg = aspd_device_cu_count();
   if (v->kernel == KERNEL_BF16_ROWS) nwg = std::min(nwg, (long)MAX_WG_ROWS);
   const long groups_max = (long)B + NQ / v->qpg;
   const long units_max = groups_max * kv->num_kv_heads * kv->max_blocks_per_seq;

@@ -102,12 +102,13 @@ def test_config_parallel_decode_full_size(A, index, hinted):
         step.max_new_per_seq = int(wl.num_branches.max())
     _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label=f"cfg{index} parallel")
     if index == 4:
-        # merge, then serial steps over prefix + all branches (three of the 32 are checked here)
+        # merge, then the 32 serial steps over prefix + all branches (all of them with the hints, the first
+        # three without)
         from gpu_drive import assert_state_equal
         tt.merge()
         gb.merge()
         one = np.ones(wl.B, dtype=np.int32)
-        for i in range(3):
+        for i in range(32 if hinted else 3):
             meta = tt.append_serial(one)
             step = gb.serial(one)
             if hinted:
@@ -128,7 +129,7 @@ def test_config5_chunk_then_decode(A, scale, batch, hinted):
     if hinted:
         step.max_new_per_seq = 16 * int(wl.num_branches.max())
     rows = None
-    if scale == 1.0:   # full size: a seeded sample of rows the oracle computes one by one
+    if scale == 1.0 and not hinted:   # full size without the hint: a seeded sample of the rows; with it: every row
         rows = np.sort(np.random.default_rng(5).choice(meta.NQ, size=256, replace=False))
     _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, rows=rows,
                        label=f"cfg5 chunk scale={scale}")
@@ -138,7 +139,7 @@ def test_config5_chunk_then_decode(A, scale, batch, hinted):
     if hinted:
         step.max_new_per_seq = int(wl.num_branches.max())
     rows = None
-    if scale == 1.0:
+    if scale == 1.0 and not hinted:
         rows = np.sort(np.random.default_rng(6).choice(meta.NQ, size=96, replace=False))
     _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, rows=rows,
                        label=f"cfg5 decode scale={scale}")
@@ -666,6 +667,102 @@ def test_sibling_kv_does_not_reach_a_branch(A):
         out = A.aspd_attn_parallel_decode(kv2, gb.state, step, q, gb.workspace)
         assert torch.isfinite(out[r].float()).all(), r
         assert (out[r].float() - base[r].float()).abs().max().item() <= 4e-3, r
+
+
+def test_permuting_the_branches_permutes_the_outputs(A):
+    """Eq. 3 knows no order among the branches of a stage: the same branches (their K/V rows and queries)
+    laid into the cache in another branch order give every branch the output it had, to rounding (the keys
+    of a row are then summed in another order).  Decode step and a 3-token chunk."""
+    import dataclasses
+    from gpu_drive import GpuBatch
+    from oracle_drive import table_at
+    wl = W.random_small(134, batch=3, prefix_range=(30, 400), branches_range=(3, 6), branch_len_range=(4, 30),
+                        extra_tokens_per_branch=8)
+    rng = np.random.default_rng(134)
+    cu = wl.cu_branches
+    # branch k of the permuted layout is branch perm[k] of the original one, per sequence
+    perm = np.concatenate([cu[s] + rng.permutation(int(wl.num_branches[s])) for s in range(wl.B)])
+    for new_tokens, fn in ((1, "aspd_attn_parallel_decode"), (3, "aspd_attn_branch_chunk")):
+        new_len = np.full(wl.NB, new_tokens, dtype=np.int32)
+        # the two layouts as the oracle's tables have them: (sequence, branch, index in branch) -> slot
+        wl_p = dataclasses.replace(wl, branch_len=wl.branch_len[perm].copy())
+        tabs, metas = [], []
+        for w in (wl, wl_p):
+            tt = table_at(w, w.branch_len)
+            metas.append(tt.append_parallel(new_len))
+            tabs.append(tt)
+
+        def where(tt, s):   # (branch number 1.., index in branch) -> physical slot, for the running stage
+            return {(tt.branch[s][j], tt.index_in_branch[s][j]): tt.physical_slot(s, j)
+                    for j in range(int(wl.prefix_len[s]), len(tt.pos[s]))}
+        k_p, v_p = wl.k_cache.clone(), wl.v_cache.clone()
+        for s in range(wl.B):
+            a, b = where(tabs[0], s), where(tabs[1], s)
+            K = int(wl.num_branches[s])
+            for kb in range(K):
+                ka = int(perm[cu[s] + kb] - cu[s])           # original number of the permuted layout's branch kb
+                for t in range(int(wl_p.branch_len[cu[s] + kb]) + new_tokens):
+                    src, dst = a[(ka + 1, t)], b[(kb + 1, t)]
+                    k_p[dst // 16, :, dst % 16] = wl.k_cache[src // 16, :, src % 16]
+                    v_p[dst // 16, :, dst % 16] = wl.v_cache[src // 16, :, src % 16]
+        wl_p = dataclasses.replace(wl_p, k_cache=k_p, v_cache=v_p)
+        # rows: packed by (sequence, branch, token); row of (branch kb, token j) in the permuted call is the row
+        # of (branch perm[kb], token j) in the original call
+        q = wl.draw_q(metas[0].NQ)
+        row_p = np.concatenate([np.arange(new_tokens) + new_tokens * perm[g] for g in range(wl.NB)])
+        outs = []
+        for w, qq in ((wl, q), (wl_p, q[row_p])):
+            gb = GpuBatch(w)
+            gb.grow_to(w.branch_len)
+            step = gb.parallel(new_len)
+            outs.append(getattr(A, fn)(gb.kv, gb.state, step, qq.to(gb.dev), gb.workspace).float().cpu())
+            assert gb.fault() == 0
+        assert torch.isfinite(outs[0]).all()
+        assert (outs[1] - outs[0][row_p]).abs().max().item() <= 4e-3, fn
+
+
+def test_unwritten_slots_may_hold_anything(A):
+    """The slots of a sequence's last page past its last token have never been written and blocks the
+    tables do not use belong to somebody else: both are filled with NaN here, K and V alike.  No call may
+    let them reach an output (a masked key has weight zero, and zero times NaN is NaN)."""
+    from gpu_drive import GpuBatch, assert_state_equal
+    for kw in (dict(), dict(dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=2)):
+        wl = W.random_small(135, batch=4, prefix_range=(5, 300), branches_range=(2, 5), **kw)
+        gb, tt = _grow_both(A, wl, wl.branch_len, False)
+
+        def poison():
+            k, v = gb.kv.k, gb.kv.v
+            for s in range(wl.B):
+                T = len(tt.pos[s])
+                cap = int((wl.block_tables[s] >= 0).sum()) * 16
+                for j in range(T, cap):
+                    ph = int(wl.block_tables[s, j // 16]) * 16 + j % 16
+                    k[ph // 16, :, ph % 16] = float("nan")
+                    v[ph // 16, :, ph % 16] = float("nan")
+
+        def write_rows(meta):   # the new tokens' K/V: finite values where the step put them
+            g = torch.Generator().manual_seed(int(meta.NQ))
+            for ph in meta.slot_mapping.tolist():
+                for cache, host in ((gb.kv.k, wl.k_cache), (gb.kv.v, wl.v_cache)):
+                    row = (torch.randn(wl.num_kv_heads, wl.head_dim, generator=g) * wl.sigma).to(wl.torch_dtype)
+                    cache[ph // 16, :, ph % 16] = row.to(gb.dev)
+                    host[ph // 16, :, ph % 16] = row
+
+        poison()
+        for new_len, fn in ((np.ones(wl.NB, dtype=np.int32), A.aspd_attn_parallel_decode),
+                            (np.full(wl.NB, 3, dtype=np.int32), A.aspd_attn_branch_chunk)):
+            meta = tt.append_parallel(new_len)
+            step = gb.parallel(new_len)
+            write_rows(meta)
+            _compare_attention(A, gb, tt, wl, step, meta, fn, label=f"poisoned {fn.__name__} {wl.dtype}")
+        tt.merge()
+        gb.merge()
+        one = np.ones(wl.B, dtype=np.int32)
+        meta = tt.append_serial(one)
+        step = gb.serial(one)
+        write_rows(meta)
+        _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label=f"poisoned serial {wl.dtype}")
+        assert_state_equal(gb, tt)
 
 
 def test_repeat_calls_agree(A):
