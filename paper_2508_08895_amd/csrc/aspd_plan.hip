@@ -64,10 +64,11 @@ __device__ __forceinline__ int groups_of(const PlanArgs& a, const Sched& sc, int
 // pays for starting a segment (start-up, reduction, a partial to be merged), so that equal shares of
 // units are about equal shares of time.  Two regimes, chosen per step:
 //
-// ALIGNED (every item at least two shares long: few long sequences; pad = 0).  Item i gets the
-// workgroups [rnd(U_i), rnd(U_i + np_i)) with U_i its first unit and rnd(x) = x * n / total rounded
-// to nearest, and is cut evenly among them.  Every workgroup then has exactly one segment, and
-// shares differ by a page or two.
+// EVEN (no more items than workgroups, and pieces that come out about as long as the shares of the
+// ragged regime would).  Every workgroup has exactly one segment: item i is cut evenly among
+// k_i = ceil(np_i / p) workgroups of its own, with p the smallest piece length for which the pieces of
+// all items fit the grid.  A workgroup pays a segment's fixed cost once, and an item that fits one piece
+// needs no merge.
 //
 // RAGGED.  Workgroup w nominally takes [w * total / n, (w + 1) * total / n); a boundary inside an
 // item's padding, or within `tol` units after it or before the item's end, is moved onto the item
@@ -75,10 +76,9 @@ __device__ __forceinline__ int groups_of(const PlanArgs& a, const Sched& sc, int
 // boundaries are tabulated in LDS (wgb), which also gives the owner of a unit by binary search.
 struct Shares {
   int total, n, tol, pad;
-  bool aligned;
-  double per_page;  // n / total: workgroups per unit
-  double share;     // total / n: units per workgroup
-  __device__ __forceinline__ int rnd(int x) const { return min(n, (int)((double)x * per_page + 0.5)); }
+  bool even;
+  int piece;        // EVEN: p, the length no piece exceeds
+  double share;     // RAGGED: total / n, units per workgroup
   __device__ __forceinline__ int nominal_begin(int w) const { return min(total, (int)((double)w * share)); }
 };
 
@@ -108,7 +108,7 @@ __device__ Item locate(const PlanArgs& a, const Sched& sc, int pad, int u, int* 
   return it;
 }
 
-// Cutting one item among its k workgroups (aligned regime).  A page of the branch region costs a wave
+// Cutting one item among its k workgroups (even regime).  A page of the branch region costs a wave
 // more than a page before it (owner tags, masking, scores that are thrown away): measured between 1.1
 // and 1.5 times, taken as 1.25.  The cut is therefore even in cost(p) = 4p + max(0, p - lp) rather than
 // in pages: piece j starts at the first page p with cost(p) * k >= j * cost(np), and page p belongs to
@@ -137,13 +137,13 @@ __device__ int share_begin(const PlanArgs& a, const Sched& sc, const Shares& sh,
 }
 
 // Fills the LDS tables and returns the shares.  All threads of the workgroup call it.
-__device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratch /* 3 * PLAN_THREADS / 64 ints */) {
+__device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratch /* 3 * PLAN_THREADS / 64 + 2 ints */) {
   constexpr int PER = (ASPD_MAX_BATCH + PLAN_THREADS - 1) / PLAN_THREADS;  // sequences per thread
   constexpr int NWV = PLAN_THREADS / 64;
   const int tid = threadIdx.x;
   int mine_p[PER], mine_i[PER];
   int sum_p = 0, sum_i = 0;
-  int shortest = 0x7fffffff;
+  int longest = 0;
 #pragma unroll
   for (int j = 0; j < PER; ++j) {
     const int s = tid * PER + j;
@@ -162,14 +162,14 @@ __device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratc
       if (np > 0 && ng > 0) {
         mine_i[j] = ng * a.num_kv_heads;
         mine_p[j] = np * mine_i[j];
-        shortest = min(shortest, np);
+        longest = max(longest, np);
       }
     }
     sum_p += mine_p[j];
     sum_i += mine_i[j];
   }
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) shortest = min(shortest, __shfl_xor(shortest, off));
+  for (int off = 32; off > 0; off >>= 1) longest = max(longest, __shfl_xor(longest, off));
   // scans: inside the wave by shuffles, across the waves through LDS (one barrier)
   int incl_p = sum_p, incl_i = sum_i;
 #pragma unroll
@@ -184,12 +184,12 @@ __device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratc
   if ((tid & 63) == 63) {
     scratch[tid >> 6] = incl_p;
     scratch[NWV + (tid >> 6)] = incl_i;
-    scratch[2 * NWV + (tid >> 6)] = shortest;
+    scratch[2 * NWV + (tid >> 6)] = longest;
   }
   __syncthreads();
   int run_p = incl_p - sum_p, run_i = incl_i - sum_i;  // exclusive within the wave
   int pages = 0, items = 0;
-  int mn = 0x7fffffff;
+  longest = 0;
 #pragma unroll
   for (int w = 0; w < NWV; ++w) {
     const int tp = scratch[w], ti = scratch[NWV + w];
@@ -199,16 +199,77 @@ __device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratc
     }
     pages += tp;
     items += ti;
-    mn = min(mn, scratch[2 * NWV + w]);
+    longest = max(longest, scratch[2 * NWV + w]);
   }
   Shares sh;
-  const int n0 = max(1, min(a.nwg, pages / MIN_PAGES_PER_WG));
-  sh.aligned = (double)mn * n0 >= 2.0 * pages;
-  sh.pad = sh.aligned ? 0 : a.pad;
+  sh.pad = a.pad;
+  sh.piece = 0;
+  sh.even = false;
+  // ---- EVEN regime?  Thread t tries piece length p_t; the smallest that fits the grid wins.
+  int* best = scratch + 3 * NWV;  // [2]: smallest piece length that fits; workgroups it takes
+  if (tid == 0) best[0] = 0x7fffffff;
+  __syncthreads();
+  if (items > 0 && items <= a.nwg) {
+    const int span = max(longest - MIN_PAGES_PER_WG, 0);
+    const int step = span / PLAN_THREADS + 1;
+    const int p = min(max(longest, 1), MIN_PAGES_PER_WG + tid * step);
+    long need = 0;
+    for (int s = 0; s < a.B; ++s) {
+      const int np = pages_of(a, sc, s);
+      if (np > 0) need += (long)groups_of(a, sc, s) * a.num_kv_heads * ((np + p - 1) / p);
+    }
+    if (need <= a.nwg) atomicMin(best, p);
+  }
+  __syncthreads();
+  if (best[0] != 0x7fffffff) {
+    // pieces of this length against what the ragged regime's longest workgroups would carry (a share and two
+    // segment starts)
+    sh.piece = best[0];
+    sh.even = (long)sh.piece + a.pad <= (long)pages / a.nwg + 2L * a.pad;
+  }
+  __syncthreads();  // (best is read by all before anyone reuses scratch)
+  if (sh.even) {
+    // cu_units[s]: first workgroup of sequence s' items (the unit of this regime is the workgroup)
+    sh.pad = 0;
+    int mine_w[PER], sum_w = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int s = tid * PER + j;
+      mine_w[j] = 0;
+      if (s < a.B && mine_i[j] > 0) mine_w[j] = mine_i[j] * ((mine_p[j] / mine_i[j] + sh.piece - 1) / sh.piece);
+      sum_w += mine_w[j];
+    }
+    int incl_w = sum_w;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl_w, off);
+      if ((tid & 63) >= off) incl_w += v;
+    }
+    if ((tid & 63) == 63) scratch[tid >> 6] = incl_w;
+    __syncthreads();
+    int run_w = incl_w - sum_w, total_w = 0;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) {
+      if (w < (tid >> 6)) run_w += scratch[w];
+      total_w += scratch[w];
+    }
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int s = tid * PER + j;
+      if (s < a.B) sc.cu_units[s] = run_w;
+      run_w += mine_w[j];
+    }
+    if (tid == 0) sc.cu_units[a.B] = total_w;
+    sh.total = total_w;
+    sh.n = total_w;
+    sh.tol = 0;
+    sh.share = 1.0;
+    __syncthreads();
+    return sh;
+  }
   sh.total = pages + sh.pad * items;
   sh.n = pages > 0 ? max(1, min(a.nwg, sh.total / MIN_PAGES_PER_WG)) : 0;
   sh.tol = min((sh.total / max(sh.n, 1)) >> 3, a.pad);
-  sh.per_page = (double)sh.n / (double)max(sh.total, 1);
   sh.share = (double)sh.total / (double)max(sh.n, 1);
 #pragma unroll
   for (int j = 0; j < PER; ++j) {
@@ -219,22 +280,13 @@ __device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratc
   }
   if (tid == 0) sc.cu_units[a.B] = sh.total;
   __syncthreads();
-  if (!sh.aligned) {
-    for (int w = tid; w <= sh.n; w += PLAN_THREADS) sc.wgb[w] = share_begin(a, sc, sh, w);
-    __syncthreads();
-  }
+  for (int w = tid; w <= sh.n; w += PLAN_THREADS) sc.wgb[w] = share_begin(a, sc, sh, w);
+  __syncthreads();
   return sh;
 }
 
-// The workgroup whose share holds unit u.
-__device__ int share_owner(const PlanArgs& a, const Sched& sc, const Shares& sh, int u) {
-  if (sh.aligned) {
-    int page;
-    const Item it = locate(a, sc, 0, u, &page);
-    const int w0 = sh.rnd(it.first_unit);
-    const int k = sh.rnd(it.first_unit + it.np) - w0;
-    return w0 + item_piece(it, page, k);
-  }
+// RAGGED: the workgroup whose share holds unit u.
+__device__ int share_owner(const Sched& sc, const Shares& sh, int u) {
   int lo = 0, hi = sh.n - 1;  // last w with wgb[w] <= u
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
@@ -243,19 +295,33 @@ __device__ int share_owner(const PlanArgs& a, const Sched& sc, const Shares& sh,
   return lo;
 }
 
-// Aligned regime: a workgroup's share is one run of pages of one item.  Rounding moves an item's first
-// workgroup by half a share at most: the item that holds the nominal boundary, or its neighbour.
-__device__ bool aligned_share(const PlanArgs& a, const Sched& sc, const Shares& sh, int w, Item* out, int* page0,
-                              int* page1) {
-  int vpage;
-  Item it = locate(a, sc, 0, sh.nominal_begin(w), &vpage);
-  if (w < sh.rnd(it.first_unit)) it = locate(a, sc, 0, it.first_unit - 1, &vpage);
-  else if (w >= sh.rnd(it.first_unit + it.np)) it = locate(a, sc, 0, it.first_unit + it.np, &vpage);
-  const int w0 = sh.rnd(it.first_unit);
-  const int k = sh.rnd(it.first_unit + it.np) - w0;
-  *page0 = item_cut(it, w - w0, k);
-  *page1 = item_cut(it, w + 1 - w0, k);
+// EVEN: the one segment of workgroup w, and the first and last workgroup of its item.
+__device__ bool even_share(const PlanArgs& a, const Sched& sc, const Shares& sh, int w, Item* out, int* page0,
+                           int* page1, int* owner, int* w_last) {
+  int lo = 0, hi = a.B - 1;  // the last sequence whose first workgroup is at or before w
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (sc.cu_units[mid] <= w) lo = mid; else hi = mid - 1;
+  }
+  Item it;
+  it.s = lo;
+  it.np = pages_of(a, sc, lo);
+  const int k = (it.np + sh.piece - 1) / sh.piece;  // workgroups per item of this sequence
+  const int local = w - sc.cu_units[lo];
+  const int idx = local / k, j = local - idx * k;
+  const int ngroups = groups_of(a, sc, lo);
+  it.h = idx / ngroups;       // row groups of one KV head are neighbours: they read the same pages
+  it.rg = idx - it.h * ngroups;
+  it.first_unit = 0;
+  it.lp = a.has_owner ? min(it.np, sc.L[lo] / ASPD_BLOCK) : it.np;
+  const int qs = sc.q0[lo];
+  it.q0 = qs + it.rg * a.qpg;
+  it.nq = min(a.qpg, sc.q0[lo + 1] - qs - it.rg * a.qpg);
   *out = it;
+  *page0 = item_cut(it, j, k);
+  *page1 = item_cut(it, j + 1, k);
+  *owner = w - j;
+  *w_last = w - j + k - 1;
   return *page1 > *page0;
 }
 
@@ -274,34 +340,38 @@ __device__ bool next_segment(const PlanArgs& a, const Sched& sc, const Shares& s
   return false;
 }
 
-// A workgroup's walk over its share, as an iterator.
+// A workgroup's walk over its share, as an iterator: each step gives a segment and the first and last
+// workgroup that hold a part of its item.
 struct Walk {
   int u, end;
-  bool aligned_pending;
+  bool even_pending;
 };
 __device__ __forceinline__ Walk walk_begin(const Sched& sc, const Shares& sh, int w) {
   Walk wk;
   wk.u = wk.end = 0;
-  wk.aligned_pending = sh.aligned && w < sh.n;
-  if (!sh.aligned && w < sh.n) {
+  wk.even_pending = sh.even && w < sh.n;
+  if (!sh.even && w < sh.n) {
     wk.u = sc.wgb[w];
     wk.end = sc.wgb[w + 1];
   }
   return wk;
 }
 __device__ __forceinline__ bool walk_next(const PlanArgs& a, const Sched& sc, const Shares& sh, int w, Walk* wk,
-                                          Item* it, int* page0, int* page1) {
-  if (sh.aligned) {
-    if (!wk->aligned_pending) return false;
-    wk->aligned_pending = false;
-    return aligned_share(a, sc, sh, w, it, page0, page1);
+                                          Item* it, int* page0, int* page1, int* owner, int* w_last) {
+  if (sh.even) {
+    if (!wk->even_pending) return false;
+    wk->even_pending = false;
+    return even_share(a, sc, sh, w, it, page0, page1, owner, w_last);
   }
-  return next_segment(a, sc, sh, &wk->u, wk->end, it, page0, page1);
+  if (!next_segment(a, sc, sh, &wk->u, wk->end, it, page0, page1)) return false;
+  *owner = *page0 == 0 ? w : share_owner(sc, sh, it->first_unit + sh.pad);
+  *w_last = *page1 == it->np ? w : share_owner(sc, sh, it->first_unit + sh.pad + it->np - 1);
+  return true;
 }
 
 __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanArgs a) {
   extern __shared__ int lds[];
-  __shared__ int scratch[3 * PLAN_THREADS / 64];
+  __shared__ int scratch[3 * PLAN_THREADS / 64 + 2];
   __shared__ int wave_tot[PLAN_THREADS / 64];
   const Sched sc = sched_at(lds, a.B);
   const int tid = threadIdx.x;
@@ -314,8 +384,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanArgs a) {
   if (w < a.nwg) {
     Walk wk = walk_begin(sc, sh, w);
     Item it;
-    int p0, p1;
-    while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1)) ++cnt;
+    int p0, p1, owner, w_last;
+    while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1, &owner, &w_last)) ++cnt;
   }
   // exclusive scan, over the workgroups, of the segments beyond the first
   const int extra = max(cnt - 1, 0);
@@ -338,11 +408,9 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanArgs a) {
   hdr[PLAN_HDR_NEXT] = run;
   Walk wk = walk_begin(sc, sh, w);
   Item it;
-  int p0, p1;
+  int p0, p1, owner, w_last;
   int i = 0;
-  while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1)) {
-    const int owner = p0 == 0 ? w : share_owner(a, sc, sh, it.first_unit + sh.pad);
-    const int w_last = p1 == it.np ? w : share_owner(a, sc, sh, it.first_unit + sh.pad + it.np - 1);
+  while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1, &owner, &w_last)) {
     int32_t* d = i == 0 ? hdr : seg_list + PLAN_SEG * (run + i - 1);
     typedef int i32x4 __attribute__((ext_vector_type(4)));
     *(i32x4*)d = i32x4{it.s | (it.h << 16), it.q0, it.nq, p0};
