@@ -140,6 +140,11 @@ typedef struct aspd_step {
   int32_t  max_workgroups;  /* host: most workgroups an attention launch of this step may use, for callers
                                that run other kernels next to attention and want compute units left for
                                them; 0 = one per compute unit.  Results do not depend on it.            */
+  int32_t  shared_mask;     /* host: 0 = the branch-independent mask of Eq. 2-3 (the paper's choice); 1 = the
+                               "Shared" mask of the ablation (Sec. 4.5.2, Table "PosId x mask"): branch tokens are
+                               treated like main-branch tokens, every row attends every slot of its sequence up
+                               to and including its own, sibling branches included.  Read by the metadata call
+                               (for the plan) and by aspd_attn_parallel_decode / aspd_attn_branch_chunk        */
   int32_t* cu_new_d;        /* [NB+1] (PARALLEL) or [B+1] (SERIAL): first row of each branch / sequence */
   int32_t* cu_seq_new_d;    /* [B+1] first row of each sequence                                    */
   int32_t* q_seq_d;         /* [NQ] sequence of the token                                          */

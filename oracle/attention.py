@@ -38,7 +38,7 @@ def attend_queries(q_rows: np.ndarray, k_rows: np.ndarray, v_rows: np.ndarray, m
 
 
 def attend(table: TokenTable, meta: StepMeta, q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor,
-           scale: float | None = None, rows=None):
+           scale: float | None = None, rows=None, shared_mask: bool = False):
     """Attention for the tokens of one append call (any of: parallel decode step, branch chunk,
     serial step), each query attending what Eq. 2-3 let it see among ALL slots now in its sequence.
 
@@ -57,7 +57,7 @@ def attend(table: TokenTable, meta: StepMeta, q: torch.Tensor, k_cache: torch.Te
     want = np.arange(NQ) if rows is None else np.asarray(rows, dtype=np.int64)
     for s in np.unique(meta.q_seq[want]):
         idx = want[meta.q_seq[want] == s]
-        mask = table.dense_mask(int(s), meta.logical_slot[idx])
+        mask = table.dense_mask(int(s), meta.logical_slot[idx], shared=shared_mask)
         phys = table.physical_slots(int(s))
         for kvh in range(Hkv):
             k_rows = _rows_f64(k_cache, phys, kvh, table.block_size)

@@ -254,9 +254,14 @@ class TokenTable:
             S = 0
         return S == 1 and (self.pos[s][i] > self.pos[s][j] or i == j)
 
-    def dense_mask(self, s: int, query_slots) -> np.ndarray:
-        """bool [len(query_slots)][T_s]: the same rule as visible_pair, on whole arrays."""
+    def dense_mask(self, s: int, query_slots, shared: bool = False) -> np.ndarray:
+        """bool [len(query_slots)][T_s]: the same rule as visible_pair, on whole arrays.
+        shared: the "Shared" mask the paper's ablation compares against (Sec. 4.5.2), read here as ordinary
+        causal attention over the one cache: every token sees every slot up to and including its own,
+        sibling branches included."""
         q = np.asarray(query_slots, dtype=np.int64)
+        if shared:
+            return np.arange(len(self.pos[s]), dtype=np.int64)[None, :] <= q[:, None]
         stage = np.asarray(self.stage[s], dtype=np.int64)
         branch = np.asarray(self.branch[s], dtype=np.int64)
         pos = np.asarray(self.pos[s], dtype=np.int64)

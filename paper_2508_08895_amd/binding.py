@@ -48,7 +48,7 @@ class aspd_state(C.Structure):
 
 class aspd_step(C.Structure):
     _fields_ = [("NQ", C.c_int32), ("max_new_per_seq", C.c_int32), ("max_workgroups", C.c_int32),
-                ("cu_new_d", C.c_void_p), ("cu_seq_new_d", C.c_void_p),
+                ("shared_mask", C.c_int32), ("cu_new_d", C.c_void_p), ("cu_seq_new_d", C.c_void_p),
                 ("q_seq_d", C.c_void_p), ("q_branch_d", C.c_void_p), ("position_ids_d", C.c_void_p),
                 ("logical_slot_d", C.c_void_p), ("slot_mapping_d", C.c_void_p), ("kv_len_d", C.c_void_p),
                 ("plan_d", C.c_void_p), ("plan_bytes", C.c_size_t), ("plan_key", C.c_uint64)]
@@ -170,6 +170,7 @@ class Step:
         self.NQ = int(NQ)
         self.max_new_per_seq = int(max_new_per_seq)   # tuning hint, 0 = unknown
         self.max_workgroups = int(max_workgroups)     # cap of the attention grids, 0 = none
+        self.shared_mask = 0                          # 1: the ablation's shared mask (see aspd_step.shared_mask)
         self.plan = None                              # device buffer for the step's plan (see aspd_step.plan_d)
         self.plan_key = 0                             # as aspd_build_branch_meta left it
         i32 = dict(dtype=torch.int32, device=device)
@@ -185,7 +186,8 @@ class Step:
 
     def struct(self) -> aspd_step:
         plan_bytes = 0 if self.plan is None else self.plan.numel() * self.plan.element_size()
-        return aspd_step(self.NQ, self.max_new_per_seq, self.max_workgroups, _ptr(self.cu_new), _ptr(self.cu_seq_new),
+        return aspd_step(self.NQ, self.max_new_per_seq, self.max_workgroups, self.shared_mask, _ptr(self.cu_new),
+                         _ptr(self.cu_seq_new),
                          _ptr(self.q_seq), _ptr(self.q_branch), _ptr(self.position_ids), _ptr(self.logical_slot),
                          _ptr(self.slot_mapping), _ptr(self.kv_len), _ptr(self.plan), plan_bytes, self.plan_key)
 

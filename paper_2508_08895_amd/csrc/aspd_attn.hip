@@ -1440,7 +1440,7 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   if (!step->q_branch_d || !step->logical_slot_d || !q_d || !out_d) return ASPD_ERR_INVALID_ARG;
   if (((uintptr_t)q_d & 15) || ((uintptr_t)out_d & 15)) return ASPD_ERR_INVALID_ARG;
   if (!(sm_scale >= 0.f)) return ASPD_ERR_INVALID_ARG;
-  const bool branches = (mode != MODE_SERIAL);
+  const bool branches = (mode != MODE_SERIAL) && step->shared_mask == 0;  // rows that may carry branch tags
   if (branches) {
     if (!state->cu_branches_d || !state->slot_owner_d) return ASPD_ERR_INVALID_ARG;
     if (state->owner_stride < kv->max_blocks_per_seq * ASPD_BLOCK || (state->owner_stride & 3) ||

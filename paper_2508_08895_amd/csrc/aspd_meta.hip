@@ -327,7 +327,7 @@ extern "C" int aspd_build_branch_meta(const aspd_kv* kv, aspd_state* state, int3
   out->plan_key = 0;
   if (out->plan_d && out->NQ > 0 &&
       aspd_choose_variant(kv, state->B, out->NQ, out->max_new_per_seq, out->max_workgroups, false,
-                          stage != ASPD_STAGE_SERIAL, &variant)) {
+                          stage != ASPD_STAGE_SERIAL && out->shared_mask == 0, &variant)) {
     if (((uintptr_t)out->plan_d & 255) ||
         out->plan_bytes < aspd_plan_words(kv, variant, state->B, out->NQ) * sizeof(int32_t))
       return ASPD_ERR_INVALID_ARG;

@@ -27,7 +27,7 @@ def A():
     return binding
 
 
-def _compare_attention(A, gb, tt, wl, step, meta, fn, rows=None, label="", check_step=True):
+def _compare_attention(A, gb, tt, wl, step, meta, fn, rows=None, label="", check_step=True, shared_mask=False):
     from gpu_drive import assert_step_equal
     if check_step:
         assert_step_equal(step, meta)
@@ -35,7 +35,7 @@ def _compare_attention(A, gb, tt, wl, step, meta, fn, rows=None, label="", check
     lse = torch.full((meta.NQ, wl.num_q_heads), float("nan"), dtype=torch.float32, device=gb.dev)
     out = fn(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace, lse=lse)
     torch.cuda.synchronize()
-    ref, ref_lse = attend(tt, meta, q, wl.k_cache, wl.v_cache, rows=rows)
+    ref, ref_lse = attend(tt, meta, q, wl.k_cache, wl.v_cache, rows=rows, shared_mask=shared_mask)
     got = out.float().cpu().numpy().astype(np.float64)
     got_lse = lse.cpu().numpy().astype(np.float64)
     sel = np.arange(meta.NQ) if rows is None else np.asarray(rows)
@@ -763,6 +763,96 @@ def test_unwritten_slots_may_hold_anything(A):
         write_rows(meta)
         _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_serial_decode, label=f"poisoned serial {wl.dtype}")
         assert_state_equal(gb, tt)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_shared_mask_of_the_ablation(A, dtype):
+    """aspd_step.shared_mask: branch rows attend like main-branch rows (every slot up to their own, siblings
+    included), set before the metadata call (the step's plan is built for it) and after it (the attention
+    call builds its own); decode step and chunk."""
+    from gpu_drive import GpuBatch
+    kw = dict(dtype="f32", head_dim=64, num_q_heads=4, num_kv_heads=2) if dtype == "f32" else {}
+    wl = W.random_small(136, batch=3, prefix_range=(20, 500), branches_range=(2, 6), **kw)
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    for new_tokens, fn, before in ((1, A.aspd_attn_parallel_decode, True), (4, A.aspd_attn_branch_chunk, False)):
+        new_len = np.full(wl.NB, new_tokens, dtype=np.int32)
+        meta = tt.append_parallel(new_len)
+        step = A.Step(int(new_len.sum()), wl.NB, wl.B, gb.dev, max_new_per_seq=new_tokens * int(wl.num_branches.max()))
+        step.shared_mask = 1 if before else 0
+        A.aspd_build_branch_meta(gb.kv, gb.state, A.STAGE_PARALLEL, gb._dev_i32(new_len), step=step)
+        step.shared_mask = 1
+        err_shared = _compare_attention(A, gb, tt, wl, step, meta, fn, label=f"shared mask {fn.__name__}", shared_mask=True)
+        # and the flag does change what is computed: the same call without it matches the independent mask
+        step.shared_mask = 0
+        _compare_attention(A, gb, tt, wl, step, meta, fn, label=f"independent mask {fn.__name__}")
+        assert err_shared <= TOL[wl.dtype]
+
+
+def test_engine_drives_the_library_like_the_oracle(A):
+    """The host engine (special-token state machine, Sec. 3.3) on the HIP library, in lockstep with the same
+    engine logic on the oracle's token table: every step's metadata bit-exact, every step's attention (the
+    entry point the engine names) against the dense-mask oracle on K/V rows written at the step's slots."""
+    from engine_drive import OracleDriver, ScriptedModel
+    from gpu_drive import GpuBatch, assert_step_equal, assert_state_equal
+    from paper_2508_08895_amd.engine import HybridEngine, LibraryDriver, SpecialTokens
+    SP = SpecialTokens(901, 902, 903, 904, 905, 906, 999, prefix_sep=(907,))
+    wl = W.random_small(137, batch=3, prefix_range=(5, 5), branches_range=(3, 3), branch_len_range=(40, 40),
+                        extra_tokens_per_seq=60)                  # sizes pools and tables only
+    gb = GpuBatch(wl)
+    lib, orc = LibraryDriver(A, gb.kv, gb.state), OracleDriver(wl.block_tables, wl.block_size)
+
+    class Tee:
+        def serial(self, n, hint):
+            self.meta = orc.serial(n, hint)
+            return lib.serial(n, hint)
+
+        def mixed(self, nb, nm, hint):
+            self.meta = orc.mixed(nb, nm, hint)
+            return lib.mixed(nb, nm, hint)
+
+        def renumber(self, k):
+            orc.renumber(k)
+            lib.renumber(k)
+
+        def merge(self, which):
+            orc.merge(which)
+            lib.merge(which)
+
+    tee = Tee()
+    eng = HybridEngine(tee, SP, batch=wl.B)
+
+    def titles(*ts):
+        out = []
+        for t in ts:
+            out += [SP.title_open, *t, SP.title_close]
+        return out + [SP.para_open]
+
+    main = [[40, 41, 42, 43, 44, 45, SP.eos],
+            [*titles([11, 12], [21]), 51, *titles([31], [11, 12]), 52, SP.eos],
+            [60, 61, *titles([11], [21, 22], [31]), 63, SP.eos]]
+    stages = [[],
+              [[[1, 2, 3, SP.branch_close], [4, SP.branch_close]], [[5, SP.branch_close], [6, 7, SP.branch_close]]],
+              [[[8, SP.branch_close], [9, 9, 9, 9, SP.branch_close], [SP.branch_close]]]]
+    model = ScriptedModel(main, stages)
+    g = torch.Generator().manual_seed(137)
+    plan = eng.prefill([[1], [2, 2], [3, 3, 3]])
+    steps = 0
+    while plan is not None:
+        meta = tee.meta
+        assert_step_equal(plan.step, meta)
+        # the new tokens' K/V rows, where the step says they go (device cache and the oracle's host copy)
+        for ph in meta.slot_mapping.tolist():
+            for cache, host in ((gb.kv.k, wl.k_cache), (gb.kv.v, wl.v_cache)):
+                row = (torch.randn(wl.num_kv_heads, wl.head_dim, generator=g) * wl.sigma).to(wl.torch_dtype)
+                cache[ph // 16, :, ph % 16] = row.to(gb.dev)
+                host[ph // 16, :, ph % 16] = row
+        _compare_attention(A, gb, orc.tt, wl, plan.step, meta, getattr(A, plan.attention), label=f"engine step {steps} {plan.attention}",
+                           check_step=False)
+        eng.accept(model(eng, plan))
+        assert_state_equal(gb, orc.tt)
+        plan = eng.next_step()
+        steps += 1
+    assert eng.finished() and [s.stages for s in eng.seqs] == [0, 2, 1]
 
 
 def test_repeat_calls_agree(A):

@@ -448,3 +448,27 @@ def test_replay_is_deterministic():
     wl = W.random_small(16, batch=3)
     a, b = table_at(wl, wl.branch_len), table_at(wl, wl.branch_len)
     assert a.pos == b.pos and a.branch == b.branch and a.stage == b.stage
+
+
+# ----------------------------------------------------------------------------- shared mask of the ablation
+def test_shared_mask_is_causal_attention_over_the_cache():
+    """The ablation's "Shared" mask: lower-triangular in slot order whatever the branches are; with one
+    branch per stage it coincides with the branch-independent mask (which is then native autoregression);
+    main-branch rows are the same under both masks."""
+    wl = W.random_small(77, batch=3, branches_range=(2, 4), branch_len_range=(2, 6), prefix_range=(1, 9))
+    tt = table_at(wl, wl.branch_len)
+    tt.merge()
+    tt.append_serial(np.ones(wl.B, dtype=np.int32))
+    for s in range(wl.B):
+        T = len(tt.pos[s])
+        m = tt.dense_mask(s, range(T), shared=True)
+        assert (m == np.tril(np.ones((T, T), dtype=bool))).all()
+        ind = tt.dense_mask(s, range(T))
+        main_rows = [j for j in range(T) if tt.branch[s][j] == MAIN]
+        assert (m[main_rows] == ind[main_rows]).all()
+        assert (m | ind == m).all()                       # the shared mask only ever adds keys
+    one = W.random_small(78, batch=2, branches_range=(1, 1), branch_len_range=(3, 9), prefix_range=(2, 9))
+    t1 = table_at(one, one.branch_len)
+    for s in range(one.B):
+        T = len(t1.pos[s])
+        assert (t1.dense_mask(s, range(T), shared=True) == t1.dense_mask(s, range(T))).all()
