@@ -17,7 +17,7 @@ Per call kind the average launch is measured separately: REP back-to-back launch
 kernel (no metadata calls between them), captured once, timed with events on the launch stream, each
 launch on another KV pool so that no timed byte comes from a cache.  `roofline` is the parallel-decode
 kernel on configuration 5 alone against the HBM peak; `roofline_chunk` the branch-chunk kernel against the
-dense bf16 MFMA peak; `cpu_baseline` the CPU oracle (numpy, BLAS-threaded) on a bounded sample.
+dense bf16 MFMA peak; `cpu_baseline` the CPU oracle (its C writing, OpenMP on all host cores) on a bounded sample.
 One GPU only.
 """
 from __future__ import annotations
@@ -466,12 +466,8 @@ def main() -> int:
 
 def cpu_baseline(wl, base_len, chunk, np):
     """The oracle as it stands, timed on this host for the parallel-decode call of the workload."""
-    from oracle import TokenTable, attend
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        threads = os.cpu_count() or 1
+    from oracle import TokenTable
+    from oracle import attention_c
     tt = TokenTable(wl.block_tables, wl.block_size)
     tt.append_serial(wl.prefix_len)
     tt.open_parallel(wl.num_branches)
@@ -490,13 +486,14 @@ def cpu_baseline(wl, base_len, chunk, np):
         rows = None
         if meta.NQ > 48:  # bound the work: a seeded sample of the rows
             rows = np.sort(np.random.default_rng(1 + steps).choice(meta.NQ, size=48, replace=False))
-        attend(tt, meta, q, wl.k_cache, wl.v_cache, rows=rows)
+        attention_c.attend_c(tt, meta, q, wl.k_cache, wl.v_cache, rows=rows)
         done += meta.NQ if rows is None else len(rows)
         total += meta.NQ
         steps += 1
     dt = time.perf_counter() - t0
-    return {"value": round(done / dt, 3), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "implementation": "numpy float64, dense mask, matrix products through the BLAS numpy links (its threads are `cores`)",
+    return {"value": round(done / dt, 3), "unit": "tokens/s", "cores": int(attention_c.last_threads), "kind": "oracle",
+            "implementation": "oracle/attention_ref.c: plain C loops, float64, explicit dense mask, OpenMP over (row, head), "
+                              "no BLAS; metadata and mask from the Python token table",
             "sample": f"{steps} consecutive parallel-decode calls: {done} of {total} branch queries x "
                       f"{wl.num_q_heads} heads, metadata + float64 dense-mask attention, {dt:.1f}s"}
 

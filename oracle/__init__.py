@@ -9,6 +9,8 @@ from it.
                   append history; position ids (Eq. 4); cache slots; the dense
                   mask (Eq. 2-3).
   attention.py    Eq. 1 in float64 with the explicit dense mask.
+  attention_ref.c the same in plain C loops with OpenMP and no BLAS (attention_c.py loads it): a second
+                  writing that the pins also run against, and the one bench.py times on the host's cores.
   rope.py         rotary encoding of the new tokens by their Eq. 4 position ids and their
                   placement in the cache (the step between the metadata and the attention call).
 
