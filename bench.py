@@ -480,12 +480,12 @@ def cpu_baseline(wl, base_len, chunk, np):
     # consecutive parallel-decode steps (metadata + attention each) until about ten seconds have passed
     t0 = time.perf_counter()
     done = total = steps = 0
-    while steps < max(max_steps, 1) and time.perf_counter() - t0 < 10.0:
+    while steps < max(max_steps, 1) and time.perf_counter() - t0 < 15.0:
         meta = tt.append_parallel(ones)
         q = wl.draw_q(meta.NQ)
         rows = None
-        if meta.NQ > 48:  # bound the work: a seeded sample of the rows
-            rows = np.sort(np.random.default_rng(1 + steps).choice(meta.NQ, size=48, replace=False))
+        if meta.NQ > 128:  # bound the work: a seeded sample of the rows
+            rows = np.sort(np.random.default_rng(1 + steps).choice(meta.NQ, size=128, replace=False))
         attention_c.attend_c(tt, meta, q, wl.k_cache, wl.v_cache, rows=rows)
         done += meta.NQ if rows is None else len(rows)
         total += meta.NQ
