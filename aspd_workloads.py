@@ -224,3 +224,32 @@ def interleaved_history(target_len) -> list:
     target_len = np.asarray(target_len, dtype=np.int32)
     steps = int(target_len.max()) if target_len.size else 0
     return [(target_len > t).astype(np.int32) for t in range(steps)]
+
+
+def random_layouts(wl: Workload, seed: int, max_stages: int = 3, max_branches: int = 6, fill: float = 1.0) -> list:
+    """Per sequence of `wl` the runs of a whole multi-stage sequence in cache order, [(branch, tokens)]:
+    (0, n) main-branch tokens, (k, n) the k-th branch of a parallel stage (branches of a stage numbered
+    1..K in order); serial and parallel stages alternate, a sequence may start or end with either, runs
+    may be empty.  The tokens of a sequence fill `fill` of what its block table has room for."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for s in range(wl.B):
+        room = int(fill * wl.block_size * int((wl.block_tables[s] >= 0).sum()))
+        P = int(rng.integers(0, max_stages + 1))
+        w = rng.random(2 * P + 1) + 0.05
+        if P > 0 and rng.random() < 0.25:
+            w[0] = 0.0                       # the sequence starts with a parallel stage
+        if P > 0 and rng.random() < 0.25:
+            w[-1] = 0.0                      # ... or ends with one
+        seg = np.floor(room * w / w.sum()).astype(np.int64)
+        runs = []
+        for i, n in enumerate(seg):
+            if i % 2 == 0:
+                runs.append((0, int(n)))
+            else:
+                K = int(rng.integers(1, max_branches + 1))
+                cut = np.sort(rng.integers(0, int(n) + 1, size=K - 1))
+                lens = np.diff(np.concatenate([[0], cut, [int(n)]]))
+                runs.extend((k + 1, int(lens[k])) for k in range(K))
+        out.append(runs)
+    return out

@@ -274,6 +274,13 @@ class TokenTable:
         itself = q[:, None] == slots[None, :]
         return S & (before | itself)
 
+    def all_tokens_meta(self) -> StepMeta:
+        """Every token now in the table as a query row, sequence-major in slot order: what a teacher-forced
+        pass over whole sequences attends (Fig. 5, training arrangement).  q_branch holds the token's branch
+        number within its own stage minus one (-1 for main-branch tokens); cu_new is not meaningful here."""
+        rows = [(s, self.branch[s][j] - 1, j) for s in range(self.B) for j in range(len(self.pos[s]))]
+        return self._step_meta(rows, np.zeros(1, dtype=np.int32))
+
     # ------------------------------------------------------------------ internals
     def _step_meta(self, rows, cu_new) -> StepMeta:
         nq = len(rows)
