@@ -362,6 +362,35 @@ def extras(name, args, mods, env, per_call):
                          "note": f"{int(ending.sum())} sequences serial, {B - int(ending.sum())} in their parallel stage, "
                                  "one launch; outside the timed step"}
     assert int(state.fault.item()) == 0
+    if wl.dtype != "bf16":
+        return
+    # whole sequences (teacher forcing, re-prefill): every token of the batch a query row, one launch
+    layouts = W.random_layouts(wl, seed=17, max_branches=10, fill=0.97)
+    cu = np.zeros(B + 1, dtype=np.int32)
+    np.cumsum([len(r) for r in layouts], out=cu[1:])
+    br = np.array([b for r in layouts for b, _ in r], dtype=np.int32)
+    ln = np.array([n for r in layouts for _, n in r], dtype=np.int32)
+    nq_all = int(ln.sum())
+    st2 = A.BatchState(B, state.owner_stride, dev)
+    step_s = A.aspd_build_sequence_meta(kv, st2, dev_i32(cu), dev_i32(br), dev_i32(ln), NQ=nq_all)
+    q_s = rand_q(nq_all)
+    out_s = torch.empty_like(q_s)
+    keys = int(step_s.kv_len[:nq_all].to(torch.int64).sum().item())
+    flops = keys * 4 * wl.head_dim * wl.num_q_heads
+
+    def seq_body():
+        for _ in range(REP):
+            A.aspd_attn_full_sequence(next_kv(), st2, step_s, q_s, ws, out=out_s)
+
+    avg = float(np.mean(timed_runner(seq_body, reps=2)))
+    assert int(st2.fault.item()) == 0
+    per_call["full_sequence"] = {"launches_per_step": 0, "avg_us": round(avg * 1e6, 1), "query_tokens_per_launch": nq_all,
+                                 "query_tokens_per_s": round(nq_all / avg, 1), "algorithmic_GFLOP": round(flops / 1e9, 1),
+                                 "TFLOPs": round(flops / avg / 1e12, 1),
+                                 "frac_of_bf16_mfma_peak": round(flops / avg / 1e12 / MFMA_BF16_TFLOPS, 4),
+                                 "note": "all tokens of the batch as query rows under the mask of Eq. 2-3 (serial and "
+                                         "parallel stages alternating, branches laid one after the other); flops count "
+                                         "visible keys only; outside the timed step"}
 
 
 def main() -> int:

@@ -252,6 +252,59 @@ ASPD_API int aspd_attn_serial_decode(const aspd_kv* kv, const aspd_state* state,
                             const void* q_d, void* out_d, float* lse_d, float sm_scale,
                             void* workspace_d, size_t workspace_bytes, void* stream);
 
+/* ---- A whole sequence in one call (teacher forcing, re-prefill) -----------------------------------
+ * Fig. 5 (training arrangement: the branches of a stage laid one after the other), Eq. 2-4 over all
+ * tokens of a multi-stage sequence at once, and the re-prefill that the "Same-Re" paradigm of Sec. 4.5.3
+ * performs after every stage.  The cache of every sequence is (re)built from slot 0.
+ *
+ * The layout of sequence s is the list of its runs cu_runs[s] .. cu_runs[s+1]-1 in cache order.  Run r holds
+ * run_len[r] >= 0 consecutive tokens of one branch: run_branch[r] = 0 for main-branch tokens, k >= 1 for the
+ * k-th branch of a parallel stage.  A parallel stage is a succession of runs numbered 1, 2, .., K (K <=
+ * ASPD_MAX_BRANCHES_PER_SEQ), each branch exactly one run; a run numbered 1 always opens a new stage.  Any
+ * other numbering raises ASPD_FAULT_LAYOUT and leaves the sequence without tokens.
+ * At most ASPD_MAX_RUNS_PER_SEQ runs per sequence. */
+#define ASPD_MAX_RUNS_PER_SEQ 2048
+#define ASPD_FAULT_LAYOUT     64 /* aspd_build_sequence_meta: branch runs of a stage not numbered 1..K in order,
+                                    or too many runs                                                      */
+typedef struct aspd_layout {
+  int32_t        num_runs;      /* host: R, runs over the whole batch                                  */
+  const int32_t* cu_runs_d;     /* [B+1] exclusive scan of runs per sequence                            */
+  const int32_t* run_branch_d;  /* [R]                                                                  */
+  const int32_t* run_len_d;     /* [R]                                                                  */
+} aspd_layout;
+
+/* Bytes of aspd_step.plan_d that aspd_build_sequence_meta needs for a batch of B sequences and NQ tokens
+ * (0 for arguments the library does not support). */
+ASPD_API size_t aspd_sequence_plan_bytes(const aspd_kv* kv, int32_t B, int32_t NQ);
+
+/* Metadata of all tokens of the batch, row r of sequence s being the token at logical slot r - cu_seq_new[s]:
+ * position ids by Eq. 4 under pos_mode (main-branch tokens as in ASPD_STAGE_SERIAL appends, tokens of a stage
+ * as in one ASPD_STAGE_PARALLEL append of whole branches, every stage followed by a merge), logical and
+ * physical slots, kv_len (the keys Eq. 2-3 let the token see, itself included), q_seq, and in q_branch the
+ * token's branch number within its own stage minus one (-1 for main-branch tokens).  cu_new_d is not
+ * written.  out->NQ must equal the sum of run_len (else ASPD_FAULT_ROW_COUNT); out->plan_d is required
+ * (aspd_sequence_plan_bytes): it receives, per row, the first slot of the row's own stage, and the list of
+ * row groups the attention call works through.  The state is left as after a merge of the last stage:
+ * seq_len = stage_base = tokens of the sequence, stage_open = 0, main_pos = the next main-branch position,
+ * branch_len of the sequence's entries untouched; slot_owner[s][j] = branch number of slot j within its
+ * stage (0 for main-branch slots).  Decoding continues from there with aspd_build_branch_meta.
+ * Faults as in aspd_build_branch_meta (a sequence that does not fit its block table or owner row, or breaks
+ * the layout rules, gets no tokens: seq_len = 0, the packed rows its layout gave it stay unwritten and the
+ * attention call skips them; ASPD_FAULT_ROW_COUNT accompanies the cause). */
+ASPD_API int aspd_build_sequence_meta(const aspd_kv* kv, aspd_state* state, const aspd_layout* layout,
+                                      int32_t pos_mode, aspd_step* out, void* stream);
+
+/* Eq. 1-3 for every token of every sequence in one launch: row r attends the slots up to and including its
+ * own that are main-branch slots, slots of other stages, or slots of its own branch.  `step` is one built by
+ * aspd_build_sequence_meta (anything else: ASPD_ERR_INVALID_ARG); the K and V rows of all its tokens are in
+ * the cache (aspd_rope_append with the same step writes them).  bf16 only (ASPD_ERR_UNSUPPORTED for fp32).
+ * Key pages beyond a row group's last slot are never read, and a wave skips the pages of a stage that hold
+ * only sibling branches of its rows.  Other arguments as aspd_attn_parallel_decode; the workspace needs
+ * aspd_workspace_bytes(kv, B, NQ) like any other call (only its counters are used). */
+ASPD_API int aspd_attn_full_sequence(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
+                                     const void* q_d, void* out_d, float* lse_d, float sm_scale,
+                                     void* workspace_d, size_t workspace_bytes, void* stream);
+
 /* aspd_attn_parallel_decode for callers that cannot allocate device memory (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace,
  * same results.  The scratch is an array inside the library's code object, ASPD_STATIC_SCRATCH_BYTES per

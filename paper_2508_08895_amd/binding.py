@@ -25,10 +25,12 @@ def POS_FIX_N(n: int) -> int:
     return 2 | (int(n) << 8)
 
 FAULT_BLOCK_TABLE, FAULT_OWNER_ROW, FAULT_ROW_COUNT, FAULT_BRANCHES, FAULT_STAGE, FAULT_INTERVAL = 1, 2, 4, 8, 16, 32
+FAULT_LAYOUT = 64
 
 EXPORTS = ("aspd_build_branch_meta", "aspd_renumber_branches", "aspd_rope_append", "aspd_plan_bytes",
            "aspd_workspace_bytes", "aspd_workspace_init", "aspd_attn_parallel_decode",
            "aspd_attn_branch_chunk", "aspd_attn_serial_decode", "aspd_attn_parallel_decode_static",
+           "aspd_sequence_plan_bytes", "aspd_build_sequence_meta", "aspd_attn_full_sequence",
            "aspd_probe_read_bandwidth", "aspd_status_string")
 
 
@@ -52,6 +54,11 @@ class aspd_step(C.Structure):
                 ("q_seq_d", C.c_void_p), ("q_branch_d", C.c_void_p), ("position_ids_d", C.c_void_p),
                 ("logical_slot_d", C.c_void_p), ("slot_mapping_d", C.c_void_p), ("kv_len_d", C.c_void_p),
                 ("plan_d", C.c_void_p), ("plan_bytes", C.c_size_t), ("plan_key", C.c_uint64)]
+
+
+class aspd_layout(C.Structure):
+    _fields_ = [("num_runs", C.c_int32), ("cu_runs_d", C.c_void_p), ("run_branch_d", C.c_void_p),
+                ("run_len_d", C.c_void_p)]
 
 
 class AspdError(RuntimeError):
@@ -82,7 +89,13 @@ def lib() -> C.CDLL:
         L.aspd_plan_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
         L.aspd_workspace_bytes.restype = C.c_size_t
         L.aspd_workspace_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
-        for name in ("aspd_attn_parallel_decode", "aspd_attn_branch_chunk", "aspd_attn_serial_decode"):
+        L.aspd_sequence_plan_bytes.restype = C.c_size_t
+        L.aspd_sequence_plan_bytes.argtypes = [C.POINTER(aspd_kv), C.c_int32, C.c_int32]
+        L.aspd_build_sequence_meta.restype = C.c_int
+        L.aspd_build_sequence_meta.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_state), C.POINTER(aspd_layout),
+                                               C.c_int32, C.POINTER(aspd_step), C.c_void_p]
+        for name in ("aspd_attn_parallel_decode", "aspd_attn_branch_chunk", "aspd_attn_serial_decode",
+                     "aspd_attn_full_sequence"):
             fn = getattr(L, name)
             fn.restype = C.c_int
             fn.argtypes = [C.POINTER(aspd_kv), C.POINTER(aspd_state), C.POINTER(aspd_step), C.c_void_p,
@@ -279,6 +292,36 @@ def aspd_attn_branch_chunk(kv, state, step, q, workspace, out=None, lse=None, sm
 
 def aspd_attn_serial_decode(kv, state, step, q, workspace, out=None, lse=None, sm_scale=0.0, stream=None):
     return _attn("aspd_attn_serial_decode", kv, state, step, q, out, lse, sm_scale, workspace, stream)
+
+
+def aspd_sequence_plan_bytes(kv: KVCache, B: int, NQ: int) -> int:
+    kvs = kv.struct()
+    return int(lib().aspd_sequence_plan_bytes(C.byref(kvs), B, NQ))
+
+
+def aspd_build_sequence_meta(kv: KVCache, state: BatchState, cu_runs: torch.Tensor, run_branch: torch.Tensor,
+                             run_len: torch.Tensor, NQ: int, step: Step | None = None, stream=None,
+                             max_workgroups: int = 0) -> Step:
+    """See aspd.h: the metadata of every token of a batch of whole multi-stage sequences.  The three int32
+    device arrays describe the layout; `NQ` = sum of run_len, known to the caller."""
+    kvs, sts = kv.struct(), state.struct()
+    if step is None:
+        step = Step(NQ, 0, state.B, state.device, 0, max_workgroups)
+    need = aspd_sequence_plan_bytes(kv, state.B, step.NQ)
+    if step.plan is None or step.plan.numel() < need:
+        step.plan = torch.empty(max(need, 256), dtype=torch.uint8, device=state.device)
+    lay = aspd_layout(int(run_branch.numel()), _ptr(cu_runs), _ptr(run_branch), _ptr(run_len))
+    sps = step.struct()
+    rc = lib().aspd_build_sequence_meta(C.byref(kvs), C.byref(sts), C.byref(lay), state.pos_mode, C.byref(sps),
+                                        _stream(stream))
+    if rc != OK:
+        raise AspdError(rc, "aspd_build_sequence_meta")
+    step.plan_key = int(sps.plan_key)
+    return step
+
+
+def aspd_attn_full_sequence(kv, state, step, q, workspace, out=None, lse=None, sm_scale=0.0, stream=None):
+    return _attn("aspd_attn_full_sequence", kv, state, step, q, out, lse, sm_scale, workspace, stream)
 
 
 def aspd_attn_parallel_decode_static(kv, state, step, q, out, lse=None, sm_scale=0.0, stream=None):

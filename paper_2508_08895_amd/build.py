@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaspd.so")
-SOURCES = ["aspd_meta.hip", "aspd_plan.hip", "aspd_attn.hip", "aspd_rope.hip"]
+SOURCES = ["aspd_meta.hip", "aspd_seq_meta.hip", "aspd_plan.hip", "aspd_attn.hip", "aspd_rope.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

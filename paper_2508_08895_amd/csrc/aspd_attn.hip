@@ -73,6 +73,7 @@ struct AttnArgs {
   float          scale_log2;    // sm_scale * log2(e)
   int            G;             // query heads per KV head
   int            rows_cap;      // rows per row group the partial slots are sized for
+  const int32_t* row_base;      // whole-sequence launches: per packed row, the first slot of the row's stage
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -92,6 +93,7 @@ struct Seg {
 // page loads.
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ i32x16 load_words16(const int32_t* p /* 64-byte aligned, uniform */) {
   return *(const __attribute__((address_space(4))) i32x16*)(uintptr_t)p;
@@ -267,14 +269,29 @@ struct RowState {
   f32x4 acc[NT][D / 16];
   float m_run[NT], l_run[NT];
   int slot[NT], tag[NT];
+  int base[NT];  // first slot of the row's own stage (kernels whose rows may belong to different stages)
 };
+
+// Largest of eight scores in four instructions.  Written as assembly because fmaxf() makes the compiler
+// quiet a possible signalling NaN in every operand first (one more instruction each: 11 instead of 4
+// per tile of every pair); scores are MFMA results or -inf and never NaN here, and the three-operand
+// maximum returns a number whenever one operand is a number.
+__device__ __forceinline__ float max8(const float (&x)[8]) {
+  float r1, r2, r3, m;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r1) : "v"(x[0]), "v"(x[1]), "v"(x[2]));
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r2) : "v"(x[3]), "v"(x[4]), "v"(x[5]));
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r3) : "v"(x[6]), "v"(x[7]), "v"(r1));
+  asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(r2), "v"(r3));
+  return m;
+}
 
 // One pair of pages (32 keys) against NT 16-row tiles: scores, mask, running softmax, accumulation.
 // `stage` holds K page 0, K page 1, V page 0, V page 1 (padded rows), `qtile` the rows' Q (padded rows).
 // kr_even / kr_odd / vu are the lane's LDS bases (see the caller).  KB k-steps of K and VB d-tiles of
 // V are fetched from LDS at a time: large batches hide the LDS latency, small ones save registers.
 // QREG: the rows' Q operands come from registers (qr[n * KSTEPS + t]) instead of `qtile`.
-template <int D, int NT, int KB, int VB, bool QREG = false>
+// ROWBASE: every row brings the first slot of its own stage (ts.base) instead of the common `L`.
+template <int D, int NT, int KB, int VB, bool QREG = false, bool ROWBASE = false>
 __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qtile, RowState<D, NT>& ts,
                                              int kr_even, int kr_odd, const int (&vu)[4], int g, int L,
                                              int mask_from, int P0, bool second_valid, uint32_t own0,
@@ -344,12 +361,13 @@ __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qt
         for (int e = 0; e < 8; ++e) {
           const int jk = slot0 + (e & 3) + (e >> 2) * ASPD_BLOCK;
           const int own = (int)(((e < 4 ? own0 : own1) >> (8 * (e & 3))) & 0xff);
-          bool vis = (jk <= ts.slot[n]) && (jk < L || ts.tag[n] == 0 || own == ts.tag[n]);
+          const int stage_first = ROWBASE ? ts.base[n] : L;
+          bool vis = (jk <= ts.slot[n]) && (jk < stage_first || ts.tag[n] == 0 || own == ts.tag[n]);
           if (e >= 4 && !second_valid) vis = false;
           sc[e] = vis ? sc[e] : -INFINITY;
         }
       }
-      float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+      float mx = max8(sc);
       mx *= scale_log2;  // scale > 0: the maximum commutes with it
       if (__any(mx > ts.m_run[n] + LAZY)) {
         mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -856,7 +874,10 @@ size_t rows_smem_bytes() {
   return 2 * ROWS_PPS * Bf16Cfg<D>::STAGE_BYTES + (BLK_WIN + 4) * 4;
 }
 
-template <int D, int NT, int NW>
+// SEQ: the rows are tokens of a whole multi-stage sequence (aspd_attn_full_sequence): each brings the first
+// slot of its own stage (a.row_base) and its branch number within that stage; otherwise all rows belong to
+// the sequence's running stage, which starts at it.L.
+template <int D, int NT, int NW, bool SEQ = false>
 __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool complete, float* pslot) {
   using C = Bf16Cfg<D>;
   constexpr int ROWS = 16 * NT;        // rows per wave
@@ -872,7 +893,7 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
   const int c = lane & 15;
   const int g = lane >> 4;
   const int R = it.nq * a.G;                       // rows of the whole row group
-  const int page0 = it.page0, page1 = it.page1, L = it.L;
+  const int page0 = it.page0, page1 = it.page1;
   const int Rw = min(ROWS, R - wave * ROWS);       // rows this wave owns (<= 0: none)
   const bool wave_active = Rw > 0;
 
@@ -894,8 +915,13 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
   for (int k = 0; k < BPT; ++k) blkreg[k] = bt[min(page0 + tid + k * THREADS, page1 - 1)];
   RowState<D, NT> ts;
   bf16x8 qr[NT * C::KSTEPS];
-  int mask_from = L;
-  int tag_lo = 0x7fffffff, tag_hi = 0;  // range of branch tags among this wave's rows
+  // What the wave's rows have in common decides which pairs need a mask and which can be left out:
+  //   mask_from  every key below this slot is visible to every row (below every row's stage and slot);
+  //   slot_hi    no key above this slot is visible to any row;
+  //   base_hi    the latest stage start among the rows.  A row of an earlier stage lies below it, so keys
+  //              from base_hi on are visible, if at all, only to the rows of that latest stage, and only
+  //              where their branch tags match: [tag_lo, tag_hi] is the range of those rows' tags.
+  int mask_from = 0x7fffffff, slot_hi = 0, base_hi = 0;
 #pragma unroll
   for (int n = 0; n < NT; ++n) {
     const int rr = min(wave * ROWS + 16 * n + c, R - 1);  // padding rows (and idle waves) repeat the last row
@@ -906,10 +932,16 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
     for (int t = 0; t < C::KSTEPS; ++t) qr[n * C::KSTEPS + t] = __builtin_bit_cast(bf16x8, qsrc[4 * t]);
     ts.slot[n] = a.logical_slot[q];
     const int qb = a.q_branch[q];
-    ts.tag[n] = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
-    mask_from = min(mask_from, ts.slot[n]);
-    tag_lo = min(tag_lo, ts.tag[n]);
-    tag_hi = max(tag_hi, ts.tag[n]);
+    if (SEQ) {
+      ts.tag[n] = max(qb, -1) + 1;
+      ts.base[n] = a.row_base[q];
+    } else {
+      ts.tag[n] = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
+      ts.base[n] = it.L;
+    }
+    mask_from = min(mask_from, min(ts.slot[n], ts.base[n]));
+    slot_hi = max(slot_hi, ts.slot[n]);
+    base_hi = max(base_hi, ts.base[n]);
     ts.m_run[n] = -INFINITY;
     ts.l_run[n] = 0.f;
 #pragma unroll
@@ -922,10 +954,25 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     mask_from = min(mask_from, __shfl_xor(mask_from, off));
+    slot_hi = max(slot_hi, __shfl_xor(slot_hi, off));
+    base_hi = max(base_hi, __shfl_xor(base_hi, off));
+  }
+  mask_from = __builtin_amdgcn_readfirstlane(mask_from);
+  slot_hi = __builtin_amdgcn_readfirstlane(slot_hi);
+  base_hi = __builtin_amdgcn_readfirstlane(base_hi);
+  int tag_lo = 0x7fffffff, tag_hi = 0;
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+    if (ts.base[n] == base_hi) {
+      tag_lo = min(tag_lo, ts.tag[n]);
+      tag_hi = max(tag_hi, ts.tag[n]);
+    }
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
     tag_lo = min(tag_lo, __shfl_xor(tag_lo, off));
     tag_hi = max(tag_hi, __shfl_xor(tag_hi, off));
   }
-  mask_from = __builtin_amdgcn_readfirstlane(mask_from);
   tag_lo = __builtin_amdgcn_readfirstlane(tag_lo);
   tag_hi = __builtin_amdgcn_readfirstlane(tag_hi);
 
@@ -1023,13 +1070,16 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
       for (int h = 0; h < PPS; ++h) {
         const int P0 = wbase + 2 * (gi * PPS + h);
         if (P0 >= wend) break;
+        // keys past the last of this wave's rows (whole sequences only: the rows of a decode or chunk step
+        // sit at the tail of their sequence, and the test costs the chunk launch 3 %)
+        if (SEQ && P0 * ASPD_BLOCK > slot_hi) continue;
         const bool second_valid = (P0 + 1) < wend;
         uint32_t own0 = 0, own1 = 0;
         if (owner_row && (P0 + 2) * ASPD_BLOCK > mask_from) {
           own0 = lane_tags(tc[h][0], g);
           own1 = lane_tags(tc[h][1], g);
-          // pairs wholly inside the branch region: skip if no key belongs to a branch of this wave's rows
-          if (P0 * ASPD_BLOCK >= L && tag_lo > 0) {
+          // pairs wholly inside the latest stage: skip if no key belongs to a branch of this wave's rows there
+          if (P0 * ASPD_BLOCK >= base_hi && tag_lo > 0) {
             bool mine = false;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -1041,8 +1091,8 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
         }
         constexpr int KB = 2;
         constexpr int VB = 4;
-        pair_compute<D, NT, KB, VB, true>(stage + h * 4 * C::LPAGE_U4, nullptr, ts, kr_even, kr_odd, vu, g, L, mask_from,
-                                          P0, second_valid, own0, own1, a.scale_log2, qr);
+        pair_compute<D, NT, KB, VB, true, true>(stage + h * 4 * C::LPAGE_U4, nullptr, ts, kr_even, kr_odd, vu, g, 0,
+                                                mask_from, P0, second_valid, own0, own1, a.scale_log2, qr);
       }
     }
     }
@@ -1097,6 +1147,57 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4,
     float* pslot = partial_slot(a, blockIdx.x, seg.page0 == 0 ? 1 : 0, D);
     segment_rows<D, NT, NW>(a, smem, seg, complete, pslot);
     if (!complete) announce_partial<D, true, THREADS, 2>(a, seg, &merge_flag);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Whole sequences (teacher forcing, re-prefill): every token of the batch is a query row.  The row
+// groups (qpg consecutive tokens of a sequence, one KV head) are listed in the step's plan, longest key
+// range first; workgroups take them from the list as they become free (the ranges differ by two orders
+// of magnitude, so no static split would balance), through one counter in the workspace that the last
+// workgroup to finish puts back to zero.  Every group is computed whole by one workgroup with the
+// row-splitting arithmetic above: nothing is split, nothing merged.
+// ---------------------------------------------------------------------------------------------
+template <int D, int NT, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void attn_bf16_seq_kernel(
+    AttnArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ int next_item;
+  const int n_groups = a.plan[0];
+  const int32_t* items = a.plan + SEQ_PLAN_HDR + ((a.NQ + 3) & ~3);
+  const int Hkv = a.kv.num_kv_heads;
+  const long total = (long)n_groups * Hkv;
+  for (;;) {
+    if (threadIdx.x == 0) next_item = atomicAdd(a.counters, 1);
+    __syncthreads();
+    const int e = next_item;
+    __syncthreads();  // everyone has read it before the next round overwrites it
+    if (e >= total) break;
+    const i32x4 w = *(const i32x4*)(items + 4 * (e / Hkv));
+    Seg seg;
+    seg.s = w[0];
+    seg.h = e % Hkv;
+    seg.q0 = w[1];
+    seg.nq = w[2];
+    seg.page0 = 0;
+    seg.page1 = seg.np = w[3];
+    seg.owner = seg.w_last = 0;
+    seg.L = 0;
+    // the list is the library's own; the check keeps a workgroup that is handed anything else inside the
+    // call's arrays
+    const bool ok = (int)(seg.s >= 0) & (int)(seg.s < a.B) & (int)(seg.q0 >= 0) & (int)(seg.nq >= 1) &
+                    (int)(seg.nq <= a.qpg) & (int)(seg.q0 <= a.NQ - seg.nq) & (int)(seg.np >= 1) &
+                    (int)(seg.np <= a.kv.max_blocks_per_seq);
+    if (!ok) continue;
+    segment_rows<D, NT, NW, true>(a, smem, seg, true, nullptr);
+  }
+  // the last workgroup to leave puts the two counters back to zero for the next launch
+  if (threadIdx.x == 0) {
+    const int gone = atomicAdd(a.counters + 1, 1);
+    if (gone == (int)gridDim.x - 1) {
+      atomicExch(a.counters, 0);
+      atomicExch(a.counters + 1, 0);
+    }
   }
 }
 
@@ -1479,6 +1580,7 @@ int attn_launch(Mode mode, const aspd_kv* kv, const aspd_state* state, const asp
   a.counters = (int*)workspace_d;
   a.partial = (float*)((char*)workspace_d + COUNTER_BYTES + plan_area_bytes(plan_words));
   a.plan = plan;
+  a.row_base = nullptr;
   a.NQ = step->NQ;
   a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)kv->head_dim) : sm_scale) * LOG2E;
   a.B = state->B;
@@ -1632,6 +1734,72 @@ extern "C" int aspd_attn_serial_decode(const aspd_kv* kv, const aspd_state* stat
                                        void* workspace_d, size_t workspace_bytes, void* stream) {
   return attn_launch(MODE_SERIAL, kv, state, step, q_d, out_d, lse_d, sm_scale, workspace_d, workspace_bytes,
                      stream);
+}
+
+extern "C" int aspd_attn_full_sequence(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
+                                       const void* q_d, void* out_d, float* lse_d, float sm_scale,
+                                       void* workspace_d, size_t workspace_bytes, void* stream) {
+  int rc = aspd_check_kv(kv);
+  if (rc != ASPD_OK) return rc;
+  if (!state || !step || state->B <= 0) return ASPD_ERR_INVALID_ARG;
+  if (state->B > ASPD_MAX_BATCH) return ASPD_ERR_UNSUPPORTED;
+  const int G = kv->num_q_heads / kv->num_kv_heads;
+  const int qpg = aspd_sequence_qpg(G);
+  if (kv->dtype != ASPD_BF16 || qpg < 1) return ASPD_ERR_UNSUPPORTED;
+  if (step->NQ < 0) return ASPD_ERR_INVALID_ARG;
+  if (step->NQ == 0) return ASPD_OK;
+  if (!step->plan_d || step->plan_key != aspd_sequence_plan_key(qpg, state->B) ||
+      step->plan_bytes < aspd_sequence_plan_words(kv, state->B, step->NQ) * sizeof(int32_t))
+    return ASPD_ERR_INVALID_ARG;  // not a step of aspd_build_sequence_meta
+  if (!step->q_branch_d || !step->logical_slot_d || !q_d || !out_d) return ASPD_ERR_INVALID_ARG;
+  if (((uintptr_t)q_d & 15) || ((uintptr_t)out_d & 15)) return ASPD_ERR_INVALID_ARG;
+  if (!(sm_scale >= 0.f)) return ASPD_ERR_INVALID_ARG;
+  if (!state->slot_owner_d || state->owner_stride < kv->max_blocks_per_seq * ASPD_BLOCK || (state->owner_stride & 3) ||
+      ((uintptr_t)state->slot_owner_d & 3))
+    return ASPD_ERR_INVALID_ARG;
+  if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
+  if (workspace_bytes < (size_t)COUNTER_BYTES) return ASPD_ERR_WORKSPACE;
+  if (step->max_workgroups < 0) return ASPD_ERR_INVALID_ARG;
+
+  AttnArgs a;
+  a.kv = make_view(kv);
+  a.cu_branches = nullptr;
+  a.slot_owner = state->slot_owner_d;
+  a.owner_stride = state->owner_stride;
+  a.q_branch = step->q_branch_d;
+  a.logical_slot = step->logical_slot_d;
+  a.q = q_d;
+  a.out = out_d;
+  a.lse = lse_d;
+  a.counters = (int*)workspace_d;
+  a.partial = nullptr;
+  a.plan = step->plan_d;
+  a.row_base = step->plan_d + SEQ_PLAN_HDR;
+  a.NQ = step->NQ;
+  a.scale_log2 = (sm_scale == 0.f ? 1.0f / sqrtf((float)kv->head_dim) : sm_scale) * LOG2E;
+  a.B = state->B;
+  a.G = G;
+  a.qpg = qpg;
+  a.rows_cap = ROWS_NW * 16 * ROWS_NT;
+  // one workgroup per compute unit, never more than there are row groups to take
+  long nwg = aspd_device_cu_count();
+  nwg = std::min(nwg, ((long)state->B + step->NQ / qpg) * kv->num_kv_heads);
+  if (step->max_workgroups > 0) nwg = std::min(nwg, (long)step->max_workgroups);
+  a.nwg = (int)std::max(1L, nwg);
+  hipStream_t hs = (hipStream_t)stream;
+  if (kv->head_dim == 128) {
+    rc = allow_big_lds((const void*)attn_bf16_seq_kernel<128, ROWS_NT, ROWS_NW>);
+    if (rc != ASPD_OK) return rc;
+    hipLaunchKernelGGL((attn_bf16_seq_kernel<128, ROWS_NT, ROWS_NW>), dim3(a.nwg), dim3(ROWS_NW * 64),
+                       (rows_smem_bytes<128, ROWS_NT, ROWS_NW>()), hs, a);
+  } else {
+    rc = allow_big_lds((const void*)attn_bf16_seq_kernel<64, ROWS_NT, ROWS_NW>);
+    if (rc != ASPD_OK) return rc;
+    hipLaunchKernelGGL((attn_bf16_seq_kernel<64, ROWS_NT, ROWS_NW>), dim3(a.nwg), dim3(ROWS_NW * 64),
+                       (rows_smem_bytes<64, ROWS_NT, ROWS_NW>()), hs, a);
+  }
+  ASPD_HIP_CHECK(hipGetLastError());
+  return ASPD_OK;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -73,5 +73,21 @@ size_t aspd_plan_words(const aspd_kv* kv, const AttnVariant& v, int32_t B, int32
 int aspd_plan_launch(const aspd_kv* kv, const AttnVariant& v, int32_t B, const int32_t* stage_base_d,
                      const int32_t* seq_len_d, const int32_t* cu_seq_new_d, int32_t* plan_d, hipStream_t stream);
 
+// ---- The plan of a whole-sequence step (aspd_build_sequence_meta / aspd_attn_full_sequence) -------
+// Layout (32-bit words):
+//   [0, 16)                 header: 0 row groups in the list, 1 tokens per row group, 2 NQ, 3 B
+//   [16, 16 + NQ4)          per packed row, the first slot of the row's own stage (its own slot for a
+//                           main-branch row); NQ4 = NQ rounded up to a multiple of 4
+//   then 4 words per row group, in the order workgroups take them: sequence, first packed row,
+//                           tokens, pages of its key range
+constexpr int SEQ_PLAN_HDR = 16;
+// Tokens per row group: what the row-splitting kernel holds per workgroup.
+static inline int aspd_sequence_qpg(int G) { return ROWS_NW * 16 * ROWS_NT / G; }
+// Identifies such a plan; no value aspd_plan_key returns has bit 62 set.
+static inline uint64_t aspd_sequence_plan_key(int qpg, int32_t B) {
+  return ((uint64_t)1 << 62) | ((uint64_t)qpg << 16) | (uint64_t)B;
+}
+size_t aspd_sequence_plan_words(const aspd_kv* kv, int32_t B, int32_t NQ);
+
 // Compute units of the current device (256 when there is none to ask, as on a build host).
 int aspd_device_cu_count();
