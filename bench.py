@@ -513,8 +513,8 @@ def cpu_baseline(wl, base_len, chunk, np):
         meta = tt.append_parallel(ones)
         q = wl.draw_q(meta.NQ)
         rows = None
-        if meta.NQ > 128:  # bound the work: a seeded sample of the rows
-            rows = np.sort(np.random.default_rng(1 + steps).choice(meta.NQ, size=128, replace=False))
+        if meta.NQ > 192:  # bound the work: a seeded sample of the rows
+            rows = np.sort(np.random.default_rng(1 + steps).choice(meta.NQ, size=192, replace=False))
         attention_c.attend_c(tt, meta, q, wl.k_cache, wl.v_cache, rows=rows)
         done += meta.NQ if rows is None else len(rows)
         total += meta.NQ

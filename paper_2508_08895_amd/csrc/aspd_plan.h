@@ -40,7 +40,11 @@ constexpr int ROWS_NT = 2;           // 16-row tiles per wave there
 constexpr int MAX_WG_ROWS = 256;     // its largest grid
 constexpr int MIN_PAGES_PER_WG = 16; // key ranges are not split finer than this
 constexpr int PAD_STREAM = 32;       // fixed cost of a segment in pages, bandwidth-bound kernel at head_dim 128
-constexpr int PAD_COMPUTE = 8;       // the same for the compute-bound kernels
+constexpr int PAD_COMPUTE = 8;       // the same for the fp32 kernel
+constexpr int PAD_ROWS = 32;         // and for the row-splitting kernel: a segment there costs about 17 us (Q operands
+                                     // of 256 rows into registers, 64-128 KB of output or partial, its share of a
+                                     // merge), 25-40 pages' worth; measured on a 64-sequence chunk step: 8 -> 828 us,
+                                     // 16 -> 818, 24 -> 809, 32 -> 804, 48 -> 822, 64 -> 827
 
 enum AttnKernel { KERNEL_F32 = 0, KERNEL_BF16_STREAM = 1, KERNEL_BF16_ROWS = 2 };
 

@@ -471,7 +471,8 @@ int aspd_choose_variant(const aspd_kv* kv, int32_t B, int32_t NQ, int32_t max_ne
   v->qpg = v->rows_cap / G;
   // A segment's fixed cost (start-up, reduction across waves, partial, merge) in units of the time one
   // more page takes its workgroup.
-  v->pad = v->kernel == KERNEL_BF16_STREAM ? PAD_STREAM * 128 / kv->head_dim : PAD_COMPUTE;
+  v->pad = v->kernel == KERNEL_BF16_STREAM ? PAD_STREAM * 128 / kv->head_dim
+           : (v->kernel == KERNEL_BF16_ROWS ? PAD_ROWS : PAD_COMPUTE);
   // Grid: as many workgroups as stay resident at once (one per compute unit: every kernel here needs more
   // than half of a compute unit's LDS or registers), never more than the pages can feed, never more than
   // the caller allows.
