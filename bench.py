@@ -297,7 +297,7 @@ def measure(name, args, timed, mods):
             entry["hbm_traffic_MB_counters"] = round(tr / 1e6, 1)
         per_call[kind] = entry
 
-    if args.extras:
+    if args.extras or (name == HEADLINE and args.workload == "all"):
         extras(name, args, mods, locals(), per_call)
     result["per_call"] = per_call
     result["_wl"] = (wl, base_len, C)
@@ -403,7 +403,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV pools to rotate through (0 = enough for 1.5 GB)")
     ap.add_argument("--no-graph", action="store_true", help="launch every call from Python instead of replaying a HIP graph")
-    ap.add_argument("--extras", action="store_true", help="also time the rotary append and a mixed step")
+    ap.add_argument("--extras", action="store_true", help="also time the rotary append, a mixed step and the whole-sequence call (the default run does so for the headline workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is one-GPU only (the path shards by sequence or KV head without "

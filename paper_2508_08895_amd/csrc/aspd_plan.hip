@@ -480,7 +480,9 @@ int aspd_choose_variant(const aspd_kv* kv, int32_t B, int32_t NQ, int32_t max_ne
   if (v->kernel == KERNEL_BF16_ROWS) nwg = std::min(nwg, (long)MAX_WG_ROWS);
   const long groups_max = (long)B + NQ / v->qpg;
   const long units_max = groups_max * kv->num_kv_heads * kv->max_blocks_per_seq;
-  nwg = std::min(nwg, (units_max + MIN_PAGES_PER_WG - 1) / MIN_PAGES_PER_WG);
+  // (... but a workgroup per item when the items are few: four items of six pages each are done sooner by
+  // four workgroups than by two that take them in turn)
+  nwg = std::min(nwg, std::max((units_max + MIN_PAGES_PER_WG - 1) / MIN_PAGES_PER_WG, groups_max * kv->num_kv_heads));
   if (max_workgroups > 0) nwg = std::min(nwg, (long)max_workgroups);
   v->nwg = (int)std::max(1L, std::min(nwg, (long)MAX_WG));
   v->stream_once = max_new_per_seq > 0 && max_new_per_seq <= v->qpg;

@@ -305,3 +305,65 @@ def test_argument_checks(A):
     with pytest.raises(A.AspdError) as e:
         _build(A, gf, [[(0, 5)], [(0, 6)]])
     assert e.value.code in (A.ERR_UNSUPPORTED, A.ERR_INVALID_ARG)
+
+
+def test_edge_layouts(A):
+    """A sequence without runs, one of empty runs only, a stage of one branch, a stage whose first branches are
+    empty, two stages back to back, a sequence that starts and ends inside stages; grid capped to 3 workgroups."""
+    from gpu_drive import GpuBatch
+    wl = W.random_small(seed=5800, batch=6, num_q_heads=16, num_kv_heads=2, head_dim=64, prefix_range=(150, 200),
+                        branches_range=(2, 3), branch_len_range=(20, 40))
+    layouts = [[],
+               [(0, 0), (1, 0), (2, 0), (0, 0)],
+               [(0, 70), (1, 90), (0, 33)],
+               [(0, 17), (1, 0), (2, 0), (3, 65), (0, 40)],
+               [(0, 31), (1, 40), (2, 45), (1, 38), (2, 1), (3, 50), (0, 5)],
+               [(1, 80), (2, 77), (0, 20), (1, 33), (2, 60)]]
+    tt, meta = replay_layout(wl.block_tables, wl.block_size, layouts)
+    gb = GpuBatch(wl)
+    cu, br, ln = _layout_arrays(layouts)
+    step = A.aspd_build_sequence_meta(gb.kv, gb.state, gb._dev_i32(cu), gb._dev_i32(br), gb._dev_i32(ln), NQ=int(ln.sum()),
+                                      max_workgroups=3)
+    torch.cuda.synchronize()
+    _check_meta(A, gb, wl, step, tt, meta, layouts)
+    _check_attention(A, gb, wl, step, tt, meta, label="edge layouts, 3 workgroups")
+
+
+def test_whole_sequence_call_in_a_hip_graph(A):
+    """Metadata and attention of whole sequences captured in a HIP graph and replayed with eager launches on the same
+    workspace in between: the work counter the launch takes its row groups from is back at zero after every launch,
+    captured or not, and every replay gives the eager result bit for bit."""
+    from gpu_drive import GpuBatch
+    wl = W.random_small(seed=5900, batch=3, prefix_range=(300, 700), branches_range=(2, 5), branch_len_range=(20, 80))
+    layouts = W.random_layouts(wl, seed=4, fill=0.95)
+    tt, meta = replay_layout(wl.block_tables, wl.block_size, layouts)
+    gb = GpuBatch(wl)
+    cu, br, ln = (gb._dev_i32(x) for x in _layout_arrays(layouts))
+    step = A.aspd_build_sequence_meta(gb.kv, gb.state, cu, br, ln, NQ=meta.NQ)
+    q = wl.draw_q(meta.NQ)
+    qd = q.to(gb.dev)
+    eager = A.aspd_attn_full_sequence(gb.kv, gb.state, step, qd, gb.workspace).clone()
+    torch.cuda.synchronize()
+    ref, _ = attend(tt, meta, q, wl.k_cache, wl.v_cache)
+    assert np.abs(eager.float().cpu().numpy() - ref).max() <= TOL
+    out = torch.empty_like(qd)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        A.aspd_build_sequence_meta(gb.kv, gb.state, cu, br, ln, NQ=meta.NQ, step=step)   # warm-up on the side stream
+        A.aspd_attn_full_sequence(gb.kv, gb.state, step, qd, gb.workspace, out=out)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        A.aspd_build_sequence_meta(gb.kv, gb.state, cu, br, ln, NQ=meta.NQ, step=step)
+        A.aspd_attn_full_sequence(gb.kv, gb.state, step, qd, gb.workspace, out=out)
+    for i in range(4):
+        out.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), i
+        again = A.aspd_attn_full_sequence(gb.kv, gb.state, step, qd, gb.workspace)      # eager, same workspace
+        torch.cuda.synchronize()
+        assert torch.equal(again, eager), i
+    assert gb.fault() == 0
