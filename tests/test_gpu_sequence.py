@@ -367,3 +367,27 @@ def test_whole_sequence_call_in_a_hip_graph(A):
         torch.cuda.synchronize()
         assert torch.equal(again, eager), i
     assert gb.fault() == 0
+
+
+def test_seeded_sweep_of_layouts(A):
+    """Sixteen random batches (head layouts, head sizes, batch sizes, stage counts, position paradigms drawn per
+    seed), metadata bit-exact and every row of the attention output against the oracle."""
+    from gpu_drive import GpuBatch
+    heads = [(32, 8, 128), (8, 8, 64), (16, 2, 128), (4, 1, 64), (12, 4, 128), (32, 4, 64)]
+    for seed in range(16):
+        rng = np.random.default_rng(9000 + seed)
+        hq, hkv, d = heads[int(rng.integers(len(heads)))]
+        wl = W.random_small(seed=6000 + seed, num_q_heads=hq, num_kv_heads=hkv, head_dim=d, batch=int(rng.integers(1, 7)),
+                            prefix_range=(0, int(rng.integers(20, 500))), branches_range=(1, int(rng.integers(2, 9))),
+                            branch_len_range=(1, int(rng.integers(5, 90))))
+        layouts = W.random_layouts(wl, seed=seed, max_stages=int(rng.integers(1, 5)), max_branches=int(rng.integers(1, 12)),
+                                   fill=float(rng.uniform(0.3, 1.0)))
+        longest = max([n for r in layouts for b, n in r if b > 0] + [1])
+        pm, pm_gpu = [("same_seq", A.POS_SAME_SEQ), ("same_max", A.POS_SAME_MAX),
+                      (("fix", longest), A.POS_FIX_N(longest))][seed % 3]
+        tt, meta = replay_layout(wl.block_tables, wl.block_size, layouts, pm)
+        gb = GpuBatch(wl)
+        step = _build(A, gb, layouts, pos_mode=pm_gpu)
+        _check_meta(A, gb, wl, step, tt, meta, layouts)
+        if meta.NQ:
+            _check_attention(A, gb, wl, step, tt, meta, label=f"sweep {seed}: {hq}/{hkv}/{d} B={wl.B} {pm}")
