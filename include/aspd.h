@@ -299,7 +299,9 @@ ASPD_API int aspd_build_sequence_meta(const aspd_kv* kv, aspd_state* state, cons
  * aspd_build_sequence_meta (anything else: ASPD_ERR_INVALID_ARG); the K and V rows of all its tokens are in
  * the cache (aspd_rope_append with the same step writes them).  bf16 only (ASPD_ERR_UNSUPPORTED for fp32).
  * Key pages beyond a row group's last slot are never read, and a wave skips the pages of a stage that hold
- * only sibling branches of its rows.  Other arguments as aspd_attn_parallel_decode; the workspace needs
+ * only sibling branches of its rows.  With step->shared_mask = 1 every row attends every slot up to and including its
+ * own (plain causal attention over the sequence: the "Shared" mask of Sec. 4.5.2, and what a re-prefill of a
+ * sequence without parallel stages computes).  Other arguments as aspd_attn_parallel_decode; the workspace needs
  * aspd_workspace_bytes(kv, B, NQ) like any other call (only its counters are used). */
 ASPD_API int aspd_attn_full_sequence(const aspd_kv* kv, const aspd_state* state, const aspd_step* step,
                                      const void* q_d, void* out_d, float* lse_d, float sm_scale,

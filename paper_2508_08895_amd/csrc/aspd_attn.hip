@@ -933,8 +933,9 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
     ts.slot[n] = a.logical_slot[q];
     const int qb = a.q_branch[q];
     if (SEQ) {
-      ts.tag[n] = max(qb, -1) + 1;
-      ts.base[n] = a.row_base[q];
+      // (no owner tags: the shared mask, every row is treated like a main-branch row)
+      ts.tag[n] = a.slot_owner ? max(qb, -1) + 1 : 0;
+      ts.base[n] = a.slot_owner ? a.row_base[q] : ts.slot[n];
     } else {
       ts.tag[n] = (qb < 0 || !a.cu_branches) ? 0 : qb - a.cu_branches[it.s] + 1;
       ts.base[n] = it.L;
@@ -1754,8 +1755,9 @@ extern "C" int aspd_attn_full_sequence(const aspd_kv* kv, const aspd_state* stat
   if (!step->q_branch_d || !step->logical_slot_d || !q_d || !out_d) return ASPD_ERR_INVALID_ARG;
   if (((uintptr_t)q_d & 15) || ((uintptr_t)out_d & 15)) return ASPD_ERR_INVALID_ARG;
   if (!(sm_scale >= 0.f)) return ASPD_ERR_INVALID_ARG;
-  if (!state->slot_owner_d || state->owner_stride < kv->max_blocks_per_seq * ASPD_BLOCK || (state->owner_stride & 3) ||
-      ((uintptr_t)state->slot_owner_d & 3))
+  const bool branches = step->shared_mask == 0;
+  if (branches && (!state->slot_owner_d || state->owner_stride < kv->max_blocks_per_seq * ASPD_BLOCK ||
+                   (state->owner_stride & 3) || ((uintptr_t)state->slot_owner_d & 3)))
     return ASPD_ERR_INVALID_ARG;
   if (!workspace_d || ((uintptr_t)workspace_d & 255)) return ASPD_ERR_INVALID_ARG;
   if (workspace_bytes < (size_t)COUNTER_BYTES) return ASPD_ERR_WORKSPACE;
@@ -1764,8 +1766,8 @@ extern "C" int aspd_attn_full_sequence(const aspd_kv* kv, const aspd_state* stat
   AttnArgs a;
   a.kv = make_view(kv);
   a.cu_branches = nullptr;
-  a.slot_owner = state->slot_owner_d;
-  a.owner_stride = state->owner_stride;
+  a.slot_owner = branches ? state->slot_owner_d : nullptr;
+  a.owner_stride = branches ? state->owner_stride : 0;
   a.q_branch = step->q_branch_d;
   a.logical_slot = step->logical_slot_d;
   a.q = q_d;

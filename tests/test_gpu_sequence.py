@@ -391,3 +391,34 @@ def test_seeded_sweep_of_layouts(A):
         _check_meta(A, gb, wl, step, tt, meta, layouts)
         if meta.NQ:
             _check_attention(A, gb, wl, step, tt, meta, label=f"sweep {seed}: {hq}/{hkv}/{d} B={wl.B} {pm}")
+
+
+def test_shared_mask_is_plain_causal_attention(A):
+    """shared_mask = 1: every row sees every slot up to its own, siblings included; against the oracle's shared
+    mask and, for one head, against torch's causal attention."""
+    from gpu_drive import GpuBatch
+    wl = W.random_small(seed=6100, batch=3, prefix_range=(100, 300), branches_range=(2, 5), branch_len_range=(10, 60))
+    layouts = W.random_layouts(wl, seed=8, fill=0.9)
+    tt, meta = replay_layout(wl.block_tables, wl.block_size, layouts)
+    gb = GpuBatch(wl)
+    step = _build(A, gb, layouts)
+    step.shared_mask = 1
+    q = wl.draw_q(meta.NQ)
+    out = A.aspd_attn_full_sequence(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace)
+    torch.cuda.synchronize()
+    ref, _ = attend(tt, meta, q, wl.k_cache, wl.v_cache, shared_mask=True)
+    got = out.float().cpu().numpy()
+    assert np.abs(got - ref).max() <= TOL
+    s, h = 1, 5
+    r0, r1 = int(meta.cu_seq_new[s]), int(meta.cu_seq_new[s + 1])
+    phys = torch.from_numpy(tt.physical_slots(s))
+    k = wl.k_cache[phys // 16, h // 4, phys % 16].double()
+    v = wl.v_cache[phys // 16, h // 4, phys % 16].double()
+    sd = torch.nn.functional.scaled_dot_product_attention(q[r0:r1, h].double()[None], k[None], v[None], is_causal=True)[0]
+    assert np.abs(got[r0:r1, h] - sd.numpy()).max() <= TOL
+    # and the branch-isolating mask gives something else for the same rows
+    step.shared_mask = 0
+    iso = A.aspd_attn_full_sequence(gb.kv, gb.state, step, q.to(gb.dev), gb.workspace).float().cpu().numpy()
+    ref_iso, _ = attend(tt, meta, q, wl.k_cache, wl.v_cache)
+    assert np.abs(iso - ref_iso).max() <= TOL
+    assert np.abs(iso - got).max() > 0.05
