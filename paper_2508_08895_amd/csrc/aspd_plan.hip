@@ -50,7 +50,7 @@ __device__ __forceinline__ Sched sched_at(int* base, int B) {
   sc.wgb = sc.q0 + (B + 1);
   return sc;
 }
-constexpr int sched_ints(int B) { return 4 * B + 2 + MAX_WG + 1; }
+constexpr int sched_ints(int B) { return (4 * B + 2 + MAX_WG + 1 + 3) & ~3; }  // (what follows stays 16-byte aligned)
 
 __device__ __forceinline__ int pages_of(const PlanArgs& a, const Sched& sc, int s) {
   return min((sc.T[s] + ASPD_BLOCK - 1) / ASPD_BLOCK, a.max_blocks_per_seq);
@@ -83,8 +83,18 @@ struct Shares {
 };
 
 // The item that holds unit `u`, and the unit's index within it (padding first, then the pages).
-__device__ Item locate(const PlanArgs& a, const Sched& sc, int pad, int u, int* vpage) {
+// `hint`: a sequence at or before the one that holds u, or -1 (a walk moves forward: the item it was at).
+__device__ Item locate(const PlanArgs& a, const Sched& sc, int pad, int u, int* vpage, int hint = -1) {
   int lo = 0, hi = a.B - 1;  // the last sequence that starts at or before u
+  if (hint >= 0) {
+    // the same sequence or one of the next two, else search from there on
+    lo = hint;
+#pragma unroll
+    for (int d = 0; d < 3; ++d) {
+      if (lo < hi && sc.cu_units[lo + 1] <= u) ++lo; else hi = lo;
+    }
+    if (lo < a.B - 1 && sc.cu_units[lo + 1] <= u) hi = a.B - 1;  // further on: bisect the rest
+  }
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
     if (sc.cu_units[mid] <= u) lo = mid; else hi = mid - 1;
@@ -164,6 +174,9 @@ __device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratc
         mine_p[j] = np * mine_i[j];
         longest = max(longest, np);
       }
+      // (for the search below; both tables are filled in for good later)
+      sc.cu_units[s] = mine_i[j];
+      sc.wgb[s] = mine_i[j] > 0 ? np : 0;
     }
     sum_p += mine_p[j];
     sum_i += mine_i[j];
@@ -213,12 +226,21 @@ __device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratc
     const int span = max(longest - MIN_PAGES_PER_WG, 0);
     const int step = span / PLAN_THREADS + 1;
     const int p = min(max(longest, 1), MIN_PAGES_PER_WG + tid * step);
+    // pieces of all items at this length: ceil(np / p) by a float reciprocal, made exact by one correction
+    // (np + p < 2^24, the estimate is off by one at most)
+    const float rp = __builtin_amdgcn_rcpf((float)p);
     long need = 0;
     for (int s = 0; s < a.B; ++s) {
-      const int np = pages_of(a, sc, s);
-      if (np > 0) need += (long)groups_of(a, sc, s) * a.num_kv_heads * ((np + p - 1) / p);
+      const int x = sc.wgb[s] + p - 1;
+      int q = (int)((float)x * rp);
+      if ((q + 1) * p <= x) ++q;
+      else if (q * p > x) --q;
+      need += (long)sc.cu_units[s] * q;
     }
-    if (need <= a.nwg) atomicMin(best, p);
+    int mine = need <= a.nwg ? p : 0x7fffffff;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mine = min(mine, __shfl_xor(mine, off));
+    if ((tid & 63) == 0 && mine != 0x7fffffff) atomicMin(best, mine);
   }
   __syncthreads();
   if (best[0] != 0x7fffffff) {
@@ -287,6 +309,15 @@ __device__ Shares build_schedule(const PlanArgs& a, const Sched& sc, int* scratc
 
 // RAGGED: the workgroup whose share holds unit u.
 __device__ int share_owner(const Sched& sc, const Shares& sh, int u) {
+  // boundaries sit within a padding's length of w * share: try the nominal owner and its neighbours first
+  {
+    const int g = min(sh.n - 1, max(0, (int)((float)u / (float)sh.share)));
+#pragma unroll
+    for (int d = -1; d <= 1; ++d) {
+      const int w = g + d;
+      if (w >= 0 && w < sh.n && sc.wgb[w] <= u && (w == sh.n - 1 || sc.wgb[w + 1] > u)) return w;
+    }
+  }
   int lo = 0, hi = sh.n - 1;  // last w with wgb[w] <= u
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
@@ -326,11 +357,12 @@ __device__ bool even_share(const PlanArgs& a, const Sched& sc, const Shares& sh,
 }
 
 // Ragged regime: the next run of real pages in [*u, end), or false at the end.
-__device__ bool next_segment(const PlanArgs& a, const Sched& sc, const Shares& sh, int* u, int end, Item* it,
-                             int* page0, int* page1) {
+__device__ bool next_segment(const PlanArgs& a, const Sched& sc, const Shares& sh, int* u, int end, int* s_hint,
+                             Item* it, int* page0, int* page1) {
   while (*u < end) {
     int v0;
-    *it = locate(a, sc, sh.pad, *u, &v0);
+    *it = locate(a, sc, sh.pad, *u, &v0, *s_hint);
+    *s_hint = it->s;
     const int v1 = min(it->np + sh.pad, v0 + (end - *u));
     *u += v1 - v0;
     *page0 = max(0, v0 - sh.pad);
@@ -344,11 +376,13 @@ __device__ bool next_segment(const PlanArgs& a, const Sched& sc, const Shares& s
 // workgroup that hold a part of its item.
 struct Walk {
   int u, end;
+  int s_hint;  // sequence of the item the walk was at last (-1: none yet)
   bool even_pending;
 };
 __device__ __forceinline__ Walk walk_begin(const Sched& sc, const Shares& sh, int w) {
   Walk wk;
   wk.u = wk.end = 0;
+  wk.s_hint = -1;
   wk.even_pending = sh.even && w < sh.n;
   if (!sh.even && w < sh.n) {
     wk.u = sc.wgb[w];
@@ -363,29 +397,47 @@ __device__ __forceinline__ bool walk_next(const PlanArgs& a, const Sched& sc, co
     wk->even_pending = false;
     return even_share(a, sc, sh, w, it, page0, page1, owner, w_last);
   }
-  if (!next_segment(a, sc, sh, &wk->u, wk->end, it, page0, page1)) return false;
+  if (!next_segment(a, sc, sh, &wk->u, wk->end, &wk->s_hint, it, page0, page1)) return false;
   *owner = *page0 == 0 ? w : share_owner(sc, sh, it->first_unit + sh.pad);
   *w_last = *page1 == it->np ? w : share_owner(sc, sh, it->first_unit + sh.pad + it->np - 1);
   return true;
 }
+
+// Segments of a workgroup that pass 1 keeps in LDS for pass 2 (8 words each); a workgroup with more is walked
+// on from where pass 1 stood when the room ran out.
+__host__ __device__ constexpr int plan_cached_segments(int nwg) { return nwg <= 256 ? 4 : (nwg <= 512 ? 2 : 1); }
 
 __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanArgs a) {
   extern __shared__ int lds[];
   __shared__ int scratch[3 * PLAN_THREADS / 64 + 2];
   __shared__ int wave_tot[PLAN_THREADS / 64];
   const Sched sc = sched_at(lds, a.B);
+  int* seg_cache = lds + sched_ints(a.B);
+  const int CS = plan_cached_segments(a.nwg);
   const int tid = threadIdx.x;
   const Shares sh = build_schedule(a, sc, scratch);
 
-  // ---- pass 1: how many segments each workgroup has (thread w: workgroup w)
+  // ---- pass 1: the segments of each workgroup (thread w: workgroup w); the first few are kept in LDS
   static_assert(PLAN_THREADS >= MAX_WG, "a thread per workgroup");
+  typedef int i32x4 __attribute__((ext_vector_type(4)));
   const int w = tid;
   int cnt = 0;
+  Walk resume;  // where the walk stood after the cached segments
   if (w < a.nwg) {
     Walk wk = walk_begin(sc, sh, w);
+    resume = wk;
     Item it;
     int p0, p1, owner, w_last;
-    while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1, &owner, &w_last)) ++cnt;
+    while (cnt < CS && walk_next(a, sc, sh, w, &wk, &it, &p0, &p1, &owner, &w_last)) {
+      int* c = seg_cache + (w * CS + cnt) * PLAN_SEG;
+      *(i32x4*)c = i32x4{it.s | (it.h << 16), it.q0, it.nq, p0};
+      *(i32x4*)(c + 4) = i32x4{p1, it.np, owner | (w_last << 16), sc.L[it.s]};
+      ++cnt;
+    }
+    resume = wk;
+    // the rest is only counted here (most of a step of the walk is then dead code)
+    if (cnt == CS)
+      while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1, &owner, &w_last)) ++cnt;
   }
   // exclusive scan, over the workgroups, of the segments beyond the first
   const int extra = max(cnt - 1, 0);
@@ -406,17 +458,16 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanArgs a) {
   int32_t* hdr = a.plan + PLAN_HDR * w;
   hdr[PLAN_HDR_NSEG] = cnt;
   hdr[PLAN_HDR_NEXT] = run;
-  Walk wk = walk_begin(sc, sh, w);
-  Item it;
-  int p0, p1, owner, w_last;
-  int i = 0;
-  while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1, &owner, &w_last)) {
+  const int cached = min(cnt, CS);
+  for (int i = 0; i < cached; ++i) {
+    const int* c = seg_cache + (w * CS + i) * PLAN_SEG;
+    const i32x4 lo = *(const i32x4*)c, hi = *(const i32x4*)(c + 4);
     int32_t* d = i == 0 ? hdr : seg_list + PLAN_SEG * (run + i - 1);
-    typedef int i32x4 __attribute__((ext_vector_type(4)));
-    *(i32x4*)d = i32x4{it.s | (it.h << 16), it.q0, it.nq, p0};
-    *(i32x4*)(d + 4) = i32x4{p1, it.np, owner | (w_last << 16), sc.L[it.s]};
+    *(i32x4*)d = lo;
+    *(i32x4*)(d + 4) = hi;
     if (i == 0) {
-      const int32_t* bt = a.block_tables + (long)it.s * a.max_blocks_per_seq;
+      const int p0 = lo[3], p1 = hi[0];
+      const int32_t* bt = a.block_tables + (long)(lo[0] & 0xffff) * a.max_blocks_per_seq;
       int ids[PLAN_IDS];
 #pragma unroll
       for (int k = 0; k < PLAN_IDS; ++k) ids[k] = bt[min(p0 + k, p1 - 1)];  // all on their way at once
@@ -426,7 +477,18 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanArgs a) {
             i32x4{min(max(ids[k], 0), a.num_blocks - 1), min(max(ids[k + 1], 0), a.num_blocks - 1),
                   min(max(ids[k + 2], 0), a.num_blocks - 1), min(max(ids[k + 3], 0), a.num_blocks - 1)};
     }
-    ++i;
+  }
+  if (cnt > CS) {
+    Walk wk = resume;
+    Item it;
+    int p0, p1, owner, w_last;
+    int i = CS;
+    while (walk_next(a, sc, sh, w, &wk, &it, &p0, &p1, &owner, &w_last)) {
+      int32_t* d = seg_list + PLAN_SEG * (run + i - 1);
+      *(i32x4*)d = i32x4{it.s | (it.h << 16), it.q0, it.nq, p0};
+      *(i32x4*)(d + 4) = i32x4{p1, it.np, owner | (w_last << 16), sc.L[it.s]};
+      ++i;
+    }
   }
 }
 
@@ -522,7 +584,7 @@ int aspd_plan_launch(const aspd_kv* kv, const AttnVariant& v, int32_t B, const i
   a.max_blocks_per_seq = kv->max_blocks_per_seq;
   a.num_blocks = kv->num_blocks;
   a.has_owner = v.has_owner ? 1 : 0;
-  const size_t lds = (size_t)(sched_ints(B)) * sizeof(int);
+  const size_t lds = (size_t)(sched_ints(B) + v.nwg * plan_cached_segments(v.nwg) * PLAN_SEG) * sizeof(int);
   hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), lds, stream, a);
   ASPD_HIP_CHECK(hipGetLastError());
   return ASPD_OK;
