@@ -54,7 +54,8 @@ WORKLOADS = {
                  what="config 5 (B=64, prefix 1024..8192, 2..10 branches of 8..128, paged 16): 16-token branch chunk, "
                       "parallel-decode step, merge, 4 serial-decode steps"),
     "cycle4": dict(index=4, chunk=16, serial=32, base_offset=-17,
-                   what="config 4's batch with a 16-token branch chunk before the decode step and 32 serial steps after"),
+                   what="config 4's batch (B=4, prefix 16384, 6 branches of 32..192): 16-token branch chunk, parallel-decode step, "
+                        "merge, 32 serial-decode steps"),
 }
 DEFAULT_SET = ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5")
 HEADLINE = "cfg5"
@@ -484,7 +485,7 @@ def main() -> int:
             "config": {"workload": f"{head_name}: {WORKLOADS[head_name]['what']}",
                        "value_is": "branch queries of one parallel-decode launch / its average duration (per_config."
                                    f"{head_name}.per_call.parallel)",
-                       "step_is": "the whole hot path on this batch: " + WORKLOADS[head_name]["what"].split(": ", 1)[1],
+                       "step_is": "the whole hot path on this batch: " + WORKLOADS[head_name]["what"].split(": ", 1)[-1],
                        "query_tokens_per_step": head["query_tokens_per_step"], "B": head["B"], "NB": head["NB"],
                        "kv_tokens": head["kv_tokens"], "kv_pools_rotated": head["kv_pools_rotated"],
                        "timed_region_s": round(head["timed_region_s"], 3)},
