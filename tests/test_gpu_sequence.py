@@ -422,3 +422,34 @@ def test_shared_mask_is_plain_causal_attention(A):
     ref_iso, _ = attend(tt, meta, q, wl.k_cache, wl.v_cache)
     assert np.abs(iso - ref_iso).max() <= TOL
     assert np.abs(iso - got).max() > 0.05
+
+
+def test_re_prefill_with_rotary_append_end_to_end(A):
+    """The three calls of a re-prefill in a row (Same-Re, Sec. 4.5.3): metadata of whole sequences, rotary encoding of
+    all their tokens by the position ids of Eq. 4 with the K and V rows written into the cache, attention over the
+    cache as written; against the oracle's chain of the same three steps in float64."""
+    from gpu_drive import GpuBatch
+    from oracle import rope_append
+    wl = W.random_small(seed=6200, batch=3, num_q_heads=16, num_kv_heads=8, head_dim=128, prefix_range=(100, 500),
+                        branches_range=(2, 5), branch_len_range=(10, 70))
+    layouts = W.random_layouts(wl, seed=6, fill=0.9)
+    tt, meta = replay_layout(wl.block_tables, wl.block_size, layouts)
+    gb = GpuBatch(wl)
+    step = _build(A, gb, layouts)
+    NQ = meta.NQ
+    g = torch.Generator().manual_seed(62)
+    q = (torch.randn(NQ, wl.num_q_heads, wl.head_dim, generator=g) * wl.sigma).to(torch.bfloat16)
+    k_new = (torch.randn(NQ, wl.num_kv_heads, wl.head_dim, generator=g) * wl.sigma).to(torch.bfloat16)
+    v_new = (torch.randn(NQ, wl.num_kv_heads, wl.head_dim, generator=g) * wl.sigma).to(torch.bfloat16)
+    k64 = gb.kv.k.double().cpu().numpy()
+    v64 = gb.kv.v.double().cpu().numpy()
+    q_dev = A.aspd_rope_append(gb.kv, step, q.to(gb.dev), k_new.to(gb.dev), v_new.to(gb.dev), 1e6)
+    q_ref = rope_append(q.double().numpy(), k_new.double().numpy(), v_new.double().numpy(), meta.position_ids,
+                        meta.slot_mapping, k64, v64, 1e6)
+    out = A.aspd_attn_full_sequence(gb.kv, gb.state, step, q_dev, gb.workspace)
+    torch.cuda.synchronize()
+    assert np.abs(q_dev.double().cpu().numpy() - q_ref).max() <= TOL
+    ref, _ = attend(tt, meta, torch.from_numpy(q_ref), torch.from_numpy(k64), torch.from_numpy(v64))
+    err = np.abs(out.double().cpu().numpy() - ref).max()
+    print(f"[re-prefill chain] rows={NQ} max|out-ref|={err:.3e}", flush=True)
+    assert err <= TOL
