@@ -1121,3 +1121,36 @@ def test_row_count_mismatch_raises_a_fault(A):
     torch.cuda.synchronize()
     if wl.NB > 1:
         assert gb.fault() & A.FAULT_ROW_COUNT
+
+
+def test_two_streams_two_workspaces(A):
+    """Two batches decoded at the same time on two streams (default priority), each call with its own workspace, as
+    the header allows; both against the oracle and against the same calls issued one after the other."""
+    wl1 = W.config(3, scale=0.2, batch=6)
+    wl2 = W.random_small(seed=777, batch=5, prefix_range=(500, 1500), branches_range=(2, 6), branch_len_range=(10, 60))
+    sides = []
+    for wl in (wl1, wl2):
+        gb, tt = _grow_both(A, wl, wl.branch_len - 1, False)
+        ones = np.ones(wl.NB, dtype=np.int32)
+        meta = tt.append_parallel(ones)
+        step = gb.parallel(ones)
+        q = wl.draw_q(meta.NQ)
+        ref, _ = attend(tt, meta, q, wl.k_cache, wl.v_cache)
+        sides.append((wl, gb, step, q.to(gb.dev), ref))
+    torch.cuda.synchronize()
+    serial = [A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace).clone() for _, gb, step, q, _ in sides]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [torch.empty_like(s) for s in serial]
+    for rep in range(6):
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for (wl, gb, step, q, _), st, o in zip(sides, streams, outs):
+            with torch.cuda.stream(st):
+                for _ in range(4):      # several launches each, so that the two streams do overlap
+                    A.aspd_attn_parallel_decode(gb.kv, gb.state, step, q, gb.workspace, out=o)
+        torch.cuda.synchronize()
+        for (wl, gb, step, q, ref), o, s in zip(sides, outs, serial):
+            assert np.abs(o.float().cpu().numpy() - ref).max() <= TOL[wl.dtype], rep
+            assert (o.float() - s.float()).abs().max().item() <= 4e-3, rep
