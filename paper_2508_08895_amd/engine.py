@@ -146,6 +146,34 @@ class HybridEngine:
         """(branch number, token) of sequence s in cache order: 0 = main branch, k = k-th branch of its stage."""
         return list(self.seqs[s].flat)
 
+    def layout(self, s: int):
+        """Sequence s as a whole-sequence layout in the training arrangement (Fig. 5: the branches of a stage laid
+        one after the other): (runs, tokens), runs = [(0, n) main-branch tokens | (k, n) the k-th branch of a
+        stage], tokens in that order.  What a re-prefill of the sequence takes (aspd_build_sequence_meta; the
+        Same-Re paradigm of Sec. 4.5.3 re-prefills after every stage).  A stage ends at the next main-branch
+        token, which the engine always appends after a merge."""
+        runs, tokens = [], []
+        stage = {}                    # branch number -> tokens, of the stage being collected
+
+        def close():
+            for k in sorted(stage):
+                runs.append((k, len(stage[k])))
+                tokens.extend(stage[k])
+            stage.clear()
+
+        for b, t in self.seqs[s].flat:
+            if b == 0:
+                close()
+                if runs and runs[-1][0] == 0:
+                    runs[-1] = (0, runs[-1][1] + 1)
+                else:
+                    runs.append((0, 1))
+                tokens.append(t)
+            else:
+                stage.setdefault(b, []).append(t)
+        close()
+        return runs, tokens
+
     # ------------------------------------------------------------------ one step
     def next_step(self) -> Optional[StepPlan]:
         """Metadata for the tokens that are due; None when every sequence has ended."""
@@ -298,3 +326,13 @@ class LibraryDriver:
 
     def merge(self, which):
         self.A.aspd_build_branch_meta(self.kv, self.state, self.A.STAGE_MERGE, self._dev(which))
+
+    def reprefill(self, layouts):
+        """Metadata of whole sequences given by their layouts (HybridEngine.layout): the step that
+        aspd_rope_append and aspd_attn_full_sequence take.  Rebuilds the state of every sequence from slot 0."""
+        cu = np.zeros(len(layouts) + 1, dtype=np.int32)
+        np.cumsum([len(r) for r in layouts], out=cu[1:])
+        br = [b for r in layouts for b, _ in r] or [0]
+        ln = [n for r in layouts for _, n in r] or [0]
+        nq = int(sum(n for r in layouts for _, n in r))
+        return self.A.aspd_build_sequence_meta(self.kv, self.state, self._dev(cu), self._dev(br), self._dev(ln), NQ=nq)

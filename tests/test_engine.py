@@ -101,6 +101,31 @@ def test_batch_switches_independently_and_runs_two_rounds():
     assert any(k == "aspd_attn_branch_chunk" for k, _ in kinds)
     # a step that served a serial sequence and branches of another at once went through the MIXED stage
     assert any(c[0] == "mixed" and sum(c[1]) > 0 and sum(c[2]) > 0 for c in drv.calls)
+    # The same sequences as whole-sequence layouts (what a re-prefill takes): the branches of a stage one after the
+    # other instead of interleaved.  Replayed through the oracle, every token gets the position it was decoded at
+    # and sees the same tokens (Eq. 2-4 do not depend on the arrangement).
+    from oracle.sequence_layout import replay_layout
+    layouts, toks = zip(*(eng.layout(s) for s in range(B)))
+    assert [r for r in layouts[0]] == [(0, len(eng.sequence(0)))]
+    assert [b for b, _ in layouts[1]] == [0, 1, 2, 0, 1, 2, 0]
+    assert [b for b, _ in layouts[2]] == [0, 1, 2, 3, 0]
+    t2, meta = replay_layout(np.arange(B * 16, dtype=np.int32).reshape(B, 16), 16, list(layouts))
+    for s in range(B):
+        flat = eng.sequence(s)
+        assert sorted(toks[s]) == sorted(t for _, t in flat) and sum(n for _, n in layouts[s]) == len(flat)
+        # match the tokens of the two arrangements by (stage, branch, index within the branch)
+        key_dec = {(tt.stage[s][j], tt.branch[s][j], tt.index_in_branch[s][j]): j for j in range(len(flat))}
+        key_re = {(t2.stage[s][j], t2.branch[s][j], t2.index_in_branch[s][j]): j for j in range(len(flat))}
+        assert key_dec.keys() == key_re.keys()
+        m_dec = tt.dense_mask(s, np.arange(len(flat)))
+        m_re = t2.dense_mask(s, np.arange(len(flat)))
+        for k, jd in key_dec.items():
+            jr = key_re[k]
+            assert flat[jd][1] == toks[s][jr]
+            assert tt.pos[s][jd] == t2.pos[s][jr]
+            seen_dec = {kk for kk, j in key_dec.items() if m_dec[jd, j]}
+            seen_re = {kk for kk, j in key_re.items() if m_re[jr, j]}
+            assert seen_dec == seen_re, (s, k)
 
 
 def test_token_budget_closes_branches_and_ends_the_sequence():

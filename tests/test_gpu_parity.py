@@ -853,6 +853,18 @@ def test_engine_drives_the_library_like_the_oracle(A):
         plan = eng.next_step()
         steps += 1
     assert eng.finished() and [s.stages for s in eng.seqs] == [0, 2, 1]
+    # Re-prefill (the Same-Re reading of Sec. 4.5.3): the sequences the engine produced, laid out whole in the
+    # training arrangement and rebuilt from slot 0 in one metadata call and one attention launch; against the
+    # oracle's replay of the same layouts.
+    from oracle.sequence_layout import replay_layout
+    layouts = [eng.layout(s)[0] for s in range(wl.B)]
+    t2, meta2 = replay_layout(wl.block_tables, wl.block_size, layouts)
+    step2 = lib.reprefill(layouts)
+    torch.cuda.synchronize()
+    for f in ("cu_seq_new", "q_seq", "position_ids", "logical_slot", "slot_mapping", "kv_len"):
+        got = getattr(step2, f).cpu().numpy()
+        assert np.array_equal(got if f == "cu_seq_new" else got[:meta2.NQ], getattr(meta2, f)), f
+    _compare_attention(A, gb, t2, wl, step2, meta2, A.aspd_attn_full_sequence, label="engine re-prefill", check_step=False)
 
 
 def test_repeat_calls_agree(A):
