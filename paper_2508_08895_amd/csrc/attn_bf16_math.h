@@ -114,12 +114,20 @@ struct RowState {
 // quiet a possible signalling NaN in every operand first (one more instruction each: 11 instead of 4
 // per tile of every pair); scores are MFMA results or -inf and never NaN here, and the three-operand
 // maximum returns a number whenever one operand is a number.
+// The operands are usually MFMA results, and a vector instruction that reads one too soon after the MFMA
+// was issued gets the old register contents: the hardware does not interlock, the compiler pads with
+// wait states for the instructions it emits itself, and it does not look into assembly.  So the block
+// brings its own wait states (16: more than the 8-pass MFMA used here needs) and is ONE statement, so
+// that no MFMA can be scheduled between them and the reads.
 __device__ __forceinline__ float max8(const float (&x)[8]) {
-  float r1, r2, r3, m;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r1) : "v"(x[0]), "v"(x[1]), "v"(x[2]));
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r2) : "v"(x[3]), "v"(x[4]), "v"(x[5]));
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r3) : "v"(x[6]), "v"(x[7]), "v"(r1));
-  asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(r2), "v"(r3));
+  float r1, r2, m;
+  asm("s_nop 15\n\t"
+      "v_max3_f32 %0, %3, %4, %5\n\t"
+      "v_max3_f32 %1, %6, %7, %8\n\t"
+      "v_max3_f32 %2, %9, %10, %0\n\t"
+      "v_max_f32 %2, %1, %2"
+      : "=&v"(r1), "=&v"(r2), "=&v"(m)
+      : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]), "v"(x[4]), "v"(x[5]), "v"(x[6]), "v"(x[7]));
   return m;
 }
 
@@ -255,6 +263,112 @@ __device__ __forceinline__ void pair_compute(const u32x4* stage, const u32x4* qt
       }
     }
 #undef ASPD_V_UNIT
+}
+
+// ---------------------------------------------------------------------------------------------
+// A staged group of PPS pairs of pages that every row of the wave sees in full (keys of the prefix and of
+// earlier stages: most of a long context).  No mask, no owner tags, and straight-line code but for one rarely
+// taken branch per group: all score products first, then one test whether any row's softmax reference must
+// be raised (the lazy reference of pair_compute, against the largest score of the whole group), then the
+// weights and second products of all pairs.  Counters on the general path show the row-splitting kernel
+// bound by the number of instructions a wave issues per pair (about 240, of which 32 MFMA), not by a
+// pipeline: this form issues about a third fewer.
+// ---------------------------------------------------------------------------------------------
+template <int D, int NT, int PPS>
+__device__ __forceinline__ void group_compute_open(const u32x4* stage, RowState<D, NT>& ts, int kr_even, int kr_odd,
+                                                   const int (&vu)[4], float scale_log2, const bf16x8* qr) {
+  using C = Bf16Cfg<D>;
+  constexpr int KB = 2;
+  f32x4 st[PPS][2][NT];
+#pragma unroll
+  for (int h = 0; h < PPS; ++h) {
+    const u32x4* sp = stage + h * 4 * C::LPAGE_U4;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) st[h][0][n] = st[h][1][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t0 = 0; t0 < C::KSTEPS; t0 += KB) {
+      bf16x8 ka[KB], kb[KB];
+#pragma unroll
+      for (int tt = 0; tt < KB; ++tt) {
+        const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
+        ka[tt] = *(const bf16x8*)&sp[0 * C::LPAGE_U4 + kr];
+        kb[tt] = *(const bf16x8*)&sp[1 * C::LPAGE_U4 + kr];
+      }
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+#pragma unroll
+        for (int tt = 0; tt < KB; ++tt) {
+          st[h][0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[tt], qr[n * C::KSTEPS + t0 + tt], st[h][0][n], 0, 0, 0);
+          st[h][1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[tt], qr[n * C::KSTEPS + t0 + tt], st[h][1][n], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // ---- the rows' references against the largest score of the group
+  float mx[NT];
+  bool up = false;
+#pragma unroll
+  for (int n = 0; n < NT; ++n) {
+#pragma unroll
+    for (int h = 0; h < PPS; ++h) {
+      float sc[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sc[e] = st[h][0][n][e];
+        sc[4 + e] = st[h][1][n][e];
+      }
+      const float m8 = max8(sc);
+      mx[n] = (h == 0) ? m8 : fmaxf(mx[n], m8);
+    }
+    mx[n] *= scale_log2;  // scale > 0: the maximum commutes with it
+    up |= mx[n] > ts.m_run[n] + LAZY;
+  }
+  if (__any(up)) {
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+      float m = mx[n];
+      m = fmaxf(m, __shfl_xor(m, 16));
+      m = fmaxf(m, __shfl_xor(m, 32));
+      const float m_new = fmaxf(ts.m_run[n], m);
+      const float alpha = __builtin_amdgcn_exp2f(ts.m_run[n] - exp2_safe_ref(m_new));
+      ts.m_run[n] = m_new;
+      ts.l_run[n] *= alpha;
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) ts.acc[n][mt] *= alpha;
+    }
+  }
+  // ---- weights and second products
+#pragma unroll
+  for (int h = 0; h < PPS; ++h) {
+    const u32x4* sp = stage + h * 4 * C::LPAGE_U4;
+    const s16x4* vs0 = (const s16x4*)(sp + 2 * C::LPAGE_U4);
+    const s16x4* vs1 = (const s16x4*)(sp + 3 * C::LPAGE_U4);
+    bf16x8 p[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+      const float neg_ref = -exp2_safe_ref(ts.m_run[n]);
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float w = __builtin_amdgcn_exp2f(fmaf(st[h][e >> 2][n][e & 3], scale_log2, neg_ref));
+        psum += w;
+        p[n][e] = (__bf16)w;
+      }
+      ts.l_run[n] += psum;
+    }
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt) {
+      const int unit = vu[mt & 3] + 16 * (mt >> 2);
+      const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs0 + unit));
+      const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs1 + unit));
+      s16x8 v8;
+      v8[0] = va[0]; v8[1] = va[1]; v8[2] = va[2]; v8[3] = va[3];
+      v8[4] = vb[0]; v8[5] = vb[1]; v8[6] = vb[2]; v8[7] = vb[3];
+      const bf16x8 vop = __builtin_bit_cast(bf16x8, v8);
+#pragma unroll
+      for (int n = 0; n < NT; ++n) ts.acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p[n], ts.acc[n][mt], 0, 0, 0);
+    }
+  }
 }
 
 }  // namespace

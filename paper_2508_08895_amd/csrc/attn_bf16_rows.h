@@ -145,8 +145,7 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
     lpos[k] = lds_pos<D>(row, ch);
   }
 
-  constexpr int RD = ROWS_PREFETCH;  // groups on their way per workgroup (a ring of register sets)
-  u32x4 nxt[RD][LPT];
+  u32x4 nxt[LPT];  // this thread's slice of the group on its way
   for (int wbase = page0; wbase < page1; wbase += BLK_WIN) {  // windows of block ids; normally one
     const int wend = min(page1, wbase + BLK_WIN);
     const int wpages = wend - wbase;
@@ -159,20 +158,18 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
         blk_lds[tid + k * THREADS] = min(max(bt[min(wbase + tid + k * THREADS, page1 - 1)], 0), a.kv.num_blocks - 1);
       __syncthreads();
     }
-    // This thread's slice of group gi.  Issued for every ring slot, also past the end of the window (the
-    // last pages again, which the caches hold): the number of loads younger than a slot is then fixed,
-    // so waiting for the oldest slot leaves the younger ones in flight.
-    // the page (of the window) this thread loads for group gi
+    // the page (of the window) this thread loads for group gi; past the end of the window the last pages
+    // again, which the caches hold
     auto page_of = [&](int gi) -> int {
       const int p = min(gi * PPS + (lpage >> 2), npairs - 1);
       return min(2 * p + (lpage & 1), wpages - 1);
     };
-    auto issue = [&](u32x4 (&dst)[LPT], int gi) {
+    auto issue = [&](int gi) {
       const int pg = page_of(gi);
       const int b = blk_lds[pg];
       const u32x4* src = (const u32x4*)(l_is_k ? a.kv.k : a.kv.v) + ((long)b * a.kv.num_kv_heads + it.h) * C::PAGE_U4;
 #pragma unroll
-      for (int k = 0; k < LPT; ++k) dst[k] = src[lt + k * PER_PAGE];
+      for (int k = 0; k < LPT; ++k) nxt[k] = src[lt + k * PER_PAGE];
     };
     // owner tags of the pairs that reach into the branch region, fetched one group ahead like the pages
     auto tags_of = [&](int gi, u32x4 (&t)[PPS][2]) {
@@ -185,33 +182,44 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
         }
       }
     };
+    issue(0);
+
+    // ---- the leading groups of the window that every row of this wave sees in full (whole pairs below
+    // mask_from): nothing to mask, no tags, nothing to clear (they end below the last row's slot).  The
+    // count differs between the waves of a workgroup; every group costs one barrier in either loop, and
+    // what a wave stages for a group does not depend on the loop it is in.
+    const int g_open = max(0, min(ngroups, (min(wend, mask_from / ASPD_BLOCK) - wbase) / (2 * PPS)));
+    for (int gi = 0; gi < g_open; ++gi) {
+      u32x4* stage = stage0 + (gi & 1) * (PPS * C::STAGE_BYTES / 16);
+#pragma unroll
+      for (int k = 0; k < LPT; ++k) stage[lpage * C::LPAGE_U4 + lpos[k]] = nxt[k];
+      issue(gi + 1);
+      __syncthreads();  // the group is staged; everyone is done with the other buffer's previous group
+      if (wave_active) group_compute_open<D, NT, PPS>(stage, ts, kr_even, kr_odd, vu, a.scale_log2, qr);
+    }
+
+    // ---- the rest of the window: pairs that may need the mask, the tags, the tail
     u32x4 tn[PPS][2];
 #pragma unroll
     for (int h = 0; h < PPS; ++h) tn[h][0] = tn[h][1] = u32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int d = 0; d < RD; ++d) issue(nxt[d], d);
-    tags_of(0, tn);
-    for (int gbase = 0; gbase < ngroups; gbase += RD) {
-#pragma unroll
-    for (int d = 0; d < RD; ++d) {  // the ring is unrolled so that every slot has fixed registers
-      const int gi = gbase + d;
-      if (gi >= ngroups) break;
+    if (g_open < ngroups) tags_of(g_open, tn);
+    for (int gi = g_open; gi < ngroups; ++gi) {
       u32x4* stage = stage0 + (gi & 1) * (PPS * C::STAGE_BYTES / 16);
       const int key0 = (wbase + page_of(gi)) * ASPD_BLOCK;  // first slot of the page this thread staged
       if (!l_is_k && key0 + ASPD_BLOCK > last_slot + 1) {
 #pragma unroll
         for (int k = 0; k < LPT; ++k)
-          if (key0 + (lt + k * PER_PAGE) / C::CH > last_slot) nxt[d][k] = u32x4{0u, 0u, 0u, 0u};
+          if (key0 + (lt + k * PER_PAGE) / C::CH > last_slot) nxt[k] = u32x4{0u, 0u, 0u, 0u};
       }
 #pragma unroll
-      for (int k = 0; k < LPT; ++k) stage[lpage * C::LPAGE_U4 + lpos[k]] = nxt[d][k];
+      for (int k = 0; k < LPT; ++k) stage[lpage * C::LPAGE_U4 + lpos[k]] = nxt[k];
       u32x4 tc[PPS][2];
 #pragma unroll
       for (int h = 0; h < PPS; ++h) {
         tc[h][0] = tn[h][0];
         tc[h][1] = tn[h][1];
       }
-      issue(nxt[d], gi + RD);
+      issue(gi + 1);
       if (gi + 1 < ngroups) tags_of(gi + 1, tn);
       __syncthreads();  // the group is staged; everyone is done with the other buffer's previous group
 
@@ -244,7 +252,6 @@ __device__ void segment_rows(const AttnArgs& a, char* smem, const Seg& it, bool 
         pair_compute<D, NT, KB, VB, true, true>(stage + h * 4 * C::LPAGE_U4, nullptr, ts, kr_even, kr_odd, vu, g, 0,
                                                 mask_from, P0, second_valid, own0, own1, a.scale_log2, qr);
       }
-    }
     }
   }
 

@@ -15,7 +15,6 @@ constexpr int THREADS = NW * 64;
 constexpr int STREAM_NW = 4;
 constexpr int STREAM_PF = 1;
 constexpr int BF16_ROWS = 16 * NT_MAX;
-constexpr int ROWS_PREFETCH = 1;      // groups of pages the row-splitting kernel keeps on their way per workgroup
 constexpr int ROWS_PPS = 2;           // pairs of pages it stages (and computes) between two barriers
 constexpr int COUNTER_BYTES = 4096;   // MAX_WG arrival counters at the head of the workspace
 static_assert(COUNTER_BYTES == MAX_WG * 4, "workspace head");
@@ -141,9 +140,11 @@ __device__ __forceinline__ float load_device_scope(const float* p) {
 // write each).  Callers order it like the 4-byte form: a later s_waitcnt vmcnt(0) covers it.
 // A store of more than 8 bytes reads its data registers a little after it issues, and the compiler, which
 // does not look inside inline assembly, may let the very next instruction overwrite them: the s_nop keeps
-// the wait states the compiler would have inserted for a store of its own.
+// the wait states the compiler would have inserted for a store of its own.  The data are usually MFMA
+// results, which a memory instruction must not read too soon after the MFMA was issued either (no hardware
+// interlock, and again the compiler's padding does not cover assembly): hence the wait states in front.
 __device__ __forceinline__ void store_device_scope_x4(float* p, f32x4 v) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
+  asm volatile("s_nop 15\n\tglobal_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(v) : "memory");
 }
 
 
