@@ -278,32 +278,52 @@ template <int D, int NT, int PPS>
 __device__ __forceinline__ void group_compute_open(const u32x4* stage, RowState<D, NT>& ts, int kr_even, int kr_odd,
                                                    const int (&vu)[4], float scale_log2, const bf16x8* qr) {
   using C = Bf16Cfg<D>;
-  constexpr int KB = 2;
+  // LDS operands are fetched a whole pair at a time and one step ahead of their use (the K pages of the next
+  // pair before the score products of this one, the V pages of a pair before its weights are computed), so
+  // that a wave waits for LDS once per phase and not once per MFMA.
+  auto fetch_k = [&](const u32x4* sp, bf16x8 (&k)[2][C::KSTEPS]) {
+#pragma unroll
+    for (int t = 0; t < C::KSTEPS; ++t) {
+      const int kr = ((t & 1) ? kr_odd : kr_even) + 8 * (t >> 1);
+      k[0][t] = *(const bf16x8*)&sp[0 * C::LPAGE_U4 + kr];
+      k[1][t] = *(const bf16x8*)&sp[1 * C::LPAGE_U4 + kr];
+    }
+  };
+  auto fetch_v = [&](const u32x4* sp, bf16x8 (&v)[C::MT]) {
+    const s16x4* vs0 = (const s16x4*)(sp + 2 * C::LPAGE_U4);
+    const s16x4* vs1 = (const s16x4*)(sp + 3 * C::LPAGE_U4);
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt) {
+      const int unit = vu[mt & 3] + 16 * (mt >> 2);
+      const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs0 + unit));
+      const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs1 + unit));
+      s16x8 v8;
+      v8[0] = va[0]; v8[1] = va[1]; v8[2] = va[2]; v8[3] = va[3];
+      v8[4] = vb[0]; v8[5] = vb[1]; v8[6] = vb[2]; v8[7] = vb[3];
+      v[mt] = __builtin_bit_cast(bf16x8, v8);
+    }
+  };
   f32x4 st[PPS][2][NT];
+  {
+    bf16x8 kop[2][2][C::KSTEPS];
+    fetch_k(stage, kop[0]);
 #pragma unroll
-  for (int h = 0; h < PPS; ++h) {
-    const u32x4* sp = stage + h * 4 * C::LPAGE_U4;
+    for (int h = 0; h < PPS; ++h) {
+      if (h + 1 < PPS) fetch_k(stage + (h + 1) * 4 * C::LPAGE_U4, kop[(h + 1) & 1]);
 #pragma unroll
-    for (int n = 0; n < NT; ++n) st[h][0][n] = st[h][1][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int n = 0; n < NT; ++n) st[h][0][n] = st[h][1][n] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int t0 = 0; t0 < C::KSTEPS; t0 += KB) {
-      bf16x8 ka[KB], kb[KB];
+      for (int t = 0; t < C::KSTEPS; ++t) {
 #pragma unroll
-      for (int tt = 0; tt < KB; ++tt) {
-        const int kr = (((t0 + tt) & 1) ? kr_odd : kr_even) + 8 * ((t0 + tt) >> 1);
-        ka[tt] = *(const bf16x8*)&sp[0 * C::LPAGE_U4 + kr];
-        kb[tt] = *(const bf16x8*)&sp[1 * C::LPAGE_U4 + kr];
-      }
-#pragma unroll
-      for (int n = 0; n < NT; ++n) {
-#pragma unroll
-        for (int tt = 0; tt < KB; ++tt) {
-          st[h][0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[tt], qr[n * C::KSTEPS + t0 + tt], st[h][0][n], 0, 0, 0);
-          st[h][1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[tt], qr[n * C::KSTEPS + t0 + tt], st[h][1][n], 0, 0, 0);
+        for (int n = 0; n < NT; ++n) {
+          st[h][0][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[h & 1][0][t], qr[n * C::KSTEPS + t], st[h][0][n], 0, 0, 0);
+          st[h][1][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[h & 1][1][t], qr[n * C::KSTEPS + t], st[h][1][n], 0, 0, 0);
         }
       }
     }
   }
+  bf16x8 vop[C::MT];
+  fetch_v(stage, vop);
   // ---- the rows' references against the largest score of the group
   float mx[NT];
   bool up = false;
@@ -340,9 +360,6 @@ __device__ __forceinline__ void group_compute_open(const u32x4* stage, RowState<
   // ---- weights and second products
 #pragma unroll
   for (int h = 0; h < PPS; ++h) {
-    const u32x4* sp = stage + h * 4 * C::LPAGE_U4;
-    const s16x4* vs0 = (const s16x4*)(sp + 2 * C::LPAGE_U4);
-    const s16x4* vs1 = (const s16x4*)(sp + 3 * C::LPAGE_U4);
     bf16x8 p[NT];
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
@@ -358,16 +375,10 @@ __device__ __forceinline__ void group_compute_open(const u32x4* stage, RowState<
     }
 #pragma unroll
     for (int mt = 0; mt < C::MT; ++mt) {
-      const int unit = vu[mt & 3] + 16 * (mt >> 2);
-      const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs0 + unit));
-      const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(vs1 + unit));
-      s16x8 v8;
-      v8[0] = va[0]; v8[1] = va[1]; v8[2] = va[2]; v8[3] = va[3];
-      v8[4] = vb[0]; v8[5] = vb[1]; v8[6] = vb[2]; v8[7] = vb[3];
-      const bf16x8 vop = __builtin_bit_cast(bf16x8, v8);
 #pragma unroll
-      for (int n = 0; n < NT; ++n) ts.acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop, p[n], ts.acc[n][mt], 0, 0, 0);
+      for (int n = 0; n < NT; ++n) ts.acc[n][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[mt], p[n], ts.acc[n][mt], 0, 0, 0);
     }
+    if (h + 1 < PPS) fetch_v(stage + (h + 1) * 4 * C::LPAGE_U4, vop);
   }
 }
 
