@@ -16,7 +16,9 @@ namespace {
 // waves share the loads rather than the keys.  Measured: 8 waves of 32 rows beat 8 of 48 (whose Q
 // operands no longer fit in registers) and 4 of 64 (one wave per SIMD overlaps nothing).
 // A wave skips the arithmetic for pairs that none of its rows can see (the chunks and earlier
-// tokens of other branches).
+// tokens of other branches).  The groups of a window that lie wholly below everything a wave's rows must
+// mask (the prefix, earlier stages) are taken first, in a loop of their own without tags, masks or
+// per-pair tests: the kernel's time follows the number of instructions a wave issues per pair.
 // ---------------------------------------------------------------------------------------------
 template <int D, int NT, int NW>
 size_t rows_smem_bytes() {

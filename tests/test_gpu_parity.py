@@ -145,6 +145,23 @@ def test_config5_chunk_then_decode(A, scale, batch, hinted):
                        label=f"cfg5 decode scale={scale}")
 
 
+def test_chunk_launch_twice_gives_the_same_bits(A):
+    """The row-splitting kernel fixes the order of every sum (each wave owns its rows, partial results are
+    merged in the order of their key ranges), so two launches on the same inputs must agree bit for bit.
+    A vector instruction that reads an MFMA result before the matrix unit has written it shows up here and,
+    being within tolerance, nowhere else."""
+    wl = W.config(5, scale=0.25, batch=16)
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    chunk = np.full(wl.NB, 16, dtype=np.int32)
+    meta = tt.append_parallel(chunk)
+    step = gb.parallel(chunk)
+    q = wl.draw_q(meta.NQ).to(gb.dev)
+    outs = [A.aspd_attn_branch_chunk(gb.kv, gb.state, step, q, gb.workspace).clone() for _ in range(4)]
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+
+
 # --------------------------------------------------------------------------------------------- mixed batches
 @pytest.mark.parametrize("seed,dtype", [(21, "bf16"), (22, "f32")])
 def test_mixed_batch_stages_switch_independently(A, seed, dtype):
