@@ -164,3 +164,35 @@ def test_rope_append_and_renumber_reject_bad_arguments_before_launch():
     assert renumber(new_len=0x40) == A.ERR_INVALID_ARG
     assert renumber(st_over=dict(B=0)) == A.ERR_INVALID_ARG
     assert renumber(st_over=dict(cu_branches_d=None)) == A.ERR_INVALID_ARG
+
+
+def test_assembly_that_may_read_mfma_results_brings_its_wait_states():
+    """The matrix unit does not interlock with a vector or memory instruction that reads an MFMA result too
+    soon, and the compiler pads only the instructions it emits itself.  Every inline-assembly statement of the
+    kernels that contains a vector or memory instruction with register inputs must therefore start with its own
+    wait states (`s_nop 15`), so that it is safe wherever the scheduler puts it."""
+    import glob, os, re
+    here = os.path.dirname(os.path.abspath(__file__))
+    files = sorted(glob.glob(os.path.join(here, "..", "paper_2508_08895_amd", "csrc", "*.h")) +
+                   glob.glob(os.path.join(here, "..", "paper_2508_08895_amd", "csrc", "*.hip")))
+    assert files
+    seen = 0
+    for f in files:
+        src = open(f).read()
+        for m in re.finditer(r"\basm\s*(?:volatile)?\s*\(", src):
+            # the statement up to its closing parenthesis + semicolon
+            depth, i = 0, m.end() - 1
+            while True:
+                depth += src[i] == "("
+                depth -= src[i] == ")"
+                i += 1
+                if depth == 0:
+                    break
+            stmt = src[m.start():i]
+            text = "".join(re.findall(r'"((?:[^"\\]|\\.)*)"', stmt.split(":")[0]))
+            text = text.replace("\\n", " ").replace("\\t", " ")
+            if not re.search(r"\b(v_[a-z0-9_]+|global_store_[a-z0-9]+|ds_write_[a-z0-9]+)\b", text):
+                continue
+            seen += 1
+            assert text.lstrip().startswith("s_nop 15"), (os.path.basename(f), text[:60])
+    assert seen >= 2   # the three-operand maximum and the write-through store
