@@ -162,6 +162,34 @@ def test_chunk_launch_twice_gives_the_same_bits(A):
         assert torch.equal(o, outs[0])
 
 
+LEAN = [dict(seed=901, head_dim=128, num_q_heads=32, num_kv_heads=8, prefix_range=(300, 900), chunk=16),
+        dict(seed=902, head_dim=64, num_q_heads=8, num_kv_heads=2, prefix_range=(130, 700), chunk=24),
+        dict(seed=903, head_dim=128, num_q_heads=4, num_kv_heads=4, prefix_range=(64, 400), chunk=40),
+        dict(seed=904, head_dim=64, num_q_heads=16, num_kv_heads=1, prefix_range=(200, 600), chunk=7),
+        dict(seed=905, head_dim=128, num_q_heads=8, num_kv_heads=1, prefix_range=(63, 65), chunk=33),
+        dict(seed=906, head_dim=128, num_q_heads=32, num_kv_heads=8, prefix_range=(1000, 2200), chunk=3)]
+
+
+@pytest.mark.parametrize("kw", LEAN, ids=lambda k: f"seed{k['seed']}")
+def test_chunk_with_a_prefix_of_several_groups(A, kw):
+    """Branch chunks behind prefixes of 4 to 140 pages, both head sizes, several row-group fillings (one wave to
+    all eight, more than one row group): the leading page groups go through the row-splitting kernel's loop
+    for fully visible groups, the branch region and the tail through the general one, and the boundary between
+    the two falls at a different place for every wave."""
+    kw = dict(kw)
+    chunk_len = kw.pop("chunk")
+    wl = W.random_small(batch=3, branches_range=(2, 6), branch_len_range=(1, 30), extra_tokens_per_branch=chunk_len + 4, **kw)
+    gb, tt = _grow_both(A, wl, wl.branch_len, False)
+    chunk = np.full(wl.NB, chunk_len, dtype=np.int32)
+    meta = tt.append_parallel(chunk)
+    step = gb.parallel(chunk)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_branch_chunk, label=f"lean {kw['seed']}")
+    ones = np.ones(wl.NB, dtype=np.int32)
+    meta = tt.append_parallel(ones)
+    step = gb.parallel(ones)
+    _compare_attention(A, gb, tt, wl, step, meta, A.aspd_attn_parallel_decode, label=f"lean {kw['seed']} decode")
+
+
 # --------------------------------------------------------------------------------------------- mixed batches
 @pytest.mark.parametrize("seed,dtype", [(21, "bf16"), (22, "f32")])
 def test_mixed_batch_stages_switch_independently(A, seed, dtype):
